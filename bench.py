@@ -1,0 +1,141 @@
+"""Benchmark of the collapsed Taylor-mode hot path on one MI355X.
+
+One step = one operator call over the whole batch: seed the coefficient block, the stacked
+GEMM + jet rule of every hidden layer, and the last layer.  Inputs are resident in HBM before
+the timed region.  Prints one JSON line (see the design doc for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "Laplacian evals/sec (50-D 768-768-512-512 tanh MLP, N=4096); % MFMA peak"
+PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}  # MI355X dense MFMA peaks
+
+
+def gemm_flops(dims, N, rho):
+    """Algorithmic flops of the stacked GEMMs of one call: 2 * (N*rho) * d_in * d_out per hidden layer
+    (un-padded widths, collapsed row count); the width-1 last layer is not a GEMM."""
+    return sum(2.0 * N * rho * dims[l] * dims[l + 1] for l in range(len(dims) - 2))
+
+
+def cpu_baseline(w, arrs, budget_s):
+    """The oracle as it stands (full Hessian per point, then the trace or contraction / 4th directional
+    derivatives), timed on the host cores for a bounded sample of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+
+    from oracle import operators as orc
+
+    def run(P):
+        sub = dict(arrs, x=arrs["x"][:P])
+        V = arrs.get("V")
+        if V is not None and V.ndim == 3:
+            sub["V"] = V[:P]
+        t0 = time.perf_counter()
+        if w.op == "laplacian":
+            orc.laplacian(sub["Ws"], sub["bs"], sub["x"], sub.get("V"), sub.get("scale", 1.0), mode="hessian")
+        elif w.op == "weighted_laplacian":
+            orc.weighted_laplacian(sub["Ws"], sub["bs"], sub["x"], sub["sigma"], mode="hessian")
+        else:
+            orc.biharmonic_rand(sub["Ws"], sub["bs"], sub["x"], sub["V"])
+        return time.perf_counter() - t0
+
+    p0 = min(8, w.N)
+    t_probe = run(p0)
+    P = int(max(p0, min(w.N, budget_s / max(t_probe / p0, 1e-9))))
+    t = run(P)
+    info = threadpool_info()
+    cores = max([i.get("num_threads", 1) for i in info] or [1])
+    return {"value": P / t, "unit": "evals/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {P} of {w.N} points of {w.name}, fp64 numpy nested-dual oracle "
+                      f"({'full Hessian per point' if w.op != 'biharmonic_rand' else '4-level duals per direction'}), {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", help="c1..c5 (c2 is the configuration the metric is quoted on)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 skips it")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (points are independent, nothing is exchanged); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2505_13644_amd as ctm
+    from paper_2505_13644_amd import synth
+
+    w = synth.WORKLOADS[args.workload]
+    arrs = w.build()
+    dev = torch.device("cuda:0")
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    x, V, sigma = t(arrs["x"]), t(arrs.get("V")), t(arrs.get("sigma"))
+    K = 4 if w.op == "biharmonic_rand" else 2
+    R = w.dims[0] if w.directions == "basis" else w.R
+    u = torch.empty(w.N, dtype=x.dtype, device=dev)
+    op = torch.empty(w.N, dtype=x.dtype, device=dev)
+    ws = torch.empty(ctm.ctm_workspace_bytes(mlp, K, w.N, R), dtype=torch.uint8, device=dev)
+
+    def step():
+        if w.op == "laplacian":
+            ctm.ctm_laplacian(mlp, x, V, arrs.get("scale", 1.0), u, op, ws)
+        elif w.op == "weighted_laplacian":
+            ctm.ctm_weighted_laplacian(mlp, x, sigma, u, op, ws)
+        else:
+            ctm.ctm_biharmonic_rand(mlp, x, V, u, op, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # per-kernel durations, measured live with HIP events on the launch stream (a second pass,
+    # so the events do not sit inside the timed region above)
+    ctm.ctm_profile_begin()
+    for _ in range(args.steps):
+        step()
+    ms, launches = ctm.ctm_profile_end()
+    rho = ctm.ctm_rows_per_point(K, R)
+    flops = gemm_flops(w.dims, w.N, rho)
+    layer_ms_per_step = ms["layer"] / args.steps
+    dt = "f64" if w.dtype == np.float64 else "f32"
+    achieved = flops / (layer_ms_per_step * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
+        "frac": achieved / PEAK_TFLOPS[dt], "traffic": None,
+        "kernel": "layer_kernel (stacked GEMM + fused jet rule)",
+        "flops_per_step": flops, "launches_per_step": launches["layer"] / args.steps,
+        "avg_launch_ms": ms["layer"] / max(1, launches["layer"]),
+        "stage_ms_per_step": {k: v / args.steps for k, v in ms.items()},
+    }
+    out = {
+        "metric": METRIC, "value": w.N / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.op}, tanh MLP {'-'.join(map(str, w.dims))}, N={w.N}, "
+                               f"{w.directions} directions R={R}, collapsed order-{K} Taylor mode, {rho} rows/point"},
+        "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(w, arrs, args.cpu_seconds)
+    mlp.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,160 @@
+/*
+ * ctm -- collapsed Taylor-mode PDE operators of a tanh MLP on one MI355X (gfx950).
+ *
+ * One call pushes a batch of points x[N,D], R first-order directional Taylor
+ * coefficients per point and ONE summed highest-order coefficient through the
+ * network and returns u[n] = f(x_n) together with
+ *
+ *     op[n] = scale * sum_{r=1..R} < d^K f(x_n), v_r^{(x)K} >        (Sec. 3.1, Eq. 5)
+ *
+ * for K = 2 (Laplacians, Sec. 3.2) or K = 4 (randomized biharmonic, Sec. 3.3).
+ * The sum over r is taken inside the propagation ("collapsed", Sec. 3.1, Eq. 6):
+ * every layer carries 1 + (K-1)R + 1 coefficient rows per point instead of 1 + K*R.
+ *
+ * The network is  f(x) = W_L act( ... act(W_1 x + b_1) ... ) + b_L  with a scalar
+ * output (d_L = 1), the activation after every layer but the last, and biases that
+ * enter the 0-th coefficient only (App. H).  Coefficients are derivative-normalised
+ * (Sec. 2: x(t) = sum_k t^k/k! x_k), so op is the K-th coefficient itself.
+ *
+ * Conventions
+ *   - "dev" pointers are device memory of the GPU that is current when the call is
+ *     made; "host" pointers are ordinary host memory.  All matrices are dense,
+ *     row-major, with no padding; element type is the handle's storage type
+ *     (double for CTM_F64, float for CTM_F32).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue work on it and return; results are valid once the stream has
+ *     reached that point.  No call synchronises the device except ctm_destroy_mlp.
+ *   - Ownership: ctm_create_mlp copies (and re-packs) the weights, so the caller may
+ *     free its own copies once `stream` has passed the call.  x, V, sigma, u, op and
+ *     the workspace stay the caller's; the library allocates nothing in the
+ *     operator calls.
+ *   - Every function returns CTM_OK (0) or a negative ctm_status; it never throws or
+ *     aborts.  Arguments are validated on the host before any GPU work is issued, and
+ *     ctm_last_error() gives a readable message for the calling thread's last failure.
+ *   - A handle is immutable: concurrent operator calls on one handle are fine as long
+ *     as they use distinct workspaces.
+ */
+#ifndef CTM_H
+#define CTM_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ctm_mlp ctm_mlp; /* opaque */
+
+typedef enum {
+  CTM_F64 = 0, /* fp64 storage, fp64 MFMA accumulate                       */
+  CTM_F32 = 1  /* fp32 storage, fp32 MFMA accumulate (the benchmarked path) */
+} ctm_dtype;
+
+typedef enum {
+  CTM_ACT_TANH = 0,
+  CTM_ACT_IDENTITY = 1 /* linear network: every operator is exactly 0 (a test hook) */
+} ctm_act;
+
+typedef enum {
+  CTM_OK = 0,
+  CTM_ERR_NULL = -1,        /* a required pointer is NULL                           */
+  CTM_ERR_SHAPE = -2,       /* a size or stride is out of range or inconsistent     */
+  CTM_ERR_DTYPE = -3,       /* unknown dtype / activation enum value                */
+  CTM_ERR_UNSUPPORTED = -4, /* valid request this build does not cover              */
+  CTM_ERR_WORKSPACE = -5,   /* workspace smaller than ctm_workspace_bytes() says    */
+  CTM_ERR_ALIGN = -6,       /* a device pointer is not aligned to 16 bytes          */
+  CTM_ERR_ALLOC = -7,       /* device allocation failed (ctm_create_mlp only)       */
+  CTM_ERR_HIP = -8          /* a HIP runtime call failed; text in ctm_last_error()  */
+} ctm_status;
+
+/*
+ * Build a handle for an MLP with n_layers linear layers (n_layers >= 2, i.e. at least one
+ * hidden layer) of widths dims[0] = D, ..., dims[n_layers] = 1   (Sec. 4 setup; App. H model).
+ *   dims  host, n_layers + 1 ints, all >= 1, dims[n_layers] must be 1
+ *   W     host array of n_layers dev pointers; W[l] is [dims[l+1], dims[l]] row-major
+ *   b     host array of n_layers dev pointers to [dims[l+1]]; the array or any entry may
+ *         be NULL, meaning a zero bias
+ * The weights are copied into the library's own zero-padded tile layout on `stream`.
+ * On failure *out is set to NULL.
+ */
+int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const void *const *b,
+                   ctm_dtype dtype, ctm_act act, void *stream, ctm_mlp **out);
+
+/* Waits for the device, then frees the handle's device memory.  NULL is allowed. */
+int ctm_destroy_mlp(ctm_mlp *mlp);
+
+/*
+ * Coefficient rows carried per point by collapsed Taylor mode of order K with R
+ * directions: 1 + (K-1)*R + 1 (Sec. 3.1).  K must be 2 or 4, R >= 1; returns -1 otherwise.
+ */
+long ctm_rows_per_point(int K, int R);
+
+/*
+ * Bytes of device workspace an operator call of order K (2 or 4) on N points with R
+ * directions needs.  Returns 0 on invalid arguments (and sets ctm_last_error()).
+ * The workspace must be 256-byte aligned; its contents are scratch.
+ */
+size_t ctm_workspace_bytes(const ctm_mlp *mlp, int K, long N, int R);
+
+/*
+ * Second-order operator  op[n] = scale * sum_r v_r^T (Hessian f)(x_n) v_r      (Sec. 3.2, Eq. 7)
+ *   x       dev [N, D]
+ *   V       dev directions, or NULL for the standard basis e_1..e_D (then R must equal D):
+ *           the exact Laplacian.  v_point_stride = 0: V is [R, D], shared by all points;
+ *           v_point_stride = R*D: V is [N, R, D], own directions per point.
+ *   scale   1 for exact operators, 1/S for the S-sample randomized Laplacian; applied to
+ *           the final scalar only
+ *   u, op   dev [N] outputs; either may be NULL if not wanted
+ * Any R >= 1 is accepted; direction sets too large for one tile are processed in several
+ * passes whose partial sums are added in a fixed order.
+ */
+int ctm_laplacian(const ctm_mlp *mlp, const void *x, long N, const void *V, int R,
+                  long v_point_stride, double scale, void *u, void *op, void *workspace,
+                  size_t workspace_bytes, void *stream);
+
+/*
+ * Weighted Laplacian  op[n] = Tr(sigma sigma^T Hessian f(x_n)) = sum_k s_k^T H s_k     (Sec. 3.2, Eq. 8)
+ *   sigma   dev [D, K] row-major, shared by all points; the directions are its K columns
+ * Same as ctm_laplacian with V = sigma^T, shared, scale = 1.
+ */
+int ctm_weighted_laplacian(const ctm_mlp *mlp, const void *x, long N, const void *sigma, int K,
+                           void *u, void *op, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/*
+ * Randomized biharmonic  op[n] = 1/(3S) * sum_s < d^4 f(x_n), v_s^{(x)4} >         (Sec. 3.3, Eq. 9)
+ * by collapsed 4th-order Taylor mode (1 + 3S + 1 rows per point).  V and
+ * v_point_stride as in ctm_laplacian (V must not be NULL).  The estimator is unbiased
+ * for standard-normal directions only; the call itself accepts any V.
+ */
+int ctm_biharmonic_rand(const ctm_mlp *mlp, const void *x, long N, const void *V, int S,
+                        long v_point_stride, void *u, void *op, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
+ * Host-side description of how an order-K, R-direction call is tiled: points per tile,
+ * 16-row MFMA blocks per tile, directions in the first (largest) pass and number of
+ * passes.  Pure host logic (no GPU needed); any output pointer may be NULL.
+ */
+int ctm_tile_plan(ctm_dtype dtype, int K, int R, int *points_per_tile, int *row_blocks,
+                  int *dirs_per_pass, int *n_passes);
+
+/*
+ * Benchmark diagnostics.  Between ctm_profile_begin() and ctm_profile_end() every operator
+ * call made by the calling thread brackets each kernel it launches with HIP events on the
+ * call's stream (this creates events, so it is not for production loops).
+ * ctm_profile_end() waits for the last event and returns, per kernel class, the summed
+ * event-to-event time in milliseconds and the number of launches:
+ *   index 0 seed kernel, 1 stacked GEMM + jet rule (one launch per hidden layer), 2 last layer.
+ * Either output pointer may be NULL.
+ */
+int ctm_profile_begin(void);
+int ctm_profile_end(double ms[3], long launches[3]);
+
+/* Message for the calling thread's most recent failing call ("" if none). */
+const char *ctm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CTM_H */

@@ -1,0 +1,377 @@
+// C ABI of libctm.so: argument validation, tiling plan, workspace carving and the
+// per-call launch sequence  seed -> (stacked GEMM + jet rule) per hidden layer -> last layer.
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/ctm.h"
+#include "ctm_internal.h"
+
+using namespace ctm;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+int fail_hip(hipError_t e, const char *what) {
+  return fail(CTM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+size_t elem_size(ctm_dtype t) { return t == CTM_F64 ? 8 : 4; }
+size_t round256(size_t b) { return (b + 255) / 256 * 256; }
+
+struct PassPlan {
+  int R, rho, MB, P;
+};
+
+// Optional per-kernel timing for benchmarks (ctm_profile_begin / ctm_profile_end).
+struct Profile {
+  bool on = false;
+  std::vector<hipEvent_t> ev;  // ev[i], ev[i+1] bracket interval i
+  std::vector<int> cls;        // kernel class of interval i, or -1 for a gap between calls
+};
+thread_local Profile g_prof;
+
+hipError_t prof_mark(hipStream_t st, int cls_of_preceding) {
+  if (!g_prof.on) return hipSuccess;
+  hipEvent_t e;
+  hipError_t rc = hipEventCreate(&e);
+  if (rc != hipSuccess) return rc;
+  rc = hipEventRecord(e, st);
+  if (rc != hipSuccess) { (void)hipEventDestroy(e); return rc; }
+  if (!g_prof.ev.empty()) g_prof.cls.push_back(cls_of_preceding);
+  g_prof.ev.push_back(e);
+  return hipSuccess;
+}
+
+long rows_per_point(int K, int R) { return 1L + (long)(K - 1) * R + 1L; }
+
+// Largest direction count whose rows fit one tile of kMaxRowBlocks MFMA row blocks.
+int max_dirs_per_pass(int K) { return (16 * kMaxRowBlocks - 2) / (K - 1); }
+
+// Pick the row-block count that wastes the fewest MFMA rows (ties: the taller tile).
+PassPlan plan_pass(int K, int R) {
+  PassPlan best{R, (int)rows_per_point(K, R), 0, 0};
+  double best_eff = -1.0;
+  static const int kChoices[] = {4, 8, 9, 12, 13, 16};
+  for (int MB : kChoices) {  // ascending, so a tie goes to the taller tile
+    const int P = 16 * MB / best.rho;
+    if (P < 1) continue;
+    const double eff = (double)P * best.rho / (16.0 * MB);
+    if (eff >= best_eff - 1e-12) {
+      best.MB = MB;
+      best.P = P;
+      if (eff > best_eff) best_eff = eff;
+    }
+  }
+  return best;
+}
+
+struct Split {
+  int n_passes, first, lastR;  // passes 0..n-2 take `first` directions, the last one `lastR`
+};
+Split split_dirs(int K, int R) {
+  const int cap = max_dirs_per_pass(K);
+  Split s;
+  s.n_passes = (R + cap - 1) / cap;
+  s.first = (R + s.n_passes - 1) / s.n_passes;
+  s.lastR = R - (s.n_passes - 1) * s.first;
+  return s;
+}
+
+}  // namespace
+
+struct ctm_mlp {
+  int L = 0;                 // linear layers
+  std::vector<int> dims;     // L + 1
+  std::vector<int> ld;       // padded widths of dims[0..L-1]
+  std::vector<int> col_tiles;  // per hidden layer l = 0..L-2
+  ctm_dtype dtype = CTM_F32;
+  ctm_act act = CTM_ACT_TANH;
+  int device = 0;
+  void *arena = nullptr;
+  std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: padded vector and scalar bias
+};
+
+namespace {
+
+int tile_cols_of(ctm_dtype t) { return t == CTM_F64 ? tile_cols<double>() : tile_cols<float>(); }
+
+struct Layout {
+  size_t block_bytes, pair_bytes, total;
+};
+Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
+  const size_t es = elem_size(m->dtype);
+  int maxld = 0;
+  for (int l = 0; l + 1 < m->L; ++l) maxld = m->ld[l] > maxld ? m->ld[l] : maxld;  // inputs of hidden layers
+  Layout lo;
+  lo.block_bytes = round256((size_t)N * (size_t)rows_per_point(K, Rpass) * (size_t)maxld * es);
+  lo.pair_bytes = round256((size_t)N * 2 * (size_t)m->ld[m->L - 1] * es);
+  lo.total = 2 * lo.block_bytes + lo.pair_bytes;
+  return lo;
+}
+
+template <typename T>
+int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, long sr, long sd,
+               double scale, T *u, T *op, void *ws, hipStream_t st) {
+  const Split sp = split_dirs(K, R);
+  const Layout lo = workspace_layout(m, K, N, sp.first);
+  T *buf[2] = {reinterpret_cast<T *>(ws), reinterpret_cast<T *>((char *)ws + lo.block_bytes)};
+  T *pair = reinterpret_cast<T *>((char *)ws + 2 * lo.block_bytes);
+  const int L = m->L;
+  if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
+  for (int pass = 0; pass < sp.n_passes; ++pass) {
+    const int Rp = (pass == sp.n_passes - 1) ? sp.lastR : sp.first;
+    const PassPlan pl = plan_pass(K, Rp);
+    SeedArgs<T> sa;
+    sa.x = x; sa.V = V; sa.out = buf[1]; sa.N = N;
+    sa.v_sn = sn; sa.v_sr = sr; sa.v_sd = sd;
+    sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = pass * sp.first;
+    hipError_t e = launch_seed<T>(sa, st);
+    if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
+    (void)prof_mark(st, 0);
+    const T *in = buf[1];
+    for (int l = 0; l + 1 < L; ++l) {
+      const bool last = (l == L - 2);
+      T *out = last ? pair : buf[l & 1];
+      LayerArgs<T> la;
+      la.Hin = in; la.W = (const T *)m->Wp[l]; la.bias = (const T *)m->bp[l]; la.Hout = out;
+      la.n_points = N; la.n_row_tiles = (N + pl.P - 1) / pl.P; la.n_col_tiles = m->col_tiles[l];
+      la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[l]; la.ldout = m->ld[l + 1];
+      la.order = K; la.R = Rp; la.last = last ? 1 : 0; la.act = (int)m->act;
+      e = launch_layer<T>(la, pl.MB, st);
+      if (e != hipSuccess) return fail_hip(e, "layer kernel launch");
+      (void)prof_mark(st, 1);
+      in = out;
+    }
+    FinalArgs<T> fa;
+    fa.pair = pair; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
+    fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = pass > 0;
+    e = launch_final<T>(fa, st);
+    if (e != hipSuccess) return fail_hip(e, "final kernel launch");
+    (void)prof_mark(st, 2);
+  }
+  return CTM_OK;
+}
+
+bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+int run_operator(const ctm_mlp *m, int K, const void *x, long N, const void *V, int R, long sn, long sr,
+                 long sd, double scale, void *u, void *op, void *ws, size_t ws_bytes, void *stream,
+                 const char *who) {
+  if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
+  if (!x) return fail(CTM_ERR_NULL, "%s: x is NULL", who);
+  if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
+  if (R < 1) return fail(CTM_ERR_SHAPE, "%s: %d directions, need at least 1", who, R);
+  if (N > (1L << 40) / rows_per_point(K, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
+  if (!ws) return fail(CTM_ERR_NULL, "%s: workspace is NULL", who);
+  const size_t need = ctm_workspace_bytes(m, K, N, R);
+  if (ws_bytes < need)
+    return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: workspace must be 256-byte aligned", who);
+  if (misaligned(x, es) || misaligned(V, es) || misaligned(u, es) || misaligned(op, es))
+    return fail(CTM_ERR_ALIGN, "%s: x, directions, u and op must be aligned to the element size", who);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (m->dtype == CTM_F64)
+    return run_passes<double>(m, K, (const double *)x, N, (const double *)V, R, sn, sr, sd, scale, (double *)u,
+                              (double *)op, ws, st);
+  return run_passes<float>(m, K, (const float *)x, N, (const float *)V, R, sn, sr, sd, scale, (float *)u,
+                           (float *)op, ws, st);
+}
+
+template <typename T> hipError_t pack_all(ctm_mlp *m, const void *const *W, const void *const *b, hipStream_t st) {
+  for (int l = 0; l < m->L; ++l) {
+    const bool lastl = (l == m->L - 1);
+    const int rows_pad = lastl ? 1 : m->col_tiles[l] * tile_cols<T>();
+    const T *bl = (b && b[l]) ? (const T *)b[l] : nullptr;
+    hipError_t e = launch_pack<T>((const T *)W[l], bl, m->dims[l + 1], m->dims[l], (T *)m->Wp[l], (T *)m->bp[l],
+                                  rows_pad, m->ld[l], st);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ctm_last_error(void) { return g_err.c_str(); }
+
+int ctm_profile_begin(void) {
+  for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+  g_prof.ev.clear();
+  g_prof.cls.clear();
+  g_prof.on = true;
+  return CTM_OK;
+}
+
+int ctm_profile_end(double ms[3], long launches[3]) {
+  g_prof.on = false;
+  int rc = CTM_OK;
+  if (ms) ms[0] = ms[1] = ms[2] = 0.0;
+  if (launches) launches[0] = launches[1] = launches[2] = 0;
+  if (!g_prof.ev.empty()) {
+    hipError_t e = hipEventSynchronize(g_prof.ev.back());
+    if (e != hipSuccess) rc = fail_hip(e, "ctm_profile_end: hipEventSynchronize");
+    for (size_t i = 0; rc == CTM_OK && i < g_prof.cls.size(); ++i) {
+      const int c = g_prof.cls[i];
+      if (c < 0) continue;
+      float dt = 0.f;
+      e = hipEventElapsedTime(&dt, g_prof.ev[i], g_prof.ev[i + 1]);
+      if (e != hipSuccess) { rc = fail_hip(e, "ctm_profile_end: hipEventElapsedTime"); break; }
+      if (ms) ms[c] += dt;
+      if (launches) launches[c] += 1;
+    }
+  }
+  for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+  g_prof.ev.clear();
+  g_prof.cls.clear();
+  return rc;
+}
+
+long ctm_rows_per_point(int K, int R) {
+  if ((K != 2 && K != 4) || R < 1) return -1;
+  return rows_per_point(K, R);
+}
+
+int ctm_tile_plan(ctm_dtype dtype, int K, int R, int *points_per_tile, int *row_blocks, int *dirs_per_pass,
+                  int *n_passes) {
+  if (dtype != CTM_F64 && dtype != CTM_F32) return fail(CTM_ERR_DTYPE, "ctm_tile_plan: unknown dtype %d", (int)dtype);
+  if (K != 2 && K != 4) return fail(CTM_ERR_UNSUPPORTED, "ctm_tile_plan: order K = %d, only 2 and 4 are built", K);
+  if (R < 1) return fail(CTM_ERR_SHAPE, "ctm_tile_plan: %d directions, need at least 1", R);
+  const Split sp = split_dirs(K, R);
+  const PassPlan pl = plan_pass(K, sp.first);
+  if (points_per_tile) *points_per_tile = pl.P;
+  if (row_blocks) *row_blocks = pl.MB;
+  if (dirs_per_pass) *dirs_per_pass = sp.first;
+  if (n_passes) *n_passes = sp.n_passes;
+  return CTM_OK;
+}
+
+int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const void *const *b, ctm_dtype dtype,
+                   ctm_act act, void *stream, ctm_mlp **out) {
+  if (!out) return fail(CTM_ERR_NULL, "ctm_create_mlp: out is NULL");
+  *out = nullptr;
+  if (!dims || !W) return fail(CTM_ERR_NULL, "ctm_create_mlp: dims or W is NULL");
+  if (dtype != CTM_F64 && dtype != CTM_F32) return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown dtype %d", (int)dtype);
+  if (act != CTM_ACT_TANH && act != CTM_ACT_IDENTITY)
+    return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown activation %d", (int)act);
+  if (n_layers < 2 || n_layers > 64)
+    return fail(CTM_ERR_SHAPE, "ctm_create_mlp: n_layers = %d, need 2..64 (at least one hidden layer)", n_layers);
+  for (int l = 0; l <= n_layers; ++l)
+    if (dims[l] < 1 || dims[l] > (1 << 20)) return fail(CTM_ERR_SHAPE, "ctm_create_mlp: dims[%d] = %d out of range", l, dims[l]);
+  if (dims[n_layers] != 1) return fail(CTM_ERR_UNSUPPORTED, "ctm_create_mlp: output width %d, only scalar outputs are built", dims[n_layers]);
+  const size_t es = elem_size(dtype);
+  for (int l = 0; l < n_layers; ++l) {
+    if (!W[l]) return fail(CTM_ERR_NULL, "ctm_create_mlp: W[%d] is NULL", l);
+    if (misaligned(W[l], es) || (b && misaligned(b[l], es)))
+      return fail(CTM_ERR_ALIGN, "ctm_create_mlp: W[%d] / b[%d] not aligned to the element size", l, l);
+  }
+
+  ctm_mlp *m = new (std::nothrow) ctm_mlp;
+  if (!m) return fail(CTM_ERR_ALLOC, "ctm_create_mlp: out of host memory");
+  m->L = n_layers;
+  m->dims.assign(dims, dims + n_layers + 1);
+  m->dtype = dtype;
+  m->act = act;
+  const int bn = tile_cols_of(dtype);
+  size_t total = 0;
+  std::vector<size_t> woff(n_layers), boff(n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    m->ld.push_back(pad_ld(dims[l]));
+    const bool lastl = (l == n_layers - 1);
+    const int ct = lastl ? 0 : (dims[l + 1] + bn - 1) / bn;
+    if (!lastl) m->col_tiles.push_back(ct);
+    const size_t rows_pad = lastl ? 1 : (size_t)ct * bn;
+    woff[l] = total;
+    total += round256(rows_pad * m->ld[l] * es);
+    boff[l] = total;
+    total += round256(rows_pad * es);
+  }
+  hipError_t e = hipGetDevice(&m->device);
+  if (e != hipSuccess) { delete m; return fail_hip(e, "ctm_create_mlp: hipGetDevice"); }
+  e = hipMalloc(&m->arena, total);
+  if (e != hipSuccess) {
+    delete m;
+    (void)hipGetLastError();
+    return fail(CTM_ERR_ALLOC, "ctm_create_mlp: hipMalloc of %zu bytes failed: %s", total, hipGetErrorString(e));
+  }
+  for (int l = 0; l < n_layers; ++l) {
+    m->Wp.push_back((char *)m->arena + woff[l]);
+    m->bp.push_back((char *)m->arena + boff[l]);
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  e = (dtype == CTM_F64) ? pack_all<double>(m, W, b, st) : pack_all<float>(m, W, b, st);
+  if (e != hipSuccess) {
+    (void)hipFree(m->arena);
+    delete m;
+    return fail_hip(e, "ctm_create_mlp: weight packing");
+  }
+  *out = m;
+  return CTM_OK;
+}
+
+int ctm_destroy_mlp(ctm_mlp *m) {
+  if (!m) return CTM_OK;
+  int rc = CTM_OK;
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) rc = fail_hip(e, "ctm_destroy_mlp: hipDeviceSynchronize");
+  e = hipFree(m->arena);
+  if (e != hipSuccess && rc == CTM_OK) rc = fail_hip(e, "ctm_destroy_mlp: hipFree");
+  delete m;
+  return rc;
+}
+
+size_t ctm_workspace_bytes(const ctm_mlp *m, int K, long N, int R) {
+  if (!m) { fail(CTM_ERR_NULL, "ctm_workspace_bytes: mlp handle is NULL"); return 0; }
+  if ((K != 2 && K != 4) || N < 1 || R < 1) {
+    fail(CTM_ERR_SHAPE, "ctm_workspace_bytes: need K in {2,4}, N >= 1, R >= 1 (got %d, %ld, %d)", K, N, R);
+    return 0;
+  }
+  return workspace_layout(m, K, N, split_dirs(K, R).first).total;
+}
+
+int ctm_laplacian(const ctm_mlp *m, const void *x, long N, const void *V, int R, long v_point_stride, double scale,
+                  void *u, void *op, void *ws, size_t ws_bytes, void *stream) {
+  if (m && !V && R != m->dims[0])
+    return fail(CTM_ERR_SHAPE, "ctm_laplacian: V = NULL selects the standard basis, so R must be D = %d (got %d)", m->dims[0], R);
+  if (m && R >= 1 && v_point_stride != 0 && v_point_stride != (long)R * m->dims[0])
+    return fail(CTM_ERR_SHAPE, "ctm_laplacian: v_point_stride = %ld, must be 0 (shared) or R*D = %ld", v_point_stride,
+                (long)R * m->dims[0]);
+  const long D = m ? m->dims[0] : 0;
+  return run_operator(m, 2, x, N, V, R, v_point_stride, D, 1, scale, u, op, ws, ws_bytes, stream, "ctm_laplacian");
+}
+
+int ctm_weighted_laplacian(const ctm_mlp *m, const void *x, long N, const void *sigma, int K, void *u, void *op,
+                           void *ws, size_t ws_bytes, void *stream) {
+  if (m && !sigma) return fail(CTM_ERR_NULL, "ctm_weighted_laplacian: sigma is NULL");
+  // direction k is column k of sigma[D][K]: element (k, d) sits at sigma[d*K + k]
+  return run_operator(m, 2, x, N, sigma, K, 0, 1, K, 1.0, u, op, ws, ws_bytes, stream, "ctm_weighted_laplacian");
+}
+
+int ctm_biharmonic_rand(const ctm_mlp *m, const void *x, long N, const void *V, int S, long v_point_stride, void *u,
+                        void *op, void *ws, size_t ws_bytes, void *stream) {
+  if (m && !V) return fail(CTM_ERR_NULL, "ctm_biharmonic_rand: V is NULL");
+  if (m && S >= 1 && v_point_stride != 0 && v_point_stride != (long)S * m->dims[0])
+    return fail(CTM_ERR_SHAPE, "ctm_biharmonic_rand: v_point_stride = %ld, must be 0 (shared) or S*D = %ld",
+                v_point_stride, (long)S * m->dims[0]);
+  const long D = m ? m->dims[0] : 0;
+  const double scale = S >= 1 ? 1.0 / (3.0 * S) : 0.0;
+  return run_operator(m, 4, x, N, V, S, v_point_stride, D, 1, scale, u, op, ws, ws_bytes, stream, "ctm_biharmonic_rand");
+}
+
+}  // extern "C"

@@ -1,0 +1,82 @@
+// Internal declarations shared by the translation units of libctm.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+
+namespace ctm {
+
+// Shape constants of the stacked-GEMM kernel, per storage type.
+//   KV  elements per 16-byte LDS/global vector
+//   BK  K-extent of one LDS stage; BK * sizeof(T) = 128 bytes for both types
+//   NB  16-column MFMA blocks per wave; a workgroup has 4 waves side by side
+template <typename T> struct Shape;
+template <> struct Shape<float> {
+  static constexpr int KV = 4, BK = 32, NB = 2;
+};
+template <> struct Shape<double> {
+  static constexpr int KV = 2, BK = 16, NB = 1;
+};
+template <typename T> constexpr int tile_cols() { return 64 * Shape<T>::NB; }
+
+// Leading dimension (in elements) of every coefficient block: widths are padded with
+// zero columns to a multiple of 32 so that both element types see whole LDS stages.
+constexpr int kLdAlign = 32;
+inline int pad_ld(int d) { return (d + kLdAlign - 1) / kLdAlign * kLdAlign; }
+
+constexpr int kMaxRowBlocks = 16;  // 16-row MFMA blocks per tile => at most 256 rows per tile
+
+template <typename T> struct LayerArgs {
+  const T *Hin;      // [n_points * rho][ldin] coefficient block entering the layer
+  const T *W;        // [n_col_tiles * tile_cols][ldin] zero-padded weights
+  const T *bias;     // [n_col_tiles * tile_cols] zero-padded bias
+  T *Hout;           // last == 0: [n_points * rho][ldout]; last == 1: [n_points][2][ldout]
+  long n_points;
+  long n_row_tiles;  // ceil(n_points / P)
+  int n_col_tiles;
+  int rho;           // coefficient rows per point
+  int P;             // points per tile, P * rho <= 16 * MB
+  int ldin;
+  int ldout;
+  int order;         // 2 or 4
+  int R;             // directions in this pass
+  int last;          // emit only the 0-th and the collapsed row
+  int act;           // 0 tanh, 1 identity
+};
+
+// Launch the stacked GEMM + fused jet rule for one layer.  MB in {4, 8, 9, 12, 13, 16}.
+template <typename T> hipError_t launch_layer(const LayerArgs<T> &a, int MB, hipStream_t s);
+bool row_blocks_supported(int MB);
+
+template <typename T> struct SeedArgs {
+  const T *x;   // [N][D]
+  const T *V;   // directions or nullptr (standard basis)
+  T *out;       // [N * rho][ld]
+  long N;
+  long v_sn;    // element strides of V: point, direction, coordinate
+  long v_sr;
+  long v_sd;
+  int D, ld, rho, order;
+  int r0;       // index of this pass's first direction
+};
+template <typename T> hipError_t launch_seed(const SeedArgs<T> &a, hipStream_t s);
+
+template <typename T>
+hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad,
+                       int ld, hipStream_t s);
+
+template <typename T> struct FinalArgs {
+  const T *pair;  // [N][2][ld] : h_0 and the collapsed h_K of the last hidden layer
+  const T *w;     // [ld] zero-padded last-layer weights
+  const T *b;     // [1]
+  T *u;           // may be nullptr
+  T *op;          // may be nullptr
+  long N;
+  int ld;
+  double scale;
+  int accumulate;  // 0: write u and op; 1: op += (later passes over a split direction set)
+};
+template <typename T> hipError_t launch_final(const FinalArgs<T> &a, hipStream_t s);
+
+}  // namespace ctm

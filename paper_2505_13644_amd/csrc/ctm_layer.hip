@@ -1,0 +1,300 @@
+// Stacked GEMM of one MLP layer over the whole coefficient block, with the collapsed
+// Taylor-mode rule of the activation fused in as its epilogue (gfx950 MFMA).
+//
+// What one layer computes (Sec. 3.1, Eq. 6; App. D collapsed scheme; App. H for tanh):
+//   for every point n and every coefficient row c of the point:  z_c = W h_c  (+ b for c = 0)
+//   order 2:  t = tanh z_0 ; a = 1 - t^2 ; b2 = -2 t a
+//             h_0 = t ;  h_{1,r} = a z_{1,r} ;  h_2 = a z_2 + b2 * sum_r z_{1,r}^2
+//   order 4:  c3 = a (6 t^2 - 2) ; d4 = 8 t a (2 - 3 t^2)        (derivatives of tanh)
+//             h_{1,r} = a z1 ; h_{2,r} = b2 z1^2 + a z2 ; h_{3,r} = c3 z1^3 + 3 b2 z1 z2 + a z3
+//             h_4 = a z_4 + sum_r [ d4 z1^4 + 6 c3 z1^2 z2 + 4 b2 z1 z3 + 3 b2 z2^2 ]
+//   (multiplicities 1, 6, 4, 3, 1 of the order-4 Faa di Bruno formula, App. A), where z_2 / z_4
+//   and h_2 / h_4 are the coefficients already summed over the directions.
+//
+// Layout.  The block is point-major: rows n*rho .. n*rho + rho - 1 belong to point n
+// (row 0: order 0; then the per-direction rows; last row: the collapsed one), each row
+// `ld` elements with zero padding.  A workgroup owns P whole points (P*rho <= 16*MB rows)
+// times 64*NB output features, so the sum over directions never leaves the workgroup:
+// the accumulators are staged through LDS once and each thread then walks the rows of one
+// (point, feature) pair, keeping the running sums in registers.
+//
+// MFMA use: v_mfma_{f32,f64}_16x16x4.  Lane l supplies A[row l%16][k l/16] and
+// B[k l/16][col l%16] and receives D[rows 4*(l/16)..+3][col l%16].  Each lane fetches KV
+// consecutive k values with one 16-byte LDS read and feeds them to KV successive MFMAs; since
+// A and B use the same assignment, the k-sum is merely taken in a permuted order.
+#include "ctm_internal.h"
+
+namespace ctm {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x2 __attribute__((ext_vector_type(2)));
+
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+  using ld = f32x4;   // 16-byte load unit
+  using acc = f32x4;  // one 16x16 MFMA block: 4 rows per lane
+};
+template <> struct Vec<double> {
+  using ld = f64x2;
+  using acc = f64x4;
+};
+
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f64x4 mfma16(double a, double b, f64x4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float act_tanh(float z) { return tanhf(z); }
+__device__ __forceinline__ double act_tanh(double z) { return tanh(z); }
+
+constexpr int kThreads = 256;
+constexpr int kXcds = 8;
+
+template <typename T, int MB> struct Tile {
+  static constexpr int KV = Shape<T>::KV;
+  static constexpr int BK = Shape<T>::BK;
+  static constexpr int NB = Shape<T>::NB;
+  static constexpr int BM = 16 * MB;
+  static constexpr int BN = 64 * NB;
+  static constexpr int PADE = 16 / sizeof(T);     // 16 bytes of padding per LDS row
+  static constexpr int LROW = BK + PADE;          // LDS row pitch of a stage, elements
+  static constexpr int UPR = BK / KV;             // 16-byte units per stage row (= 8)
+  static constexpr int A_STAGE = BM * LROW;
+  static constexpr int B_STAGE = BN * LROW;
+  static constexpr int A_LD = (BM * UPR + kThreads - 1) / kThreads;
+  static constexpr int B_LD = (BN * UPR) / kThreads;
+  static constexpr int CROW = BN + PADE;          // LDS row pitch of the staged C tile
+  static constexpr size_t kStageBytes = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(T);
+  static constexpr size_t kCBytes = (size_t)BM * CROW * sizeof(T);
+  static constexpr size_t kLdsBytes = kStageBytes > kCBytes ? kStageBytes : kCBytes;
+  static_assert((BN * UPR) % kThreads == 0, "B tile must split evenly over the threads");
+  static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
+};
+
+template <typename T, int MB>
+__global__ __launch_bounds__(kThreads) void layer_kernel(const LayerArgs<T> a) {
+  using TL = Tile<T, MB>;
+  using vld = typename Vec<T>::ld;
+  using vacc = typename Vec<T>::acc;
+  constexpr int KV = TL::KV, BK = TL::BK, NB = TL::NB, BN = TL::BN;
+  constexpr int LROW = TL::LROW, UPR = TL::UPR, CROW = TL::CROW;
+
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  T *lds = reinterpret_cast<T *>(lds_raw);
+  T *As = lds;                      // [2][A_STAGE]
+  T *Bs = lds + 2 * TL::A_STAGE;    // [2][B_STAGE]
+  T *Cs = lds;                      // [BM][CROW], reuses the stages after the k loop
+
+  // ---- which tile: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
+  // Give every XCD one contiguous run of tiles, ordered so that the column tiles of one
+  // row tile (which read the same rows of Hin) are neighbours in time on the same L2.
+  const long n_tiles = a.n_row_tiles * a.n_col_tiles;
+  const int xcd = blockIdx.x % kXcds;
+  const long slot = blockIdx.x / kXcds;
+  const long base = n_tiles / kXcds, rem = n_tiles % kXcds;
+  const long mine = base + (xcd < rem ? 1 : 0);
+  if (slot >= mine) return;
+  const long tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  const long row_tile = tile / a.n_col_tiles;
+  const int col_tile = (int)(tile % a.n_col_tiles);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+
+  const long p0 = row_tile * a.P;                                   // first point of the tile
+  const int p_valid = (int)((a.n_points - p0) < a.P ? (a.n_points - p0) : a.P);
+  const int rows_valid = p_valid * a.rho;                           // <= BM
+  const T *Ag = a.Hin + p0 * a.rho * (long)a.ldin;
+  const T *Bg = a.W + (long)col_tile * BN * a.ldin;
+
+  // ---- per-thread global->LDS copy slots (16 bytes each)
+  int a_off[TL::A_LD];      // element offset inside an LDS stage, or -1
+  long a_goff[TL::A_LD];    // element offset from Ag
+  bool a_ok[TL::A_LD];
+#pragma unroll
+  for (int i = 0; i < TL::A_LD; ++i) {
+    const int u = tid + i * kThreads;
+    const int row = u / UPR, kq = u % UPR;
+    a_off[i] = (u < TL::BM * UPR) ? row * LROW + kq * KV : -1;
+    a_ok[i] = (u < TL::BM * UPR) && (row < rows_valid);
+    a_goff[i] = (long)row * a.ldin + kq * KV;
+  }
+  int b_off[TL::B_LD];
+  long b_goff[TL::B_LD];
+#pragma unroll
+  for (int i = 0; i < TL::B_LD; ++i) {
+    const int u = tid + i * kThreads;
+    const int row = u / UPR, kq = u % UPR;
+    b_off[i] = row * LROW + kq * KV;
+    b_goff[i] = (long)row * a.ldin + kq * KV;
+  }
+
+  vld a_reg[TL::A_LD], b_reg[TL::B_LD];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < TL::A_LD; ++i) {
+      vld v = {};
+      if (a_ok[i]) v = *reinterpret_cast<const vld *>(Ag + a_goff[i] + k0);
+      a_reg[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < TL::B_LD; ++i) b_reg[i] = *reinterpret_cast<const vld *>(Bg + b_goff[i] + k0);
+  };
+  auto store_lds = [&](int stage) {
+    T *Ad = As + stage * TL::A_STAGE;
+    T *Bd = Bs + stage * TL::B_STAGE;
+#pragma unroll
+    for (int i = 0; i < TL::A_LD; ++i)
+      if (a_off[i] >= 0) *reinterpret_cast<vld *>(Ad + a_off[i]) = a_reg[i];
+#pragma unroll
+    for (int i = 0; i < TL::B_LD; ++i) *reinterpret_cast<vld *>(Bd + b_off[i]) = b_reg[i];
+  };
+
+  vacc acc[MB][NB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = vacc{0, 0, 0, 0};
+
+  const int nk = a.ldin / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int stage = kt & 1;
+    if (kt + 1 < nk) load_global((kt + 1) * BK);  // in flight while this stage is consumed
+
+    const T *Ac = As + stage * TL::A_STAGE + lr * LROW + lg * KV;
+    const T *Bc = Bs + stage * TL::B_STAGE + (wave * 16 * NB + lr) * LROW + lg * KV;
+#pragma unroll
+    for (int kg = 0; kg < BK / (4 * KV); ++kg) {
+      vld bf[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vld *>(Bc + nb * 16 * LROW + kg * 4 * KV);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const vld af = *reinterpret_cast<const vld *>(Ac + mb * 16 * LROW + kg * 4 * KV);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+          for (int j = 0; j < KV; ++j) acc[mb][nb] = mfma16(af[j], bf[nb][j], acc[mb][nb]);
+      }
+    }
+
+    if (kt + 1 < nk) store_lds(stage ^ 1);  // the other stage was last read before the previous barrier
+    __syncthreads();
+  }
+
+  // ---- stage the accumulators through LDS (all waves have passed the final barrier, so the
+  // k-loop stages are dead)
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        Cs[(mb * 16 + lg * 4 + v) * CROW + wave * 16 * NB + nb * 16 + lr] = acc[mb][nb][v];
+  __syncthreads();
+
+  // ---- collapsed jet rule: one thread per (point, feature) pair, rows walked in order
+  const int j = tid % BN;
+  const long jg = (long)col_tile * BN + j;
+  if (jg >= a.ldout) return;  // no barrier follows
+  const T bias = a.bias[jg];
+  const int R = a.R, rho = a.rho;
+  for (int p = tid / BN; p < p_valid; p += kThreads / BN) {
+    const T *c = Cs + (long)p * rho * CROW + j;
+    const long n = p0 + p;
+    T *o = a.last ? a.Hout + (n * 2) * a.ldout + jg : a.Hout + (n * rho) * a.ldout + jg;
+    const long ostep = a.ldout;
+    const T z0 = c[0] + bias;
+    T t, d1, d2;
+    if (a.act == 0) {
+      t = act_tanh(z0);
+      d1 = T(1) - t * t;
+      d2 = T(-2) * t * d1;
+    } else {
+      t = z0;
+      d1 = T(1);
+      d2 = T(0);
+    }
+    o[0] = t;
+    if (a.order == 2) {
+      T s = T(0);
+      for (int r = 1; r <= R; ++r) {
+        const T z1 = c[(long)r * CROW];
+        s += z1 * z1;
+        if (!a.last) o[r * ostep] = d1 * z1;
+      }
+      const T z2 = c[(long)(R + 1) * CROW];
+      const T h2 = d1 * z2 + d2 * s;
+      o[(a.last ? 1 : R + 1) * ostep] = h2;
+    } else {
+      T d3, d4;
+      if (a.act == 0) {
+        d3 = d1 * (T(6) * t * t - T(2));
+        d4 = T(8) * t * d1 * (T(2) - T(3) * t * t);
+      } else {
+        d3 = T(0);
+        d4 = T(0);
+      }
+      T s = T(0);
+      for (int r = 0; r < R; ++r) {
+        const T *cr = c + (long)(1 + 3 * r) * CROW;
+        const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW];
+        const T z1s = z1 * z1;
+        s += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
+        if (!a.last) {
+          T *orow = o + (long)(1 + 3 * r) * ostep;
+          orow[0] = d1 * z1;
+          orow[ostep] = d2 * z1s + d1 * z2;
+          orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+        }
+      }
+      const T z4 = c[(long)(3 * R + 1) * CROW];
+      o[(a.last ? 1 : 3 * R + 1) * ostep] = d1 * z4 + s;
+    }
+  }
+}
+
+template <typename T, int MB> static hipError_t launch_one(const LayerArgs<T> &a, hipStream_t s) {
+  using TL = Tile<T, MB>;
+  static bool attr_set = false;  // benign race: every thread sets the same value
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&layer_kernel<T, MB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)TL::kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const long n_tiles = a.n_row_tiles * a.n_col_tiles;
+  const long grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
+  if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((layer_kernel<T, MB>), dim3((unsigned)grid), dim3(kThreads), TL::kLdsBytes, s, a);
+  return hipGetLastError();
+}
+
+bool row_blocks_supported(int MB) {
+  return MB == 4 || MB == 8 || MB == 9 || MB == 12 || MB == 13 || MB == 16;
+}
+
+template <typename T> hipError_t launch_layer(const LayerArgs<T> &a, int MB, hipStream_t s) {
+  switch (MB) {
+    case 4: return launch_one<T, 4>(a, s);
+    case 8: return launch_one<T, 8>(a, s);
+    case 9: return launch_one<T, 9>(a, s);
+    case 12: return launch_one<T, 12>(a, s);
+    case 13: return launch_one<T, 13>(a, s);
+    case 16: return launch_one<T, 16>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template hipError_t launch_layer<float>(const LayerArgs<float> &, int, hipStream_t);
+template hipError_t launch_layer<double>(const LayerArgs<double> &, int, hipStream_t);
+
+}  // namespace ctm

@@ -1,0 +1,111 @@
+// Small bandwidth-bound kernels around the stacked GEMM: seeding the input coefficient
+// block, re-packing weights at handle creation, and the last (width-1) linear layer.
+#include "ctm_internal.h"
+
+namespace ctm {
+
+// ---- input jets (Sec. 3.1: x_{0,r} = x_0, x_{1,r} = v_r, x_{k>=2,r} = 0) ---------------
+// Row c of point n:  c = 0 -> x_n ; first-order rows -> v_r ; every other row -> 0.
+// order 2: rows 1..R are first order.  order 4: rows 1+3r are first order, 2+3r and 3+3r are
+// the (zero) second and third order coefficients of direction r.
+template <typename T> __global__ void seed_kernel(const SeedArgs<T> a) {
+  const long total = a.N * a.rho * a.ld;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(i % a.ld);
+    const long m = i / a.ld;
+    const int c = (int)(m % a.rho);
+    const long n = m / a.rho;
+    T v = T(0);
+    if (k < a.D) {
+      if (c == 0) {
+        v = a.x[n * a.D + k];
+      } else if (c < a.rho - 1) {
+        int r = -1;
+        if (a.order == 2) r = c - 1;
+        else if ((c - 1) % 3 == 0) r = (c - 1) / 3;
+        if (r >= 0) {
+          r += a.r0;
+          v = a.V ? a.V[n * a.v_sn + r * a.v_sr + k * a.v_sd] : (k == r ? T(1) : T(0));
+        }
+      }
+    }
+    a.out[i] = v;
+  }
+}
+
+template <typename T> hipError_t launch_seed(const SeedArgs<T> &a, hipStream_t s) {
+  const long total = a.N * a.rho * a.ld;
+  long blocks = (total + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(seed_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+template hipError_t launch_seed<float>(const SeedArgs<float> &, hipStream_t);
+template hipError_t launch_seed<double>(const SeedArgs<double> &, hipStream_t);
+
+// ---- weights: [d_out][d_in] -> zero-padded [rows_pad][ld]; bias -> [rows_pad] ---------------
+template <typename T>
+__global__ void pack_kernel(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad, int ld) {
+  const long total = (long)rows_pad * ld;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(i % ld);
+    const int j = (int)(i / ld);
+    Wp[i] = (j < d_out && k < d_in) ? W[(long)j * d_in + k] : T(0);
+    if (k == 0) bp[j] = (b != nullptr && j < d_out) ? b[j] : T(0);
+  }
+}
+
+template <typename T>
+hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad, int ld, hipStream_t s) {
+  const long total = (long)rows_pad * ld;
+  long blocks = (total + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(pack_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, W, b, d_out, d_in, Wp, bp, rows_pad, ld);
+  return hipGetLastError();
+}
+template hipError_t launch_pack<float>(const float *, const float *, int, int, float *, float *, int, int, hipStream_t);
+template hipError_t launch_pack<double>(const double *, const double *, int, int, double *, double *, int, int, hipStream_t);
+
+// ---- last layer (App. H: g is linear, bias on the 0-th coefficient only) ------------------
+//   u_n = w . h_0(n) + b        op_n = scale * (w . h_K(n))
+// One wavefront per point; lanes stride the features and the 64 partial sums are folded
+// with a fixed butterfly, so the result does not depend on scheduling.
+template <typename T> __global__ __launch_bounds__(256) void final_kernel(const FinalArgs<T> a) {
+  const int lane = threadIdx.x & 63;
+  const long n = blockIdx.x * 4L + (threadIdx.x >> 6);
+  if (n >= a.N) return;
+  const T *h0 = a.pair + n * 2 * a.ld;
+  const T *hk = h0 + a.ld;
+  T s0 = T(0), sk = T(0);
+  for (int k = lane; k < a.ld; k += 64) {
+    const T w = a.w[k];
+    s0 += w * h0[k];
+    sk += w * hk[k];
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    s0 += __shfl_xor(s0, off, 64);
+    sk += __shfl_xor(sk, off, 64);
+  }
+  if (lane == 0) {
+    const T opv = (T)(a.scale * (double)sk);
+    if (a.accumulate) {
+      if (a.op) a.op[n] += opv;
+    } else {
+      if (a.u) a.u[n] = s0 + a.b[0];
+      if (a.op) a.op[n] = opv;
+    }
+  }
+}
+
+template <typename T> hipError_t launch_final(const FinalArgs<T> &a, hipStream_t s) {
+  const long blocks = (a.N + 3) / 4;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(final_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+template hipError_t launch_final<float>(const FinalArgs<float> &, hipStream_t);
+template hipError_t launch_final<double>(const FinalArgs<double> &, hipStream_t);
+
+}  // namespace ctm

@@ -1,0 +1,51 @@
+"""Shared by the GPU parity tests, the smoke check and the benchmark: run one workload
+through the C-ABI binding, and through the CPU oracle."""
+import numpy as np
+
+
+def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None):
+    """arrs: dict from synth.Workload.build() (numpy).  Returns (u, op) as fp64 numpy arrays."""
+    import torch
+
+    import paper_2505_13644_amd as ctm
+
+    dev = torch.device("cuda:0")
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    own = mlp is None
+    if own:
+        mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]],
+                                 ctm.CTM_ACT_TANH if act is None else act)
+    x = t(arrs["x"])
+    if op == "laplacian":
+        u, o = ctm.ctm_laplacian(mlp, x, t(arrs.get("V")), arrs.get("scale", 1.0))
+    elif op == "weighted_laplacian":
+        u, o = ctm.ctm_weighted_laplacian(mlp, x, t(arrs["sigma"]))
+    elif op == "biharmonic_rand":
+        u, o = ctm.ctm_biharmonic_rand(mlp, x, t(arrs["V"]))
+    else:
+        raise ValueError(op)
+    torch.cuda.synchronize()
+    res = (u.double().cpu().numpy(), o.double().cpu().numpy())
+    if return_mlp:
+        return res + (mlp,)
+    if own:
+        mlp.close()
+    return res
+
+
+def oracle_run(arrs, op, act="tanh", idx=None, mode="directional"):
+    """Oracle on the same arrays (optionally only the points in idx)."""
+    from oracle import operators as orc
+
+    sel = slice(None) if idx is None else np.asarray(idx)
+    x = arrs["x"][sel]
+    V = arrs.get("V")
+    if V is not None and V.ndim == 3:
+        V = V[sel]
+    if op == "laplacian":
+        return orc.laplacian(arrs["Ws"], arrs["bs"], x, V, arrs.get("scale", 1.0), act=act, mode=mode)
+    if op == "weighted_laplacian":
+        return orc.weighted_laplacian(arrs["Ws"], arrs["bs"], x, arrs["sigma"], act=act, mode=mode)
+    if op == "biharmonic_rand":
+        return orc.biharmonic_rand(arrs["Ws"], arrs["bs"], x, V, act=act)
+    raise ValueError(op)

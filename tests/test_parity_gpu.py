@@ -1,0 +1,247 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by
+element on identical seeded inputs.  Error metric (pass/fail): max_n |gpu_n - ref_n| / max_n |ref_n|.
+Bars: fp64 <= 1e-5 (tightened here to 1e-10, the arithmetic allows it), fp32 <= 2e-4.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2505_13644_amd import synth
+from helpers import gpu_run, oracle_run
+
+pytestmark = pytest.mark.gpu
+
+TOL32 = 2e-4
+TOL64 = 1e-10
+
+
+def err(got, ref):
+    from oracle.operators import scaled_max_err
+    return scaled_max_err(got, ref)
+
+
+def check(got, ref, tol, what):
+    gu, go = got
+    ru, ro = ref
+    eu, eo = err(gu, ru), err(go, ro)
+    print(f"[{what}] scaled max err: u {eu:.3e}  op {eo:.3e}  (tol {tol:g}; max|op| {np.max(np.abs(ro)):.3e})", flush=True)
+    assert np.all(np.isfinite(gu)) and np.all(np.isfinite(go))
+    assert eu <= tol, f"{what}: u error {eu}"
+    assert eo <= tol, f"{what}: op error {eo}"
+
+
+def tol_of(dtype):
+    return TOL64 if dtype == np.float64 else TOL32
+
+
+# ---------------------------------------------------------------------------
+# the five named workloads
+# ---------------------------------------------------------------------------
+def test_c1_exact_laplacian_fp64_full():
+    w = synth.WORKLOADS["c1"]
+    arrs = w.build()
+    print("case c1 N=8 fp64", flush=True)
+    got = gpu_run(arrs, w.op)
+    check(got, oracle_run(arrs, w.op, mode="hessian"), TOL64, "c1 hessian")
+    check(got, oracle_run(arrs, w.op, mode="directional"), TOL64, "c1 directional")
+    assert TOL64 <= w.tol
+
+
+@pytest.mark.parametrize("name,N", [("c2", 37), ("c3", 45), ("c4", 50), ("c5", 23)])
+def test_named_workloads_reduced_batch(name, N):
+    # same network, directions and dtype as the named workload, batch cut so that the oracle takes
+    # seconds; N is chosen to span several tiles and leave a ragged last tile
+    w = synth.WORKLOADS[name]
+    arrs = w.build(N)
+    print(f"case {name} N={N}", flush=True)
+    got = gpu_run(arrs, w.op)
+    check(got, oracle_run(arrs, w.op), w.tol, f"{name} N={N}")
+    if name == "c2":
+        idx = [0, 17, 36]
+        ref_h = oracle_run(arrs, w.op, idx=idx, mode="hessian")
+        check((got[0][idx], got[1][idx]), ref_h, w.tol, "c2 full-Hessian trace")
+
+
+@pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c3", 48), ("c4", 64), ("c5", 48)])
+def test_named_workloads_full_size_sampled(name, n_sample):
+    # the launch configuration the benchmark times; the oracle checks a seeded sample of points
+    w = synth.WORKLOADS[name]
+    arrs = w.build()
+    print(f"case {name} full N={w.N}", flush=True)
+    gu, go, mlp = gpu_run(arrs, w.op, return_mlp=True)
+    idx = np.sort(np.random.default_rng(123).choice(w.N, n_sample, replace=False))
+    idx[0], idx[-1] = 0, w.N - 1
+    ru, ro = oracle_run(arrs, w.op, idx=idx)
+    # the sample's scale stands in for the batch's
+    check((gu[idx], go[idx]), (ru, ro), w.tol, f"{name} full-size sample")
+    assert np.all(np.isfinite(go)) and np.all(np.isfinite(gu))
+    # properties that hold at any size: run-to-run bitwise determinism, and every point's
+    # result is independent of the rest of the batch (bitwise, since no row mixes points)
+    gu2, go2 = gpu_run(arrs, w.op, mlp=mlp)
+    assert np.array_equal(gu, gu2) and np.array_equal(go, go2)
+    sub = dict(arrs)
+    sub["x"] = arrs["x"][idx]
+    if arrs.get("V") is not None and arrs["V"].ndim == 3:
+        sub["V"] = arrs["V"][idx]
+    su, so = gpu_run(sub, w.op, mlp=mlp)
+    assert np.array_equal(su, gu[idx]) and np.array_equal(so, go[idx])
+    mlp.close()
+
+
+# ---------------------------------------------------------------------------
+# shapes that stress tiling: odd widths, one hidden layer, N = 1, R = 1, many directions
+# ---------------------------------------------------------------------------
+def small_case(dims, N, dtype, seed, R=None, kind="gaussian", per_point=True, bias=0.1):
+    Ws, bs = synth.make_mlp(dims, seed, bias, dtype)
+    arrs = {"Ws": Ws, "bs": bs, "x": synth.make_points(N, dims[0], seed, dtype)}
+    if R is None:
+        arrs["V"], arrs["scale"] = None, 1.0
+    else:
+        shape = (N, R, dims[0]) if per_point else (R, dims[0])
+        arrs["V"], arrs["scale"] = synth.make_directions(kind, shape, seed, dtype), 1.0 / R
+    return arrs
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,R,per_point", [
+    ((7, 33, 65, 1), 19, None, False),     # widths that are no multiple of anything
+    ((3, 100, 1), 130, None, False),       # one hidden layer
+    ((5, 16, 16, 1), 1, None, False),      # a single point
+    ((6, 40, 24, 1), 11, 1, True),         # a single direction
+    ((6, 40, 24, 1), 70, 9, False),        # shared directions [R, D]
+    ((4, 48, 48, 48, 1), 33, 21, True),    # per-point directions
+    ((50, 96, 1), 9, 150, False),          # more rows per point than half a tile
+])
+def test_laplacian_shapes(dtype, dims, N, R, per_point):
+    arrs = small_case(dims, N, dtype, seed=len(dims) + N, R=R, per_point=per_point)
+    print(f"case laplacian dims={dims} N={N} R={R} per_point={per_point} {dtype.__name__}", flush=True)
+    check(gpu_run(arrs, "laplacian"), oracle_run(arrs, "laplacian"), tol_of(dtype), f"laplacian {dims}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("R", [300, 255, 509])
+def test_laplacian_direction_set_split_over_passes(dtype, R):
+    # more directions than fit one tile: several passes whose partial sums are added
+    dims, N = (6, 24, 16, 1), 21
+    arrs = small_case(dims, N, dtype, seed=R, R=R, per_point=False)
+    print(f"case multi-pass R={R} {dtype.__name__}", flush=True)
+    check(gpu_run(arrs, "laplacian"), oracle_run(arrs, "laplacian"), tol_of(dtype), f"multi-pass R={R}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,K", [((9, 50, 30, 1), 40, 4), ((50, 64, 64, 1), 17, 50), ((5, 16, 1), 3, 1)])
+def test_weighted_laplacian_shapes(dtype, dims, N, K):
+    Ws, bs = synth.make_mlp(dims, 3, 0.1, dtype)
+    arrs = {"Ws": Ws, "bs": bs, "x": synth.make_points(N, dims[0], 3, dtype), "sigma": synth.make_sigma(dims[0], K, 3, dtype)}
+    print(f"case weighted dims={dims} N={N} K={K} {dtype.__name__}", flush=True)
+    got = gpu_run(arrs, "weighted_laplacian")
+    check(got, oracle_run(arrs, "weighted_laplacian", mode="hessian"), tol_of(dtype), f"weighted {dims} K={K}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,S,per_point", [
+    ((10, 64, 32, 1), 37, 5, True),
+    ((3, 20, 1), 9, 1, True),
+    ((4, 32, 32, 32, 1), 50, 12, False),
+    ((5, 24, 16, 1), 6, 100, False),       # S above the per-tile limit of 84: two passes
+])
+def test_biharmonic_shapes(dtype, dims, N, S, per_point):
+    arrs = small_case(dims, N, dtype, seed=S, R=S, per_point=per_point, bias=0.05)
+    print(f"case biharmonic dims={dims} N={N} S={S} {dtype.__name__}", flush=True)
+    check(gpu_run(arrs, "biharmonic_rand"), oracle_run(arrs, "biharmonic_rand"), tol_of(dtype), f"biharmonic {dims} S={S}")
+
+
+# ---------------------------------------------------------------------------
+# properties and special cases
+# ---------------------------------------------------------------------------
+def test_one_hidden_layer_closed_form_on_gpu():
+    # u = sum_j a_j tanh(w_j.x + b_j) + c  =>  Lap u = sum_j a_j |w_j|^2 tanh''(z_j),
+    # <d^4 u, v^4> = sum_j a_j (w_j.v)^4 tanh''''(z_j)   (special case of the App. H scheme)
+    dims, N, S = (6, 40, 1), 25, 3
+    arrs = small_case(dims, N, np.float64, 77, R=S, per_point=True)
+    W1, a = arrs["Ws"]
+    b1, c = arrs["bs"]
+    x, V = arrs["x"], arrs["V"]
+    z = x @ W1.T + b1
+    t = np.tanh(z)
+    s = 1 - t * t
+    d2, d4 = -2 * t * s, 16 * t * s * s - 8 * t ** 3 * s
+    lap = dict(arrs, V=None, scale=1.0)
+    gu, go = gpu_run(lap, "laplacian")
+    np.testing.assert_allclose(gu, t @ a[0] + c[0], rtol=1e-12)
+    np.testing.assert_allclose(go, (d2 * (W1 ** 2).sum(1)) @ a[0], rtol=1e-10, atol=1e-13)
+    _, gb = gpu_run(arrs, "biharmonic_rand")
+    wv = np.einsum("id,nsd->nsi", W1, V)
+    np.testing.assert_allclose(gb, np.einsum("nsi,ni,i->n", wv ** 4, d4, a[0]) / (3 * S), rtol=1e-10, atol=1e-13)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_identity_activation_gives_exactly_zero(dtype):
+    import paper_2505_13644_amd as ctm
+    arrs = small_case((5, 16, 16, 1), 13, dtype, 5, R=4, per_point=True)
+    gu, go = gpu_run(arrs, "laplacian", act=ctm.CTM_ACT_IDENTITY)
+    ru, ro = oracle_run(arrs, "laplacian", act="identity")
+    assert np.all(go == 0.0) and np.all(ro == 0.0)
+    assert err(gu, ru) <= (1e-12 if dtype == np.float64 else 1e-5)
+    _, gb = gpu_run(arrs, "biharmonic_rand", act=ctm.CTM_ACT_IDENTITY)
+    assert np.all(gb == 0.0)
+
+
+def test_collapsed_sum_equals_sum_of_single_direction_calls():
+    # Sec. 3.1: propagating the sum equals summing R separately propagated jets
+    arrs = small_case((6, 32, 32, 1), 20, np.float64, 9, R=5, per_point=True)
+    _, full = gpu_run(dict(arrs, scale=1.0), "laplacian")
+    parts = sum(gpu_run(dict(arrs, V=np.ascontiguousarray(arrs["V"][:, r:r + 1]), scale=1.0), "laplacian")[1] for r in range(5))
+    np.testing.assert_allclose(full, parts, rtol=1e-11, atol=1e-13)
+    _, full4 = gpu_run(arrs, "biharmonic_rand")
+    parts4 = sum(gpu_run(dict(arrs, V=np.ascontiguousarray(arrs["V"][:, r:r + 1])), "biharmonic_rand")[1] for r in range(5)) / 5
+    np.testing.assert_allclose(full4, parts4, rtol=1e-10, atol=1e-13)
+
+
+def test_basis_and_sigma_special_cases_agree():
+    dims, N = (8, 40, 24, 1), 15
+    arrs = small_case(dims, N, np.float64, 4)
+    _, exact = gpu_run(arrs, "laplacian")
+    eye = np.eye(8)
+    _, via_v = gpu_run(dict(arrs, V=eye, scale=1.0), "laplacian")
+    _, via_sigma = gpu_run(dict(arrs, sigma=eye), "weighted_laplacian")
+    Q, _ = np.linalg.qr(np.random.default_rng(0).standard_normal((8, 8)))
+    _, rotated = gpu_run(dict(arrs, V=np.ascontiguousarray(Q.T), scale=1.0), "laplacian")
+    np.testing.assert_array_equal(exact, via_v)
+    np.testing.assert_array_equal(exact, via_sigma)
+    np.testing.assert_allclose(rotated, exact, rtol=1e-10, atol=1e-12)
+
+
+def test_errors_from_the_library_with_a_live_handle():
+    import torch
+    import paper_2505_13644_amd as ctm
+    from paper_2505_13644_amd import binding as B
+    arrs = small_case((5, 16, 16, 1), 8, np.float32, 1)
+    dev = torch.device("cuda:0")
+    mlp = ctm.ctm_create_mlp([torch.from_numpy(W).to(dev) for W in arrs["Ws"]], None)
+    x = torch.from_numpy(arrs["x"]).to(dev)
+    u = torch.empty(8, device=dev)
+    need = ctm.ctm_workspace_bytes(mlp, 2, 8, 5)
+    ws = torch.empty(need + 256, dtype=torch.uint8, device=dev)
+    L = B.lib()
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.ctm_laplacian(mlp.handle, p(x), 8, None, 4, 0, 1.0, p(u), p(u), p(ws), need, st) == -2   # basis needs R = D
+    assert L.ctm_laplacian(mlp.handle, p(x), 8, p(x), 5, 7, 1.0, p(u), p(u), p(ws), need, st) == -2   # bad stride
+    assert L.ctm_laplacian(mlp.handle, p(x), 0, None, 5, 0, 1.0, p(u), p(u), p(ws), need, st) == -2
+    assert L.ctm_laplacian(mlp.handle, p(x), 8, None, 5, 0, 1.0, p(u), p(u), p(ws), need - 1, st) == -5
+    assert "workspace" in ctm.ctm_last_error()
+    assert L.ctm_laplacian(mlp.handle, p(x), 8, None, 5, 0, 1.0, p(u), p(u), ctypes.c_void_p(ws.data_ptr() + 4), need, st) == -6
+    assert L.ctm_laplacian(mlp.handle, None, 8, None, 5, 0, 1.0, p(u), p(u), p(ws), need, st) == -1
+    assert L.ctm_biharmonic_rand(mlp.handle, p(x), 8, None, 5, 0, p(u), p(u), p(ws), need, st) == -1
+    assert L.ctm_weighted_laplacian(mlp.handle, p(x), 8, None, 5, p(u), p(u), p(ws), need, st) == -1
+    # u or op may be left out
+    op = torch.full((8,), 7.0, device=dev)
+    assert L.ctm_laplacian(mlp.handle, p(x), 8, None, 5, 0, 1.0, None, p(op), p(ws), need, st) == 0
+    torch.cuda.synchronize()
+    ref = oracle_run({"Ws": arrs["Ws"], "bs": [np.zeros_like(b) for b in arrs["bs"]], "x": arrs["x"], "V": None}, "laplacian")
+    assert err(op.double().cpu().numpy(), ref[1]) <= TOL32
+    with pytest.raises(ValueError):
+        ctm.ctm_laplacian(mlp, x[:, :4].contiguous())
+    mlp.close()
