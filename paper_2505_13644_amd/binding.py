@@ -56,6 +56,10 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_13644_amd.build`")
+        # PyTorch ships its own copy of the HIP runtime.  Import it first so that libctm.so binds to
+        # that copy (same soname) and both see the same device context; two runtimes in one
+        # process do not share devices or allocations.
+        _torch()
         handle = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(handle, name)

@@ -19,7 +19,8 @@
 // (point, feature) pair, keeping the running sums in registers.
 //
 // MFMA use: v_mfma_{f32,f64}_16x16x4.  Lane l supplies A[row l%16][k l/16] and
-// B[k l/16][col l%16] and receives D[rows 4*(l/16)..+3][col l%16].  Each lane fetches KV
+// B[k l/16][col l%16]; it receives four elements of column l%16 of D, in rows
+// 4*(l/16) + v for f32 and 4*v + l/16 for f64 (v = register index).  Each lane fetches KV
 // consecutive k values with one 16-byte LDS read and feeds them to KV successive MFMAs; since
 // A and B use the same assignment, the k-sum is merely taken in a permuted order.
 #include "ctm_internal.h"
@@ -34,10 +35,12 @@ template <typename T> struct Vec;
 template <> struct Vec<float> {
   using ld = f32x4;   // 16-byte load unit
   using acc = f32x4;  // one 16x16 MFMA block: 4 rows per lane
+  static __device__ __forceinline__ int out_row(int lane_group, int v) { return lane_group * 4 + v; }
 };
 template <> struct Vec<double> {
   using ld = f64x2;
   using acc = f64x4;
+  static __device__ __forceinline__ int out_row(int lane_group, int v) { return v * 4 + lane_group; }
 };
 
 __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(const LayerArgs<T> a) {
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        Cs[(mb * 16 + lg * 4 + v) * CROW + wave * 16 * NB + nb * 16 + lr] = acc[mb][nb][v];
+        Cs[(mb * 16 + Vec<T>::out_row(lg, v)) * CROW + wave * 16 * NB + nb * 16 + lr] = acc[mb][nb][v];
   __syncthreads();
 
   // ---- collapsed jet rule: one thread per (point, feature) pair, rows walked in order
