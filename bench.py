@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", help="c1..c5 (c2 is the configuration the metric is quoted on)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 skips it")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (points are independent, nothing is exchanged); use --gpus 1")
@@ -93,6 +95,13 @@ def main():
             ctm.ctm_weighted_laplacian(mlp, x, sigma, u, op, ws)
         else:
             ctm.ctm_biharmonic_rand(mlp, x, V, u, op, ws)
+
+    if args.copy_probe_mib > 0:
+        src = torch.ones(args.copy_probe_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -77,8 +77,13 @@ template <typename T, int MB> struct Tile {
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
 };
 
+// amdgpu_waves_per_eu(2, 2) caps the kernel at 256 registers per lane.  With the cap the compiler
+// keeps the accumulators in ordinary VGPRs and issues MFMAs on them directly; without it (512
+// registers allowed) it parks them in AGPRs and copies each block back and forth around every
+// MFMA group, which left the matrix pipe idle almost half of the time.
 template <typename T, int MB>
-__global__ __launch_bounds__(kThreads) void layer_kernel(const LayerArgs<T> a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void layer_kernel(const LayerArgs<T> a) {
   using TL = Tile<T, MB>;
   using vld = typename Vec<T>::ld;
   using vacc = typename Vec<T>::acc;
@@ -114,45 +119,44 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(const LayerArgs<T> a) {
   const T *Ag = a.Hin + p0 * a.rho * (long)a.ldin;
   const T *Bg = a.W + (long)col_tile * BN * a.ldin;
 
-  // ---- per-thread global->LDS copy slots (16 bytes each)
-  int a_off[TL::A_LD];      // element offset inside an LDS stage, or -1
-  long a_goff[TL::A_LD];    // element offset from Ag
-  bool a_ok[TL::A_LD];
+  // ---- per-thread global->LDS copy slots (16 bytes each).  Every slot is loaded and stored
+  // unconditionally, so the k loop has no branches and the loads stay in flight across the
+  // MFMAs: a slot past the end of the tile repeats the tile's last slot (same value to the same
+  // LDS address), and a row past the tile's last valid row re-reads that last valid row.  Such
+  // rows only feed accumulator rows the epilogue never looks at (MFMA rows do not mix).
+  int a_off[TL::A_LD];
+  const T *a_src[TL::A_LD];
 #pragma unroll
   for (int i = 0; i < TL::A_LD; ++i) {
-    const int u = tid + i * kThreads;
+    int u = tid + i * kThreads;
+    u = u < TL::BM * UPR ? u : TL::BM * UPR - 1;
     const int row = u / UPR, kq = u % UPR;
-    a_off[i] = (u < TL::BM * UPR) ? row * LROW + kq * KV : -1;
-    a_ok[i] = (u < TL::BM * UPR) && (row < rows_valid);
-    a_goff[i] = (long)row * a.ldin + kq * KV;
+    a_off[i] = row * LROW + kq * KV;
+    const int grow = row < rows_valid ? row : rows_valid - 1;
+    a_src[i] = Ag + (long)grow * a.ldin + kq * KV;
   }
   int b_off[TL::B_LD];
-  long b_goff[TL::B_LD];
+  const T *b_src[TL::B_LD];
 #pragma unroll
   for (int i = 0; i < TL::B_LD; ++i) {
     const int u = tid + i * kThreads;
     const int row = u / UPR, kq = u % UPR;
     b_off[i] = row * LROW + kq * KV;
-    b_goff[i] = (long)row * a.ldin + kq * KV;
+    b_src[i] = Bg + (long)row * a.ldin + kq * KV;
   }
 
   vld a_reg[TL::A_LD], b_reg[TL::B_LD];
   auto load_global = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) {
-      vld v = {};
-      if (a_ok[i]) v = *reinterpret_cast<const vld *>(Ag + a_goff[i] + k0);
-      a_reg[i] = v;
-    }
+    for (int i = 0; i < TL::A_LD; ++i) a_reg[i] = *reinterpret_cast<const vld *>(a_src[i] + k0);
 #pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) b_reg[i] = *reinterpret_cast<const vld *>(Bg + b_goff[i] + k0);
+    for (int i = 0; i < TL::B_LD; ++i) b_reg[i] = *reinterpret_cast<const vld *>(b_src[i] + k0);
   };
   auto store_lds = [&](int stage) {
     T *Ad = As + stage * TL::A_STAGE;
     T *Bd = Bs + stage * TL::B_STAGE;
 #pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i)
-      if (a_off[i] >= 0) *reinterpret_cast<vld *>(Ad + a_off[i]) = a_reg[i];
+    for (int i = 0; i < TL::A_LD; ++i) *reinterpret_cast<vld *>(Ad + a_off[i]) = a_reg[i];
 #pragma unroll
     for (int i = 0; i < TL::B_LD; ++i) *reinterpret_cast<vld *>(Bd + b_off[i]) = b_reg[i];
   };
@@ -174,19 +178,33 @@ __global__ __launch_bounds__(kThreads) void layer_kernel(const LayerArgs<T> a) {
 
     const T *Ac = As + stage * TL::A_STAGE + lr * LROW + lg * KV;
     const T *Bc = Bs + stage * TL::B_STAGE + (wave * 16 * NB + lr) * LROW + lg * KV;
+    // One step = one A fragment (16 rows x KV k-values per lane) against the NB B fragments of its
+    // k-group.  The A fragment of step s+1 is fetched from LDS before the MFMAs of step s are
+    // issued, so the LDS latency hides behind NB*KV MFMAs instead of stalling each step.
+    constexpr int NKG = BK / (4 * KV);
+    constexpr int STEPS = NKG * MB;
+    vld bf[2][NB], af[2];
 #pragma unroll
-    for (int kg = 0; kg < BK / (4 * KV); ++kg) {
-      vld bf[NB];
+    for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Bc + nb * 16 * LROW);
+    af[0] = *reinterpret_cast<const vld *>(Ac);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vld *>(Bc + nb * 16 * LROW + kg * 4 * KV);
+    for (int st = 0; st < STEPS; ++st) {
+      const int kg = st / MB, mb = st % MB;
+      if (st + 1 < STEPS) {
+        const int kg1 = (st + 1) / MB, mb1 = (st + 1) % MB;
+        af[(st + 1) & 1] = *reinterpret_cast<const vld *>(Ac + mb1 * 16 * LROW + kg1 * 4 * KV);
+        if (mb == 0 && kg + 1 < NKG) {
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        const vld af = *reinterpret_cast<const vld *>(Ac + mb * 16 * LROW + kg * 4 * KV);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-          for (int j = 0; j < KV; ++j) acc[mb][nb] = mfma16(af[j], bf[nb][j], acc[mb][nb]);
+          for (int nb = 0; nb < NB; ++nb)
+            bf[(kg + 1) & 1][nb] = *reinterpret_cast<const vld *>(Bc + nb * 16 * LROW + (kg + 1) * 4 * KV);
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's MFMAs
+#pragma unroll
+      for (int j = 0; j < KV; ++j)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma16(af[st & 1][j], bf[kg & 1][nb][j], acc[mb][nb]);
+      __builtin_amdgcn_sched_barrier(0);
     }
 
     if (kt + 1 < nk) store_lds(stage ^ 1);  // the other stage was last read before the previous barrier
