@@ -9,11 +9,11 @@ namespace ctm {
 
 // Shape constants of the stacked-GEMM kernel, per storage type.
 //   KV  elements per 16-byte LDS/global vector
-//   BK  K-extent of one LDS stage; BK * sizeof(T) = 128 bytes for both types
+//   BK  K-extent of one LDS stage
 //   NB  16-column MFMA blocks per wave; a workgroup has 4 waves side by side
 template <typename T> struct Shape;
 template <> struct Shape<float> {
-  static constexpr int KV = 4, BK = 32, NB = 2;
+  static constexpr int KV = 4, BK = 16, NB = 2;
 };
 template <> struct Shape<double> {
   static constexpr int KV = 2, BK = 16, NB = 1;

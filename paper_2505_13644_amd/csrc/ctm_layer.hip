@@ -15,8 +15,10 @@
 // (row 0: order 0; then the per-direction rows; last row: the collapsed one), each row
 // `ld` elements with zero padding.  A workgroup owns P whole points (P*rho <= 16*MB rows)
 // times 64*NB output features, so the sum over directions never leaves the workgroup:
-// the accumulators are staged through LDS once and each thread then walks the rows of one
-// (point, feature) pair, keeping the running sums in registers.
+// the accumulators are staged through LDS (64 columns at a time) and each thread then walks
+// the rows of one (point, feature) pair, keeping the running sums in registers.
+// LDS per workgroup stays below 80 KiB for fp32 so that two workgroups share a CU and one's
+// epilogue, barriers and first loads overlap with the other's MFMAs.
 //
 // MFMA use: v_mfma_{f32,f64}_16x16x4.  Lane l supplies A[row l%16][k l/16] and
 // B[k l/16][col l%16]; it receives four elements of column l%16 of D, in rows
@@ -69,7 +71,8 @@ template <typename T, int MB> struct Tile {
   static constexpr int B_STAGE = BN * LROW;
   static constexpr int A_LD = (BM * UPR + kThreads - 1) / kThreads;
   static constexpr int B_LD = (BN * UPR) / kThreads;
-  static constexpr int CROW = BN + PADE;          // LDS row pitch of the staged C tile
+  static constexpr int CCOLS = 64;                // the C tile is staged 64 columns at a time
+  static constexpr int CROW = CCOLS + PADE;       // LDS row pitch of the staged C chunk
   static constexpr size_t kStageBytes = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(T);
   static constexpr size_t kCBytes = (size_t)BM * CROW * sizeof(T);
   static constexpr size_t kLdsBytes = kStageBytes > kCBytes ? kStageBytes : kCBytes;
@@ -94,7 +97,7 @@ void layer_kernel(const LayerArgs<T> a) {
   T *lds = reinterpret_cast<T *>(lds_raw);
   T *As = lds;                      // [2][A_STAGE]
   T *Bs = lds + 2 * TL::A_STAGE;    // [2][B_STAGE]
-  T *Cs = lds;                      // [BM][CROW], reuses the stages after the k loop
+  T *Cs = lds;                      // [BM][CROW] chunk of the C tile, reuses the stages after the k loop
 
   // ---- which tile: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
   // Give every XCD one contiguous run of tiles, ordered so that the column tiles of one
@@ -177,7 +180,7 @@ void layer_kernel(const LayerArgs<T> a) {
     if (kt + 1 < nk) load_global((kt + 1) * BK);  // in flight while this stage is consumed
 
     const T *Ac = As + stage * TL::A_STAGE + lr * LROW + lg * KV;
-    const T *Bc = Bs + stage * TL::B_STAGE + (wave * 16 * NB + lr) * LROW + lg * KV;
+    const T *Bc = Bs + stage * TL::B_STAGE + (wave * 16 + lr) * LROW + lg * KV;  // + nb * 64 rows
     // One step = one A fragment (16 rows x KV k-values per lane) against the NB B fragments of its
     // k-group.  The A fragment of step s+1 is fetched from LDS before the MFMAs of step s are
     // issued, so the LDS latency hides behind NB*KV MFMAs instead of stalling each step.
@@ -185,7 +188,7 @@ void layer_kernel(const LayerArgs<T> a) {
     constexpr int STEPS = NKG * MB;
     vld bf[2][NB], af[2];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Bc + nb * 16 * LROW);
+    for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Bc + nb * 64 * LROW);
     af[0] = *reinterpret_cast<const vld *>(Ac);
 #pragma unroll
     for (int st = 0; st < STEPS; ++st) {
@@ -196,7 +199,7 @@ void layer_kernel(const LayerArgs<T> a) {
         if (mb == 0 && kg + 1 < NKG) {
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
-            bf[(kg + 1) & 1][nb] = *reinterpret_cast<const vld *>(Bc + nb * 16 * LROW + (kg + 1) * 4 * KV);
+            bf[(kg + 1) & 1][nb] = *reinterpret_cast<const vld *>(Bc + nb * 64 * LROW + (kg + 1) * 4 * KV);
         }
       }
       __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's MFMAs
@@ -211,74 +214,77 @@ void layer_kernel(const LayerArgs<T> a) {
     __syncthreads();
   }
 
-  // ---- stage the accumulators through LDS (all waves have passed the final barrier, so the
-  // k-loop stages are dead)
+  // ---- epilogue, 64 output columns at a time (wave w holds columns nb*64 + w*16 .. +15 of the
+  // tile in acc[.][nb]): stage that chunk of the accumulators through LDS, then apply the
+  // collapsed jet rule with one thread per (point, feature) pair, walking the point's rows in
+  // order.  All waves have passed the k loop's final barrier, so its stages are dead.
+  const int R = a.R, rho = a.rho;
+  const int j = tid & 63;
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
+  for (int nb = 0; nb < NB; ++nb) {
+    if (nb > 0) __syncthreads();  // the previous chunk has been consumed
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int v = 0; v < 4; ++v)
-        Cs[(mb * 16 + Vec<T>::out_row(lg, v)) * CROW + wave * 16 * NB + nb * 16 + lr] = acc[mb][nb][v];
-  __syncthreads();
+        Cs[(mb * 16 + Vec<T>::out_row(lg, v)) * CROW + wave * 16 + lr] = acc[mb][nb][v];
+    __syncthreads();
 
-  // ---- collapsed jet rule: one thread per (point, feature) pair, rows walked in order
-  const int j = tid % BN;
-  const long jg = (long)col_tile * BN + j;
-  if (jg >= a.ldout) return;  // no barrier follows
-  const T bias = a.bias[jg];
-  const int R = a.R, rho = a.rho;
-  for (int p = tid / BN; p < p_valid; p += kThreads / BN) {
-    const T *c = Cs + (long)p * rho * CROW + j;
-    const long n = p0 + p;
-    T *o = a.last ? a.Hout + (n * 2) * a.ldout + jg : a.Hout + (n * rho) * a.ldout + jg;
-    const long ostep = a.ldout;
-    const T z0 = c[0] + bias;
-    T t, d1, d2;
-    if (a.act == 0) {
-      t = act_tanh(z0);
-      d1 = T(1) - t * t;
-      d2 = T(-2) * t * d1;
-    } else {
-      t = z0;
-      d1 = T(1);
-      d2 = T(0);
-    }
-    o[0] = t;
-    if (a.order == 2) {
-      T s = T(0);
-      for (int r = 1; r <= R; ++r) {
-        const T z1 = c[(long)r * CROW];
-        s += z1 * z1;
-        if (!a.last) o[r * ostep] = d1 * z1;
-      }
-      const T z2 = c[(long)(R + 1) * CROW];
-      const T h2 = d1 * z2 + d2 * s;
-      o[(a.last ? 1 : R + 1) * ostep] = h2;
-    } else {
-      T d3, d4;
+    const long jg = (long)col_tile * BN + nb * 64 + j;
+    if (jg >= a.ldout) continue;  // uniform per wave; barriers are outside this branch
+    const T bias = a.bias[jg];
+    for (int p = wave; p < p_valid; p += kThreads / 64) {
+      const T *c = Cs + (long)p * rho * CROW + j;
+      const long n = p0 + p;
+      T *o = a.last ? a.Hout + (n * 2) * a.ldout + jg : a.Hout + (n * rho) * a.ldout + jg;
+      const long ostep = a.ldout;
+      const T z0 = c[0] + bias;
+      T t, d1, d2;
       if (a.act == 0) {
-        d3 = d1 * (T(6) * t * t - T(2));
-        d4 = T(8) * t * d1 * (T(2) - T(3) * t * t);
+        t = act_tanh(z0);
+        d1 = T(1) - t * t;
+        d2 = T(-2) * t * d1;
       } else {
-        d3 = T(0);
-        d4 = T(0);
+        t = z0;
+        d1 = T(1);
+        d2 = T(0);
       }
-      T s = T(0);
-      for (int r = 0; r < R; ++r) {
-        const T *cr = c + (long)(1 + 3 * r) * CROW;
-        const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW];
-        const T z1s = z1 * z1;
-        s += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
-        if (!a.last) {
-          T *orow = o + (long)(1 + 3 * r) * ostep;
-          orow[0] = d1 * z1;
-          orow[ostep] = d2 * z1s + d1 * z2;
-          orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+      o[0] = t;
+      if (a.order == 2) {
+        T s = T(0);
+        for (int r = 1; r <= R; ++r) {
+          const T z1 = c[(long)r * CROW];
+          s += z1 * z1;
+          if (!a.last) o[r * ostep] = d1 * z1;
         }
+        const T z2 = c[(long)(R + 1) * CROW];
+        const T h2 = d1 * z2 + d2 * s;
+        o[(a.last ? 1 : R + 1) * ostep] = h2;
+      } else {
+        T d3, d4;
+        if (a.act == 0) {
+          d3 = d1 * (T(6) * t * t - T(2));
+          d4 = T(8) * t * d1 * (T(2) - T(3) * t * t);
+        } else {
+          d3 = T(0);
+          d4 = T(0);
+        }
+        T s = T(0);
+        for (int r = 0; r < R; ++r) {
+          const T *cr = c + (long)(1 + 3 * r) * CROW;
+          const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW];
+          const T z1s = z1 * z1;
+          s += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
+          if (!a.last) {
+            T *orow = o + (long)(1 + 3 * r) * ostep;
+            orow[0] = d1 * z1;
+            orow[ostep] = d2 * z1s + d1 * z2;
+            orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+          }
+        }
+        const T z4 = c[(long)(3 * R + 1) * CROW];
+        o[(a.last ? 1 : 3 * R + 1) * ostep] = d1 * z4 + s;
       }
-      const T z4 = c[(long)(3 * R + 1) * CROW];
-      o[(a.last ? 1 : 3 * R + 1) * ostep] = d1 * z4 + s;
     }
   }
 }
