@@ -111,7 +111,7 @@ namespace {
 int tile_cols_of(ctm_dtype t) { return t == CTM_F64 ? tile_cols<double>() : tile_cols<float>(); }
 
 struct Layout {
-  size_t block_bytes, pair_bytes, total;
+  size_t block_bytes, pair_bytes, dirs_bytes, total;
 };
 Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
   const size_t es = elem_size(m->dtype);
@@ -120,7 +120,8 @@ Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
   Layout lo;
   lo.block_bytes = round256((size_t)N * (size_t)rows_per_point(K, Rpass) * (size_t)maxld * es);
   lo.pair_bytes = round256((size_t)N * 2 * (size_t)m->ld[m->L - 1] * es);
-  lo.total = 2 * lo.block_bytes + lo.pair_bytes;
+  lo.dirs_bytes = round256((size_t)(Rpass + 1) * (size_t)m->ld[1 < m->L ? 1 : 0] * es);  // W_1 v_r rows + moments
+  lo.total = 2 * lo.block_bytes + lo.pair_bytes + lo.dirs_bytes;
   return lo;
 }
 
@@ -131,20 +132,41 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
   const Layout lo = workspace_layout(m, K, N, sp.first);
   T *buf[2] = {reinterpret_cast<T *>(ws), reinterpret_cast<T *>((char *)ws + lo.block_bytes)};
   T *pair = reinterpret_cast<T *>((char *)ws + 2 * lo.block_bytes);
+  T *dirs = reinterpret_cast<T *>((char *)ws + 2 * lo.block_bytes + lo.pair_bytes);
   const int L = m->L;
   if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
   for (int pass = 0; pass < sp.n_passes; ++pass) {
     const int Rp = (pass == sp.n_passes - 1) ? sp.lastR : sp.first;
     const PassPlan pl = plan_pass(K, Rp);
-    SeedArgs<T> sa;
-    sa.x = x; sa.V = V; sa.out = buf[1]; sa.N = N;
-    sa.v_sn = sn; sa.v_sr = sr; sa.v_sd = sd;
-    sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = pass * sp.first;
-    hipError_t e = launch_seed<T>(sa, st);
-    if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
-    (void)prof_mark(st, 0);
+    const bool fast_first = first_layer_fast_path(m->dims[0], sn);
     const T *in = buf[1];
-    for (int l = 0; l + 1 < L; ++l) {
+    int l_begin = 0;
+    hipError_t e;
+    if (fast_first) {
+      // shared directions: the first layer is written directly, without a seed block or a GEMM
+      const bool last = (L == 2);
+      FirstArgs<T> fa;
+      fa.x = x; fa.V = V; fa.W = (const T *)m->Wp[0]; fa.bias = (const T *)m->bp[0];
+      fa.Z1 = dirs; fa.mom = dirs + (size_t)Rp * m->ld[1];
+      fa.out = last ? pair : buf[0];
+      fa.N = N; fa.v_sr = sr; fa.v_sd = sd;
+      fa.D = m->dims[0]; fa.ld0 = m->ld[0]; fa.ld1 = m->ld[1]; fa.rho = pl.rho; fa.order = K; fa.R = Rp;
+      fa.r0 = pass * sp.first; fa.last = last ? 1 : 0; fa.act = (int)m->act;
+      e = launch_first<T>(fa, st);
+      if (e != hipSuccess) return fail_hip(e, "first-layer kernel launch");
+      (void)prof_mark(st, 0);
+      in = fa.out;
+      l_begin = 1;
+    } else {
+      SeedArgs<T> sa;
+      sa.x = x; sa.V = V; sa.out = buf[1]; sa.N = N;
+      sa.v_sn = sn; sa.v_sr = sr; sa.v_sd = sd;
+      sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = pass * sp.first;
+      e = launch_seed<T>(sa, st);
+      if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
+      (void)prof_mark(st, 0);
+    }
+    for (int l = l_begin; l + 1 < L; ++l) {
       const bool last = (l == L - 2);
       T *out = last ? pair : buf[l & 1];
       LayerArgs<T> la;

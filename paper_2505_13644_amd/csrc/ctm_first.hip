@@ -1,0 +1,145 @@
+// First layer for direction sets shared by all points (standard basis, shared V, sigma).
+//
+// With seeds x_{0} = x_n, x_{1,r} = v_r, x_{k>=2} = 0 (Sec. 3.1) the first linear layer gives
+//   z_0(n) = W_1 x_n + b_1          -- one small dot product per (point, feature)
+//   z_{1,r} = W_1 v_r               -- the same for every point, so it is computed once
+//   z_{k>=2} = 0
+// and the activation rule (same formulas as in the stacked-GEMM epilogue) reduces to products
+// of per-(point, feature) factors with per-(direction, feature) constants:
+//   order 2:  h_0 = t, h_{1,r} = d1 * z1_r, h_2 = d2 * sum_r z1_r^2
+//   order 4:  h_{1,r} = d1 z1_r, h_{2,r} = d2 z1_r^2, h_{3,r} = d3 z1_r^3, h_4 = d4 * sum_r z1_r^4
+// so the whole layer is bound by writing the [N * rho, d_1] block to HBM; no GEMM over the
+// rho rows of every point is needed.
+#include "ctm_internal.h"
+
+namespace ctm {
+
+__device__ __forceinline__ float tanh_of(float z) { return tanhf(z); }
+__device__ __forceinline__ double tanh_of(double z) { return tanh(z); }
+
+// z1[r][j] = sum_k W[j][k] v_r[k]  and  mom[j] = sum_r z1[r][j]^order.  One thread per feature.
+template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= a.ld1) return;
+  const T *w = a.W + (long)j * a.ld0;
+  T mom = T(0);
+  for (int r = 0; r < a.R; ++r) {
+    T z = T(0);
+    if (a.V == nullptr) {
+      z = w[a.r0 + r];
+    } else {
+      const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
+      for (int k = 0; k < a.D; ++k) z += w[k] * v[(long)k * a.v_sd];
+    }
+    a.Z1[(long)r * a.ld1 + j] = z;
+    const T z2 = z * z;
+    mom += (a.order == 2) ? z2 : z2 * z2;
+  }
+  a.mom[j] = mom;
+}
+
+constexpr int kFirstPoints = 16;  // points per workgroup
+constexpr int kFirstDmax = 64;    // input widths up to this are held in registers
+
+template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
+  __shared__ T xs[kFirstPoints][kFirstDmax];
+  const int tid = threadIdx.x;
+  const int j = blockIdx.x * 256 + tid;
+  const long n0 = (long)blockIdx.y * kFirstPoints;
+  const int np = (int)((a.N - n0) < kFirstPoints ? (a.N - n0) : kFirstPoints);
+  for (int i = tid; i < kFirstPoints * kFirstDmax; i += 256) {  // unused entries must be zero, not stale
+    const int p = i / kFirstDmax, k = i % kFirstDmax;
+    xs[p][k] = (p < np && k < a.D) ? a.x[(n0 + p) * a.D + k] : T(0);
+  }
+  __syncthreads();
+  if (j >= a.ld1) return;
+
+  T w[kFirstDmax];
+#pragma unroll
+  for (int k = 0; k < kFirstDmax; ++k) w[k] = k < a.D ? a.W[(long)j * a.ld0 + k] : T(0);
+  const T bias = a.bias[j];
+
+  T t[kFirstPoints], d1[kFirstPoints];
+#pragma unroll
+  for (int p = 0; p < kFirstPoints; ++p) {
+    T z0 = bias;
+#pragma unroll
+    for (int k = 0; k < kFirstDmax; ++k) z0 += w[k] * xs[p][k];   // k >= D: both factors are zero
+    if (a.act == 0) {
+      t[p] = tanh_of(z0);
+      d1[p] = T(1) - t[p] * t[p];
+    } else {
+      t[p] = z0;
+      d1[p] = T(1);
+    }
+  }
+
+  const long ld = a.ld1;
+  const int rho = a.rho;
+  T *o = a.last ? a.out + (n0 * 2) * ld + j : a.out + (n0 * rho) * ld + j;
+  const long pstep = (a.last ? 2 : rho) * ld;
+  const T tanh_on = a.act == 0 ? T(1) : T(0);
+#pragma unroll
+  for (int p = 0; p < kFirstPoints; ++p)
+    if (p < np) o[p * pstep] = t[p];
+  if (!a.last) {
+    for (int r = 0; r < a.R; ++r) {
+      const T z1 = a.Z1[(long)r * ld + j];
+      if (a.order == 2) {
+        T *orow = o + (long)(1 + r) * ld;
+#pragma unroll
+        for (int p = 0; p < kFirstPoints; ++p)
+          if (p < np) orow[p * pstep] = d1[p] * z1;
+      } else {
+        T *orow = o + (long)(1 + 3 * r) * ld;
+        const T z1s = z1 * z1, z1c = z1s * z1;
+#pragma unroll
+        for (int p = 0; p < kFirstPoints; ++p)
+          if (p < np) {
+            const T d2 = T(-2) * t[p] * d1[p] * tanh_on;
+            const T d3 = d1[p] * (T(6) * t[p] * t[p] - T(2)) * tanh_on;
+            orow[p * pstep] = d1[p] * z1;
+            orow[p * pstep + ld] = d2 * z1s;
+            orow[p * pstep + 2 * ld] = d3 * z1c;
+          }
+      }
+    }
+  }
+  const T mom = a.mom[j];
+  T *olast = o + (long)(a.last ? 1 : rho - 1) * ld;
+#pragma unroll
+  for (int p = 0; p < kFirstPoints; ++p)
+    if (p < np) {
+      T dk;
+      if (a.order == 2) dk = T(-2) * t[p] * d1[p];
+      else dk = T(8) * t[p] * d1[p] * (T(2) - T(3) * t[p] * t[p]);
+      olast[p * pstep] = dk * tanh_on * mom;
+    }
+}
+
+bool first_layer_fast_path(int D, long v_point_stride) { return v_point_stride == 0 && D <= kFirstDmax; }
+
+template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s) {
+  hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256), dim3(256), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long chunks = (a.N + kFirstPoints - 1) / kFirstPoints;
+  if (chunks > 65535L * 65535L) return hipErrorInvalidValue;
+  // grid.y is limited to 65535: fold larger batches into several launches
+  for (long c0 = 0; c0 < chunks; c0 += 65535) {
+    const long nc = (chunks - c0) < 65535 ? (chunks - c0) : 65535;
+    FirstArgs<T> b = a;
+    b.x = a.x + c0 * kFirstPoints * a.D;
+    b.out = a.out + c0 * kFirstPoints * (a.last ? 2 : a.rho) * (long)a.ld1;
+    b.N = a.N - c0 * kFirstPoints;
+    if (b.N > nc * kFirstPoints) b.N = nc * kFirstPoints;
+    hipLaunchKernelGGL(first_layer_kernel<T>, dim3((a.ld1 + 255) / 256, (unsigned)nc), dim3(256), 0, s, b);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+template hipError_t launch_first<float>(const FirstArgs<float> &, hipStream_t);
+template hipError_t launch_first<double>(const FirstArgs<double> &, hipStream_t);
+
+}  // namespace ctm

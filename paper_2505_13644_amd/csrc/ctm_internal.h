@@ -62,6 +62,22 @@ template <typename T> struct SeedArgs {
 };
 template <typename T> hipError_t launch_seed(const SeedArgs<T> &a, hipStream_t s);
 
+// First layer when every point shares the directions: no GEMM over the per-direction rows.
+template <typename T> struct FirstArgs {
+  const T *x;     // [N][D]
+  const T *V;     // shared directions (element (r, k) at V[r*v_sr + k*v_sd]) or nullptr (basis)
+  const T *W;     // zero-padded first-layer weights [rows_pad][ld0]
+  const T *bias;  // [rows_pad]
+  T *Z1;          // scratch [R][ld1]: W_1 v_r
+  T *mom;         // scratch [ld1]: sum_r (W_1 v_r)^order
+  T *out;         // last == 0: [N * rho][ld1]; last == 1: [N][2][ld1]
+  long N;
+  long v_sr, v_sd;
+  int D, ld0, ld1, rho, order, R, r0, last, act;
+};
+bool first_layer_fast_path(int D, long v_point_stride);
+template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s);
+
 template <typename T>
 hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad,
                        int ld, hipStream_t s);
