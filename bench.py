@@ -29,6 +29,20 @@ def gemm_flops(dims, N, rho, R, per_point_dirs):
     return f
 
 
+def recorded_traffic(name):
+    """HBM bytes per stacked-GEMM launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
+    workload (counters cannot be read from inside this process); None if there is no such summary."""
+    path = os.path.join(ROOT, "profiles", f"layer_kernel_{name}_hbm_traffic.txt")
+    try:
+        with open(path) as fh:
+            for line in fh:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, arrs, budget_s):
     """The oracle as it stands (full Hessian per point, then the trace or contraction / 4th directional
     derivatives), timed on the host cores for a bounded sample of the same workload."""
@@ -131,7 +145,7 @@ def main():
     achieved = flops / (layer_ms_per_step * 1e-3) / 1e12
     roofline = {
         "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
-        "frac": achieved / PEAK_TFLOPS[dt], "traffic": None,
+        "frac": achieved / PEAK_TFLOPS[dt], "traffic": recorded_traffic(w.name),
         "kernel": "layer_kernel (stacked GEMM + fused jet rule)",
         "flops_per_step": flops, "launches_per_step": launches["layer"] / args.steps,
         "avg_launch_ms": ms["layer"] / max(1, launches["layer"]),
