@@ -120,7 +120,7 @@ Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
   Layout lo;
   lo.block_bytes = round256((size_t)N * (size_t)rows_per_point(K, Rpass) * (size_t)maxld * es);
   lo.pair_bytes = round256((size_t)N * 2 * (size_t)m->ld[m->L - 1] * es);
-  lo.dirs_bytes = round256((size_t)(Rpass + 1) * (size_t)m->ld[1 < m->L ? 1 : 0] * es);  // W_1 v_r rows + moments
+  lo.dirs_bytes = round256((size_t)Rpass * (size_t)m->ld[1] * es);  // W_1 v_r rows
   lo.total = 2 * lo.block_bytes + lo.pair_bytes + lo.dirs_bytes;
   return lo;
 }
@@ -147,7 +147,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       const bool last = (L == 2);
       FirstArgs<T> fa;
       fa.x = x; fa.V = V; fa.W = (const T *)m->Wp[0]; fa.bias = (const T *)m->bp[0];
-      fa.Z1 = dirs; fa.mom = dirs + (size_t)Rp * m->ld[1];
+      fa.Z1 = dirs;
       fa.out = last ? pair : buf[0];
       fa.N = N; fa.v_sr = sr; fa.v_sd = sd;
       fa.D = m->dims[0]; fa.ld0 = m->ld[0]; fa.ld1 = m->ld[1]; fa.rho = pl.rho; fa.order = K; fa.R = Rp;

@@ -17,25 +17,20 @@ namespace ctm {
 __device__ __forceinline__ float tanh_of(float z) { return tanhf(z); }
 __device__ __forceinline__ double tanh_of(double z) { return tanh(z); }
 
-// z1[r][j] = sum_k W[j][k] v_r[k]  and  mom[j] = sum_r z1[r][j]^order.  One thread per feature.
+// z1[r][j] = sum_k W[j][k] v_r[k].  One thread per (direction, feature).
 template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int r = blockIdx.y;
   if (j >= a.ld1) return;
   const T *w = a.W + (long)j * a.ld0;
-  T mom = T(0);
-  for (int r = 0; r < a.R; ++r) {
-    T z = T(0);
-    if (a.V == nullptr) {
-      z = w[a.r0 + r];
-    } else {
-      const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
-      for (int k = 0; k < a.D; ++k) z += w[k] * v[(long)k * a.v_sd];
-    }
-    a.Z1[(long)r * a.ld1 + j] = z;
-    const T z2 = z * z;
-    mom += (a.order == 2) ? z2 : z2 * z2;
+  T z = T(0);
+  if (a.V == nullptr) {
+    z = w[a.r0 + r];
+  } else {
+    const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
+    for (int k = 0; k < a.D; ++k) z += w[k] * v[(long)k * a.v_sd];
   }
-  a.mom[j] = mom;
+  a.Z1[(long)r * a.ld1 + j] = z;
 }
 
 constexpr int kFirstPoints = 16;  // points per workgroup
@@ -82,30 +77,31 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
     if (p < np) o[p * pstep] = t[p];
-  if (!a.last) {
-    for (int r = 0; r < a.R; ++r) {
-      const T z1 = a.Z1[(long)r * ld + j];
-      if (a.order == 2) {
-        T *orow = o + (long)(1 + r) * ld;
+  T mom = T(0);  // sum_r z1_r^order, the only term of the collapsed row at the first layer
+  for (int r = 0; r < a.R; ++r) {
+    const T z1 = a.Z1[(long)r * ld + j];
+    const T z1s = z1 * z1;
+    mom += (a.order == 2) ? z1s : z1s * z1s;
+    if (a.last) continue;
+    if (a.order == 2) {
+      T *orow = o + (long)(1 + r) * ld;
 #pragma unroll
-        for (int p = 0; p < kFirstPoints; ++p)
-          if (p < np) orow[p * pstep] = d1[p] * z1;
-      } else {
-        T *orow = o + (long)(1 + 3 * r) * ld;
-        const T z1s = z1 * z1, z1c = z1s * z1;
+      for (int p = 0; p < kFirstPoints; ++p)
+        if (p < np) orow[p * pstep] = d1[p] * z1;
+    } else {
+      T *orow = o + (long)(1 + 3 * r) * ld;
+      const T z1c = z1s * z1;
 #pragma unroll
-        for (int p = 0; p < kFirstPoints; ++p)
-          if (p < np) {
-            const T d2 = T(-2) * t[p] * d1[p] * tanh_on;
-            const T d3 = d1[p] * (T(6) * t[p] * t[p] - T(2)) * tanh_on;
-            orow[p * pstep] = d1[p] * z1;
-            orow[p * pstep + ld] = d2 * z1s;
-            orow[p * pstep + 2 * ld] = d3 * z1c;
-          }
-      }
+      for (int p = 0; p < kFirstPoints; ++p)
+        if (p < np) {
+          const T d2 = T(-2) * t[p] * d1[p] * tanh_on;
+          const T d3 = d1[p] * (T(6) * t[p] * t[p] - T(2)) * tanh_on;
+          orow[p * pstep] = d1[p] * z1;
+          orow[p * pstep + ld] = d2 * z1s;
+          orow[p * pstep + 2 * ld] = d3 * z1c;
+        }
     }
   }
-  const T mom = a.mom[j];
   T *olast = o + (long)(a.last ? 1 : rho - 1) * ld;
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
@@ -120,7 +116,7 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 bool first_layer_fast_path(int D, long v_point_stride) { return v_point_stride == 0 && D <= kFirstDmax; }
 
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s) {
-  hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256, a.R), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long chunks = (a.N + kFirstPoints - 1) / kFirstPoints;

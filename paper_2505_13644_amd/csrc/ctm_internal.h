@@ -9,14 +9,14 @@ namespace ctm {
 
 // Shape constants of the stacked-GEMM kernel, per storage type.
 //   KV  elements per 16-byte LDS/global vector
-//   BK  K-extent of one LDS stage
+//   BK  K-extent of one LDS stage (4 * KV: each lane's 16-byte fragment feeds KV MFMAs)
 //   NB  16-column MFMA blocks per wave; a workgroup has 4 waves side by side
 template <typename T> struct Shape;
 template <> struct Shape<float> {
   static constexpr int KV = 4, BK = 16, NB = 2;
 };
 template <> struct Shape<double> {
-  static constexpr int KV = 2, BK = 16, NB = 1;
+  static constexpr int KV = 2, BK = 8, NB = 1;
 };
 template <typename T> constexpr int tile_cols() { return 64 * Shape<T>::NB; }
 
@@ -69,7 +69,6 @@ template <typename T> struct FirstArgs {
   const T *W;     // zero-padded first-layer weights [rows_pad][ld0]
   const T *bias;  // [rows_pad]
   T *Z1;          // scratch [R][ld1]: W_1 v_r
-  T *mom;         // scratch [ld1]: sum_r (W_1 v_r)^order
   T *out;         // last == 0: [N * rho][ld1]; last == 1: [N][2][ld1]
   long N;
   long v_sr, v_sd;

@@ -148,20 +148,23 @@ void layer_kernel(const LayerArgs<T> a) {
     b_src[i] = Bg + (long)row * a.ldin + kq * KV;
   }
 
-  vld a_reg[TL::A_LD], b_reg[TL::B_LD];
-  auto load_global = [&](int k0) {
+  // Two register sets for the global->LDS copies: while k-block kt is being multiplied, k-block
+  // kt+1 sits in one set (fetched a whole stage earlier) and k-block kt+2 is being fetched into
+  // the other.
+  vld ga[2][TL::A_LD], gb[2][TL::B_LD];
+  auto load_global = [&](int set, int k0) {
 #pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) a_reg[i] = *reinterpret_cast<const vld *>(a_src[i] + k0);
+    for (int i = 0; i < TL::A_LD; ++i) ga[set][i] = *reinterpret_cast<const vld *>(a_src[i] + k0);
 #pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) b_reg[i] = *reinterpret_cast<const vld *>(b_src[i] + k0);
+    for (int i = 0; i < TL::B_LD; ++i) gb[set][i] = *reinterpret_cast<const vld *>(b_src[i] + k0);
   };
-  auto store_lds = [&](int stage) {
+  auto store_lds = [&](int stage, int set) {
     T *Ad = As + stage * TL::A_STAGE;
     T *Bd = Bs + stage * TL::B_STAGE;
 #pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) *reinterpret_cast<vld *>(Ad + a_off[i]) = a_reg[i];
+    for (int i = 0; i < TL::A_LD; ++i) *reinterpret_cast<vld *>(Ad + a_off[i]) = ga[set][i];
 #pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) *reinterpret_cast<vld *>(Bd + b_off[i]) = b_reg[i];
+    for (int i = 0; i < TL::B_LD; ++i) *reinterpret_cast<vld *>(Bd + b_off[i]) = gb[set][i];
   };
 
   vacc acc[MB][NB];
@@ -170,54 +173,73 @@ void layer_kernel(const LayerArgs<T> a) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = vacc{0, 0, 0, 0};
 
-  const int nk = a.ldin / BK;
-  load_global(0);
-  store_lds(0);
+  // ---- k loop.  A stage is one k-block of BK = 4*KV values, i.e. MB steps of NB*KV MFMAs (one A
+  // fragment against the NB B fragments).  The loop body covers two stages so that every LDS
+  // buffer, register set and fragment slot is a compile-time choice.  Within a stage:
+  //   * the global loads for the k-block two stages ahead are issued first;
+  //   * at step kWriteStep the k-block one stage ahead (already in registers) goes to the other
+  //     LDS buffer -- every wave finished reading that buffer before the previous barrier;
+  //   * every step fetches the next step's A fragment before issuing its own MFMAs;
+  //   * the last step waits for this wave's LDS traffic, passes the barrier (after which the other
+  //     buffer is complete) and fetches the first fragments of the next stage, so they arrive
+  //     while the last MFMAs of this stage execute.
+  static_assert(BK == 4 * KV, "one k-group per stage");
+  constexpr int kWriteStep = 2;
+  static_assert(kWriteStep < MB - 1, "the LDS write must precede the stage's barrier step");
+  const int npairs = a.ldin / (2 * BK);  // ldin is a multiple of 32, so the stage count is even
+  const T *Ar = As + lr * LROW + lg * KV;
+  const T *Br = Bs + (wave * 16 + lr) * LROW + lg * KV;  // + nb * 64 rows
+  vld bf[2][NB], af[2];
+
+  load_global(0, 0);
+  load_global(1, BK);
+  store_lds(0, 0);
   __syncthreads();
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Br + nb * 64 * LROW);
+  af[0] = *reinterpret_cast<const vld *>(Ar);
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
-    if (kt + 1 < nk) load_global((kt + 1) * BK);  // in flight while this stage is consumed
-
-    const T *Ac = As + stage * TL::A_STAGE + lr * LROW + lg * KV;
-    const T *Bc = Bs + stage * TL::B_STAGE + (wave * 16 + lr) * LROW + lg * KV;  // + nb * 64 rows
-    // One step = one A fragment (16 rows x KV k-values per lane) against the NB B fragments of its
-    // k-group.  The A fragment of step s+1 is fetched from LDS before the MFMAs of step s are
-    // issued, so the LDS latency hides behind NB*KV MFMAs instead of stalling each step.
-    constexpr int NKG = BK / (4 * KV);
-    constexpr int STEPS = NKG * MB;
-    vld bf[2][NB], af[2];
+  // The body is branch-free: the last pair fetches and stores its own k-blocks once more (unused)
+  // rather than skipping, because a conditional load would make the compiler wait for *all*
+  // outstanding loads at the LDS write.
+  const int k_last = a.ldin - 2 * BK;
+  for (int kp = 0; kp < npairs; ++kp) {
+    const int k_next = (2 * kp + 2) * BK < k_last ? (2 * kp + 2) * BK : k_last;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Bc + nb * 64 * LROW);
-    af[0] = *reinterpret_cast<const vld *>(Ac);
+    for (int half = 0; half < 2; ++half) {
+      // stage `half` reads LDS buffer `half`; set 1-half holds the next k-block; set half is free
+      load_global(half, k_next + half * BK);
+      const T *Ac = Ar + half * TL::A_STAGE;
+      const T *An = Ar + (half ^ 1) * TL::A_STAGE;
+      const T *Bn = Br + (half ^ 1) * TL::B_STAGE;
 #pragma unroll
-    for (int st = 0; st < STEPS; ++st) {
-      const int kg = st / MB, mb = st % MB;
-      if (st + 1 < STEPS) {
-        const int kg1 = (st + 1) / MB, mb1 = (st + 1) % MB;
-        af[(st + 1) & 1] = *reinterpret_cast<const vld *>(Ac + mb1 * 16 * LROW + kg1 * 4 * KV);
-        if (mb == 0 && kg + 1 < NKG) {
+      for (int st = 0; st < MB; ++st) {
+        const int s = half * MB + st;  // fragment slot parity runs across both stages
+        if (st == kWriteStep) store_lds(half ^ 1, half ^ 1);
+        if (st + 1 < MB) {
+          af[(s + 1) & 1] = *reinterpret_cast<const vld *>(Ac + (st + 1) * 16 * LROW);
+        } else {
+          __syncthreads();
+          af[(s + 1) & 1] = *reinterpret_cast<const vld *>(An);
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            bf[(kg + 1) & 1][nb] = *reinterpret_cast<const vld *>(Bc + nb * 64 * LROW + (kg + 1) * 4 * KV);
+          for (int nb = 0; nb < NB; ++nb) bf[half ^ 1][nb] = *reinterpret_cast<const vld *>(Bn + nb * 64 * LROW);
         }
+        __builtin_amdgcn_sched_barrier(0);  // keep the fetches ahead of this step's MFMAs
+#pragma unroll
+        for (int j = 0; j < KV; ++j)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[st][nb] = mfma16(af[s & 1][j], bf[half][nb][j], acc[st][nb]);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);  // keep the prefetch ahead of this step's MFMAs
-#pragma unroll
-      for (int j = 0; j < KV; ++j)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = mfma16(af[st & 1][j], bf[kg & 1][nb][j], acc[mb][nb]);
-      __builtin_amdgcn_sched_barrier(0);
     }
-
-    if (kt + 1 < nk) store_lds(stage ^ 1);  // the other stage was last read before the previous barrier
-    __syncthreads();
   }
+  // Each wave's last real fragment read completed before it entered the final barrier above, so the
+  // stages can be reused for the C tile right away (the fragments fetched after that barrier are unused).
 
   // ---- epilogue, 64 output columns at a time (wave w holds columns nb*64 + w*16 .. +15 of the
   // tile in acc[.][nb]): stage that chunk of the accumulators through LDS, then apply the
   // collapsed jet rule with one thread per (point, feature) pair, walking the point's rows in
-  // order.  All waves have passed the k loop's final barrier, so its stages are dead.
+  // order.
   const int R = a.R, rho = a.rho;
   const int j = tid & 63;
 #pragma unroll
@@ -252,7 +274,18 @@ void layer_kernel(const LayerArgs<T> a) {
       o[0] = t;
       if (a.order == 2) {
         T s = T(0);
-        for (int r = 1; r <= R; ++r) {
+        int r = 1;
+        for (; r + 3 <= R; r += 4) {  // four independent LDS reads in flight per trip
+          T z1[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) z1[i] = c[(long)(r + i) * CROW];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            s += z1[i] * z1[i];
+            if (!a.last) o[(r + i) * ostep] = d1 * z1[i];
+          }
+        }
+        for (; r <= R; ++r) {
           const T z1 = c[(long)r * CROW];
           s += z1 * z1;
           if (!a.last) o[r * ostep] = d1 * z1;
