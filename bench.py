@@ -61,6 +61,8 @@ def cpu_baseline(w, arrs, budget_s):
             orc.laplacian(sub["Ws"], sub["bs"], sub["x"], sub.get("V"), sub.get("scale", 1.0), mode="hessian")
         elif w.op == "weighted_laplacian":
             orc.weighted_laplacian(sub["Ws"], sub["bs"], sub["x"], sub["sigma"], mode="hessian")
+        elif w.op == "biharmonic_exact":
+            orc.biharmonic_exact(sub["Ws"], sub["bs"], sub["x"])
         else:
             orc.biharmonic_rand(sub["Ws"], sub["bs"], sub["x"], sub["V"])
         return time.perf_counter() - t0
@@ -69,11 +71,13 @@ def cpu_baseline(w, arrs, budget_s):
     t_probe = run(p0)
     P = int(max(p0, min(w.N, budget_s / max(t_probe / p0, 1e-9))))
     t = run(P)
+    kind = {"biharmonic_rand": "4-level duals per direction", "biharmonic_exact": "4-level duals per index pair (i,i,j,j)"}.get(
+        w.op, "full Hessian per point")
     info = threadpool_info()
     cores = max([i.get("num_threads", 1) for i in info] or [1])
     return {"value": P / t, "unit": "evals/s", "cores": cores, "kind": "oracle",
             "sample": f"first {P} of {w.N} points of {w.name}, fp64 numpy nested-dual oracle "
-                      f"({'full Hessian per point' if w.op != 'biharmonic_rand' else '4-level duals per direction'}), {t:.1f} s"}
+                      f"({kind}), {t:.1f} s"}
 
 
 def main():
@@ -101,17 +105,23 @@ def main():
     t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
     mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
     x, V, sigma = t(arrs["x"]), t(arrs.get("V")), t(arrs.get("sigma"))
-    K = 4 if w.op == "biharmonic_rand" else 2
+    K = 4 if w.op.startswith("biharmonic") else 2
     R = w.dims[0] if w.directions == "basis" else w.R
     u = torch.empty(w.N, dtype=x.dtype, device=dev)
     op = torch.empty(w.N, dtype=x.dtype, device=dev)
-    ws = torch.empty(ctm.ctm_workspace_bytes(mlp, K, w.N, R), dtype=torch.uint8, device=dev)
+    if w.op == "biharmonic_exact":
+        ws_bytes = ctm.binding.lib().ctm_biharmonic_exact_workspace_bytes(mlp.handle, w.N)
+    else:
+        ws_bytes = ctm.ctm_workspace_bytes(mlp, K, w.N, R)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def step():
         if w.op == "laplacian":
             ctm.ctm_laplacian(mlp, x, V, arrs.get("scale", 1.0), u, op, ws)
         elif w.op == "weighted_laplacian":
             ctm.ctm_weighted_laplacian(mlp, x, sigma, u, op, ws)
+        elif w.op == "biharmonic_exact":
+            ctm.ctm_biharmonic_exact(mlp, x, u, op, ws)
         else:
             ctm.ctm_biharmonic_rand(mlp, x, V, u, op, ws)
 
@@ -139,7 +149,13 @@ def main():
         step()
     ms, launches = ctm.ctm_profile_end()
     rho = ctm.ctm_rows_per_point(K, R)
-    flops = gemm_flops(w.dims, w.N, rho, R, w.directions in ("rademacher", "gaussian"))
+    if w.op == "biharmonic_exact":
+        D = w.dims[0]
+        fams = [D, D * (D - 1), D * (D - 1) // 2]
+        flops = sum(gemm_flops(w.dims, w.N, ctm.ctm_rows_per_point(4, r), r, False) for r in fams if r)
+        rho = sum(ctm.ctm_rows_per_point(4, r) for r in fams if r)
+    else:
+        flops = gemm_flops(w.dims, w.N, rho, R, w.directions in ("rademacher", "gaussian"))
     layer_ms_per_step = ms["layer"] / args.steps
     dt = "f64" if w.dtype == np.float64 else "f32"
     achieved = flops / (layer_ms_per_step * 1e-3) / 1e12

@@ -132,6 +132,28 @@ int ctm_biharmonic_rand(const ctm_mlp *mlp, const void *x, long N, const void *V
                         size_t workspace_bytes, void *stream);
 
 /*
+ * Exact biharmonic  op[n] = sum_{d1,d2} d^4 f / dx_{d1}^2 dx_{d2}^2 (x_n)          (Sec. 3.3, Eq. 9 exact case)
+ * by interpolation with three collapsed families of 4-jets (Sec. 3.3 Eq. 12; App. E.1, last display):
+ *   op = 1/24 [ (2 D g40 + 2 g31 + g22) sum_d <d^4 f,(4 e_d)^4> + 2 g31 sum_{d1 != d2} <d^4 f,(3 e_d1 + e_d2)^4>
+ *               + 2 g22 sum_{d1 < d2} <d^4 f,(2 e_d1 + 2 e_d2)^4> ],   g_j = gamma_{(2,2), j}.
+ * The families have D, D(D-1) and D(D-1)/2 directions; they are generated on the device into the
+ * workspace and run as shared-direction order-4 calls whose results are added in this order.
+ * Workspace: ctm_biharmonic_exact_workspace_bytes(mlp, N) bytes (0 on invalid arguments), 256-byte aligned.
+ */
+size_t ctm_biharmonic_exact_workspace_bytes(const ctm_mlp *mlp, long N);
+int ctm_biharmonic_exact(const ctm_mlp *mlp, const void *x, long N, void *u, void *op, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/*
+ * Interpolation coefficient gamma_{i,j} of the mixed-partial reconstruction (App. E, the coefficient
+ * definition with generalised binomials), as an exact fraction num/den in lowest terms (den > 0).
+ *   I     number of distinct directions (1..4); i, j: host arrays of I non-negative ints with
+ *         |i| = |j| in 1..8
+ * Pure host arithmetic.
+ */
+int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, long long *den);
+
+/*
  * Host-side description of how an order-K, R-direction call is tiled: points per tile,
  * 16-row MFMA blocks per tile, directions in the first (largest) pass and number of
  * passes.  Pure host logic (no GPU needed); any output pointer may be NULL.

@@ -34,6 +34,10 @@ SIGNATURES = {
                                        c_size_t, c_void_p]),
     "ctm_biharmonic_rand": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]),
+    "ctm_biharmonic_exact_workspace_bytes": (c_size_t, [c_void_p, c_long]),
+    "ctm_biharmonic_exact": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "ctm_interpolation_gamma": (c_int, [c_int, POINTER(c_int), POINTER(c_int), POINTER(ctypes.c_longlong),
+                                        POINTER(ctypes.c_longlong)]),
     "ctm_tile_plan": (c_int, [c_int, c_int, c_int, POINTER(c_int), POINTER(c_int), POINTER(c_int), POINTER(c_int)]),
     "ctm_profile_begin": (c_int, []),
     "ctm_profile_end": (c_int, [POINTER(c_double), POINTER(c_long)]),
@@ -86,6 +90,15 @@ def ctm_tile_plan(dtype: int, K: int, R: int):
     out = [c_int(0) for _ in range(4)]
     _check(lib().ctm_tile_plan(dtype, K, R, *[ctypes.byref(o) for o in out]))
     return tuple(o.value for o in out)
+
+
+def ctm_interpolation_gamma(i, j):
+    """gamma_{i,j} as a fractions.Fraction."""
+    from fractions import Fraction
+    I = len(i)
+    num, den = ctypes.c_longlong(0), ctypes.c_longlong(1)
+    _check(lib().ctm_interpolation_gamma(I, (c_int * I)(*i), (c_int * I)(*j), ctypes.byref(num), ctypes.byref(den)))
+    return Fraction(num.value, den.value)
 
 
 def ctm_profile_begin():
@@ -253,4 +266,24 @@ def ctm_biharmonic_rand(mlp: Mlp, x, V, u=None, op=None, workspace=None):
                                      _dev_ptr(u, mlp.dtype, "u"), _dev_ptr(op, mlp.dtype, "op"),
                                      c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                      _stream_ptr()))
+    return u, op
+
+
+def ctm_biharmonic_exact(mlp: Mlp, x, u=None, op=None, workspace=None):
+    """Exact biharmonic by interpolation with three collapsed 4-jet families.  Returns (u, op)."""
+    torch = _torch()
+    _check_shapes(mlp, x, None)
+    N = x.shape[0]
+    need = lib().ctm_biharmonic_exact_workspace_bytes(mlp.handle, N)
+    if need == 0:
+        raise CtmError(-2, ctm_last_error())
+    if u is None:
+        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if op is None:
+        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check(lib().ctm_biharmonic_exact(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(u, mlp.dtype, "u"),
+                                      _dev_ptr(op, mlp.dtype, "op"), c_void_p(workspace.data_ptr()),
+                                      workspace.numel() * workspace.element_size(), _stream_ptr()))
     return u, op

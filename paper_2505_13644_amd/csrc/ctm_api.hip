@@ -80,6 +80,54 @@ PassPlan plan_pass(int K, int R) {
   return best;
 }
 
+// ---- interpolation coefficients gamma_{i,j} (App. E, Eq. "ttc_coeff"), exact rational arithmetic
+struct Frac {
+  long long n = 0, d = 1;
+};
+long long gcd_ll(long long a, long long b) {
+  a = a < 0 ? -a : a;
+  b = b < 0 ? -b : b;
+  while (b) { long long t = a % b; a = b; b = t; }
+  return a ? a : 1;
+}
+Frac norm(Frac f) {
+  if (f.d < 0) { f.n = -f.n; f.d = -f.d; }
+  const long long g = gcd_ll(f.n, f.d);
+  f.n /= g; f.d /= g;
+  return f;
+}
+Frac mul(Frac a, Frac b) { return norm(Frac{a.n * b.n, a.d * b.d}); }
+Frac add(Frac a, Frac b) { return norm(Frac{a.n * b.d + b.n * a.d, a.d * b.d}); }
+// generalised binomial (a over b) = prod_{l<b} (a - l) / (b - l), a rational, b a non-negative integer
+Frac gbinom(Frac a, int b) {
+  Frac r{1, 1};
+  for (int l = 0; l < b; ++l) r = mul(r, norm(Frac{a.n - (long long)l * a.d, a.d * (long long)(b - l)}));
+  return r;
+}
+// gamma_{i,j} = sum_{0 < m <= i} (-1)^{|i-m|} (i over m) (|i| m/|m| over j) (|m|/|i|)^{|i|}
+Frac interp_gamma(int I, const int *iv, const int *jv) {
+  int isum = 0;
+  for (int t = 0; t < I; ++t) isum += iv[t];
+  Frac total{0, 1};
+  std::vector<int> m(I, 0);
+  while (true) {
+    int t = 0;  // next multi-index m in the box [0, i]
+    while (t < I && m[t] == iv[t]) m[t++] = 0;
+    if (t == I) break;
+    ++m[t];
+    int msum = 0, dist = 0;
+    for (int q = 0; q < I; ++q) { msum += m[q]; dist += iv[q] - m[q]; }
+    Frac term{(dist & 1) ? -1 : 1, 1};
+    for (int q = 0; q < I; ++q) {
+      term = mul(term, gbinom(Frac{iv[q], 1}, m[q]));
+      term = mul(term, gbinom(norm(Frac{(long long)isum * m[q], msum}), jv[q]));
+    }
+    for (int q = 0; q < isum; ++q) term = mul(term, norm(Frac{msum, isum}));
+    total = add(total, term);
+  }
+  return total;
+}
+
 struct Split {
   int n_passes, first, lastR;  // passes 0..n-2 take `first` directions, the last one `lastR`
 };
@@ -127,7 +175,7 @@ Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
 
 template <typename T>
 int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, long sr, long sd,
-               double scale, T *u, T *op, void *ws, hipStream_t st) {
+               double scale, T *u, T *op, void *ws, hipStream_t st, bool accumulate_first = false) {
   const Split sp = split_dirs(K, R);
   const Layout lo = workspace_layout(m, K, N, sp.first);
   T *buf[2] = {reinterpret_cast<T *>(ws), reinterpret_cast<T *>((char *)ws + lo.block_bytes)};
@@ -181,7 +229,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
     }
     FinalArgs<T> fa;
     fa.pair = pair; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
-    fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = pass > 0;
+    fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = (pass > 0 || accumulate_first) ? 1 : 0;
     e = launch_final<T>(fa, st);
     if (e != hipSuccess) return fail_hip(e, "final kernel launch");
     (void)prof_mark(st, 2);
@@ -394,6 +442,77 @@ int ctm_biharmonic_rand(const ctm_mlp *m, const void *x, long N, const void *V, 
   const long D = m ? m->dims[0] : 0;
   const double scale = S >= 1 ? 1.0 / (3.0 * S) : 0.0;
   return run_operator(m, 4, x, N, V, S, v_point_stride, D, 1, scale, u, op, ws, ws_bytes, stream, "ctm_biharmonic_rand");
+}
+
+int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, long long *den) {
+  if (!i || !j || !num || !den) return fail(CTM_ERR_NULL, "ctm_interpolation_gamma: NULL argument");
+  if (I < 1 || I > 4) return fail(CTM_ERR_SHAPE, "ctm_interpolation_gamma: I = %d, need 1..4", I);
+  int si = 0, sj = 0;
+  for (int t = 0; t < I; ++t) {
+    if (i[t] < 0 || j[t] < 0 || i[t] > 8 || j[t] > 8) return fail(CTM_ERR_SHAPE, "ctm_interpolation_gamma: entries must lie in 0..8");
+    si += i[t];
+    sj += j[t];
+  }
+  if (si != sj || si < 1 || si > 8) return fail(CTM_ERR_SHAPE, "ctm_interpolation_gamma: |i| = %d and |j| = %d must agree and lie in 1..8", si, sj);
+  const Frac g = interp_gamma(I, i, j);
+  *num = g.n;
+  *den = g.d;
+  return CTM_OK;
+}
+
+size_t ctm_biharmonic_exact_workspace_bytes(const ctm_mlp *m, long N) {
+  if (!m) { fail(CTM_ERR_NULL, "ctm_biharmonic_exact_workspace_bytes: mlp handle is NULL"); return 0; }
+  if (N < 1) { fail(CTM_ERR_SHAPE, "ctm_biharmonic_exact_workspace_bytes: N = %ld, need N >= 1", N); return 0; }
+  const long D = m->dims[0];
+  const long rmax = D > 1 ? D * (D - 1) : D;
+  if (rmax > 0x7fffffffL) { fail(CTM_ERR_SHAPE, "ctm_biharmonic_exact_workspace_bytes: D too large"); return 0; }
+  return workspace_layout(m, 4, N, split_dirs(4, (int)rmax).first).total + round256((size_t)rmax * D * elem_size(m->dtype));
+}
+
+int ctm_biharmonic_exact(const ctm_mlp *m, const void *x, long N, void *u, void *op, void *ws, size_t ws_bytes,
+                         void *stream) {
+  const char *who = "ctm_biharmonic_exact";
+  if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
+  if (!x) return fail(CTM_ERR_NULL, "%s: x is NULL", who);
+  if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
+  if (!ws) return fail(CTM_ERR_NULL, "%s: workspace is NULL", who);
+  const size_t need = ctm_biharmonic_exact_workspace_bytes(m, N);
+  if (need == 0) return CTM_ERR_SHAPE;
+  if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: workspace must be 256-byte aligned", who);
+  if (misaligned(x, es) || misaligned(u, es) || misaligned(op, es))
+    return fail(CTM_ERR_ALIGN, "%s: x, u and op must be aligned to the element size", who);
+  const int D = m->dims[0];
+  // weights of the three direction families (final form of the interpolation formula, App. E.1)
+  const int i22[2] = {2, 2}, j40[2] = {4, 0}, j31[2] = {3, 1}, j22[2] = {2, 2};
+  const Frac g40 = interp_gamma(2, i22, j40), g31 = interp_gamma(2, i22, j31), g22 = interp_gamma(2, i22, j22);
+  const double G40 = (double)g40.n / g40.d, G31 = (double)g31.n / g31.d, G22 = (double)g22.n / g22.d;
+  const double weight[3] = {(2.0 * D * G40 + 2.0 * G31 + G22) / 24.0, 2.0 * G31 / 24.0, 2.0 * G22 / 24.0};
+  const long count[3] = {D, (long)D * (D - 1), (long)D * (D - 1) / 2};
+  const long rmax = D > 1 ? (long)D * (D - 1) : D;
+  const size_t vbytes = round256((size_t)rmax * D * es);
+  void *vbuf = (char *)ws + (need - vbytes);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  bool first = true;
+  for (int fam = 0; fam < 3; ++fam) {
+    if (count[fam] == 0) continue;
+    int rc;
+    if (m->dtype == CTM_F64) {
+      hipError_t e = launch_biharm_dirs<double>((double *)vbuf, D, fam, st);
+      if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
+      rc = run_passes<double>(m, 4, (const double *)x, N, (const double *)vbuf, (int)count[fam], 0, D, 1, weight[fam],
+                              first ? (double *)u : nullptr, (double *)op, ws, st, !first);
+    } else {
+      hipError_t e = launch_biharm_dirs<float>((float *)vbuf, D, fam, st);
+      if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
+      rc = run_passes<float>(m, 4, (const float *)x, N, (const float *)vbuf, (int)count[fam], 0, D, 1, weight[fam],
+                             first ? (float *)u : nullptr, (float *)op, ws, st, !first);
+    }
+    if (rc != CTM_OK) return rc;
+    first = false;
+  }
+  return CTM_OK;
 }
 
 }  // extern "C"

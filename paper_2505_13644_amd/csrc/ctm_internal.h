@@ -81,6 +81,10 @@ template <typename T>
 hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad,
                        int ld, hipStream_t s);
 
+// Direction families of the exact biharmonic (interpolation with 4-jets): family 0: 4 e_d (D rows);
+// family 1: 3 e_d1 + e_d2, d1 != d2 (D(D-1) rows); family 2: 2 e_d1 + 2 e_d2, d1 < d2 (D(D-1)/2 rows).
+template <typename T> hipError_t launch_biharm_dirs(T *V, int D, int family, hipStream_t s);
+
 template <typename T> struct FinalArgs {
   const T *pair;  // [N][2][ld] : h_0 and the collapsed h_K of the last hidden layer
   const T *w;     // [ld] zero-padded last-layer weights

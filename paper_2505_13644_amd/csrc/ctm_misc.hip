@@ -67,6 +67,42 @@ hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp
 template hipError_t launch_pack<float>(const float *, const float *, int, int, float *, float *, int, int, hipStream_t);
 template hipError_t launch_pack<double>(const double *, const double *, int, int, double *, double *, int, int, hipStream_t);
 
+// ---- direction sets of the exact biharmonic (Sec. 3.3 / App. E.1: 4-jets along 4 e_d, 3 e_d1 + e_d2, 2 e_d1 + 2 e_d2)
+template <typename T> __global__ void biharm_dirs_kernel(T *V, int D, int family, long rows) {
+  const long total = rows * D;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(i % D);
+    const long r = i / D;
+    T v = T(0);
+    if (family == 0) {
+      v = (k == r) ? T(4) : T(0);
+    } else if (family == 1) {  // r enumerates (d1, d2) with d2 != d1: d2 skips d1
+      const int d1 = (int)(r / (D - 1));
+      int d2 = (int)(r % (D - 1));
+      d2 += d2 >= d1 ? 1 : 0;
+      v = (k == d1) ? T(3) : (k == d2 ? T(1) : T(0));
+    } else {  // r enumerates pairs d1 < d2 in lexicographic order
+      long rem = r;
+      int d1 = 0;
+      while (rem >= D - 1 - d1) { rem -= D - 1 - d1; ++d1; }
+      const int d2 = d1 + 1 + (int)rem;
+      v = (k == d1 || k == d2) ? T(2) : T(0);
+    }
+    V[i] = v;
+  }
+}
+
+template <typename T> hipError_t launch_biharm_dirs(T *V, int D, int family, hipStream_t s) {
+  const long rows = family == 0 ? D : (family == 1 ? (long)D * (D - 1) : (long)D * (D - 1) / 2);
+  if (rows == 0) return hipSuccess;
+  long blocks = (rows * D + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(biharm_dirs_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, V, D, family, rows);
+  return hipGetLastError();
+}
+template hipError_t launch_biharm_dirs<float>(float *, int, int, hipStream_t);
+template hipError_t launch_biharm_dirs<double>(double *, int, int, hipStream_t);
+
 // ---- last layer (App. H: g is linear, bias on the 0-th coefficient only) ------------------
 //   u_n = w . h_0(n) + b        op_n = scale * (w . h_K(n))
 // One wavefront per point; lanes stride the features and the 64 partial sums are folded

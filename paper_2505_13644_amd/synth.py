@@ -77,7 +77,7 @@ class Workload:
         D = self.dims[0]
         Ws, bs = make_mlp(self.dims, self.seed, self.bias_std, self.dtype)
         out = {"Ws": Ws, "bs": bs, "x": make_points(N, D, self.seed, self.dtype)}
-        if self.directions == "basis":
+        if self.directions in ("basis", "interpolation"):
             out["V"], out["scale"] = None, 1.0
         elif self.directions == "sigma":
             out["sigma"] = make_sigma(D, self.R, self.seed, self.dtype)
@@ -100,4 +100,7 @@ WORKLOADS = {
     "c4": Workload("c4", "weighted_laplacian", BIG, 2048, np.float32, 0.01, 2e-4, "sigma", 10),
     # randomized biharmonic, per-point Gaussian directions, S = 32
     "c5": Workload("c5", "biharmonic_rand", (10, 256, 256, 128, 1), 1024, np.float32, 0.0, 2e-4, "gaussian", 32),
+    # beyond the five named configurations: the paper's exact-biharmonic setting (Sec. 4: D = 5, same 768/768/512/512 net),
+    # three interpolation families of 5, 20 and 10 directions
+    "e1": Workload("e1", "biharmonic_exact", (5, 768, 768, 512, 512, 1), 1024, np.float32, 0.01, 2e-4, "interpolation", 20),
 }

@@ -22,6 +22,8 @@ def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None):
         u, o = ctm.ctm_weighted_laplacian(mlp, x, t(arrs["sigma"]))
     elif op == "biharmonic_rand":
         u, o = ctm.ctm_biharmonic_rand(mlp, x, t(arrs["V"]))
+    elif op == "biharmonic_exact":
+        u, o = ctm.ctm_biharmonic_exact(mlp, x)
     else:
         raise ValueError(op)
     torch.cuda.synchronize()
@@ -48,4 +50,6 @@ def oracle_run(arrs, op, act="tanh", idx=None, mode="directional"):
         return orc.weighted_laplacian(arrs["Ws"], arrs["bs"], x, arrs["sigma"], act=act, mode=mode)
     if op == "biharmonic_rand":
         return orc.biharmonic_rand(arrs["Ws"], arrs["bs"], x, V, act=act)
+    if op == "biharmonic_exact":
+        return orc.value(arrs["Ws"], arrs["bs"], x, act=act), orc.biharmonic_exact(arrs["Ws"], arrs["bs"], x, act=act)
     raise ValueError(op)

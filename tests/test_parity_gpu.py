@@ -63,7 +63,7 @@ def test_named_workloads_reduced_batch(name, N):
         check((got[0][idx], got[1][idx]), ref_h, w.tol, "c2 full-Hessian trace")
 
 
-@pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c3", 48), ("c4", 64), ("c5", 48)])
+@pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c3", 48), ("c4", 64), ("c5", 48), ("e1", 12)])
 def test_named_workloads_full_size_sampled(name, n_sample):
     # the launch configuration the benchmark times; the oracle checks a seeded sample of points
     w = synth.WORKLOADS[name]
@@ -150,6 +150,33 @@ def test_biharmonic_shapes(dtype, dims, N, S, per_point):
     arrs = small_case(dims, N, dtype, seed=S, R=S, per_point=per_point, bias=0.05)
     print(f"case biharmonic dims={dims} N={N} S={S} {dtype.__name__}", flush=True)
     check(gpu_run(arrs, "biharmonic_rand"), oracle_run(arrs, "biharmonic_rand"), tol_of(dtype), f"biharmonic {dims} S={S}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N", [((1, 12, 1), 9), ((2, 16, 16, 1), 21), ((5, 32, 24, 1), 13), ((7, 20, 1), 5)])
+def test_exact_biharmonic_by_interpolation(dtype, dims, N):
+    # three collapsed 4-jet families combined with gamma_{(2,2),j} (Sec. 3.3, App. E.1) against the full
+    # tensor sum_{ij} d^4 u / dx_i^2 dx_j^2 of the oracle; D = 5 is the paper's benchmark dimension
+    arrs = small_case(dims, N, dtype, seed=dims[0], bias=0.1)
+    print(f"case exact biharmonic dims={dims} N={N} {dtype.__name__}", flush=True)
+    check(gpu_run(arrs, "biharmonic_exact"), oracle_run(arrs, "biharmonic_exact"), tol_of(dtype) if dtype == np.float64 else 2e-4,
+          f"exact biharmonic {dims}")
+
+
+def test_exact_biharmonic_many_directions_and_stochastic_estimate():
+    # D = 12: the 132-direction family needs two passes; a 4096-sample Gaussian estimate must agree statistically
+    dims, N = (12, 24, 1), 4
+    arrs = small_case(dims, N, np.float64, seed=12)
+    gu, go = gpu_run(arrs, "biharmonic_exact")
+    ru, ro = oracle_run(arrs, "biharmonic_exact")
+    check((gu, go), (ru, ro), TOL64, "exact biharmonic D=12")
+    S = 4096
+    V = synth.make_directions("gaussian", (N, S, 12), 1, np.float64)
+    _, est = gpu_run(dict(arrs, V=V), "biharmonic_rand")
+    from oracle.operators import directional_derivative
+    d4 = directional_derivative(arrs["Ws"], arrs["bs"], arrs["x"], V, 4) / 3.0
+    np.testing.assert_allclose(est, d4.mean(axis=1), rtol=1e-9, atol=1e-12)
+    assert np.all(np.abs(est - go) <= 6 * d4.std(axis=1) / np.sqrt(S))
 
 
 # ---------------------------------------------------------------------------
