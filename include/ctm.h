@@ -62,7 +62,7 @@ typedef enum {
   CTM_ERR_DTYPE = -3,       /* unknown dtype / activation enum value                */
   CTM_ERR_UNSUPPORTED = -4, /* valid request this build does not cover              */
   CTM_ERR_WORKSPACE = -5,   /* workspace smaller than ctm_workspace_bytes() says    */
-  CTM_ERR_ALIGN = -6,       /* a device pointer is not aligned to 16 bytes          */
+  CTM_ERR_ALIGN = -6,       /* a pointer is not aligned as the call requires        */
   CTM_ERR_ALLOC = -7,       /* device allocation failed (ctm_create_mlp only)       */
   CTM_ERR_HIP = -8          /* a HIP runtime call failed; text in ctm_last_error()  */
 } ctm_status;
@@ -120,6 +120,21 @@ int ctm_laplacian(const ctm_mlp *mlp, const void *x, long N, const void *V, int 
 int ctm_weighted_laplacian(const ctm_mlp *mlp, const void *x, long N, const void *sigma, int K,
                            void *u, void *op, void *workspace, size_t workspace_bytes,
                            void *stream);
+
+/*
+ * Weighted Laplacian with a point-dependent sigma and / or Monte-Carlo directions       (Sec. 3.2, Eq. 8)
+ *   sigma   dev; sigma_point_stride = 0: [D, K] shared; = D*K: [N, D, K], sigma depends on the point
+ *   V       dev random vectors in R^K; v_point_stride = 0: [S, K] shared; = S*K: [N, S, K] per point.
+ *           op[n] = (1/S) sum_s (sigma_n v_{n,s})^T H(x_n) (sigma_n v_{n,s})    (stochastic case)
+ *           V = NULL with S = 0: the exact operator Tr(sigma_n sigma_n^T H(x_n)), directions = columns of sigma_n
+ * The directions sigma_n v_{n,s} are formed on the device in the tail of the workspace.
+ * Workspace: ctm_weighted_laplacian_rand_workspace_bytes(...) bytes (0 on invalid arguments), 256-byte aligned.
+ */
+size_t ctm_weighted_laplacian_rand_workspace_bytes(const ctm_mlp *mlp, long N, int K, int S,
+                                                   long sigma_point_stride, long v_point_stride);
+int ctm_weighted_laplacian_rand(const ctm_mlp *mlp, const void *x, long N, const void *sigma, int K,
+                                long sigma_point_stride, const void *V, int S, long v_point_stride,
+                                void *u, void *op, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Randomized biharmonic  op[n] = 1/(3S) * sum_s < d^4 f(x_n), v_s^{(x)4} >         (Sec. 3.3, Eq. 9)

@@ -155,6 +155,29 @@ def weighted_laplacian(Ws, bs, x, sigma, act="tanh", mode="hessian"):
     return laplacian(Ws, bs, x, V=sigma.T, scale=1.0, act=act, mode="directional")
 
 
+def weighted_laplacian_rand(Ws, bs, x, sigma, V=None, act="tanh"):
+    """(u, (1/S) sum_s (sigma_n v_{n,s})^T H(x_n) (sigma_n v_{n,s}))  (Eq. 8, stochastic case).
+
+    sigma is [D, K] (shared) or [N, D, K] (depends on the point); V is [S, K] or [N, S, K].
+    V=None gives the exact operator Tr(sigma_n sigma_n^T H(x_n)) for a point-dependent sigma.
+    """
+    x = _as64(x)
+    N, D = x.shape
+    sigma = _as64(sigma)
+    if sigma.ndim == 2:
+        sigma = np.broadcast_to(sigma[None], (N,) + sigma.shape)
+    u = value(Ws, bs, x, act)
+    H = hessian(Ws, bs, x, act)
+    if V is None:
+        return u, np.einsum("nde,ndk,nek->n", H, sigma, sigma)
+    V = _as64(V)
+    if V.ndim == 2:
+        V = np.broadcast_to(V[None], (N,) + V.shape)
+    S = V.shape[1]
+    dirs = np.einsum("ndk,nsk->nsd", sigma, V)
+    return u, np.einsum("nsd,nde,nse->n", dirs, H, dirs) / S
+
+
 def biharmonic_rand(Ws, bs, x, V, act="tanh"):
     """(u, (1/(3S)) sum_s <d^4 u, v_s^{(x)4}>) (Eq. 9, stochastic case)."""
     V = _as64(V)

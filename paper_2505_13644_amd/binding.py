@@ -34,6 +34,9 @@ SIGNATURES = {
                                        c_size_t, c_void_p]),
     "ctm_biharmonic_rand": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]),
+    "ctm_weighted_laplacian_rand_workspace_bytes": (c_size_t, [c_void_p, c_long, c_int, c_int, c_long, c_long]),
+    "ctm_weighted_laplacian_rand": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_int, c_long,
+                                            c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "ctm_biharmonic_exact_workspace_bytes": (c_size_t, [c_void_p, c_long]),
     "ctm_biharmonic_exact": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "ctm_interpolation_gamma": (c_int, [c_int, POINTER(c_int), POINTER(c_int), POINTER(ctypes.c_longlong),
@@ -286,4 +289,36 @@ def ctm_biharmonic_exact(mlp: Mlp, x, u=None, op=None, workspace=None):
     _check(lib().ctm_biharmonic_exact(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(u, mlp.dtype, "u"),
                                       _dev_ptr(op, mlp.dtype, "op"), c_void_p(workspace.data_ptr()),
                                       workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return u, op
+
+
+def ctm_weighted_laplacian_rand(mlp: Mlp, x, sigma, V=None, u=None, op=None, workspace=None):
+    """sigma: [D, K] or [N, D, K]; V: None (exact), [S, K] or [N, S, K].  Returns (u, op)."""
+    torch = _torch()
+    _check_shapes(mlp, x, None)
+    N, D = x.shape
+    if sigma.dim() not in (2, 3) or sigma.shape[-2] != D or (sigma.dim() == 3 and sigma.shape[0] != N):
+        raise ValueError(f"sigma has shape {tuple(sigma.shape)}, expected [{D}, K] or [{N}, {D}, K]")
+    K = sigma.shape[-1]
+    s_stride = D * K if sigma.dim() == 3 else 0
+    if V is None:
+        S, v_stride = 0, 0
+    else:
+        if V.dim() not in (2, 3) or V.shape[-1] != K or (V.dim() == 3 and V.shape[0] != N):
+            raise ValueError(f"V has shape {tuple(V.shape)}, expected [S, {K}] or [{N}, S, {K}]")
+        S = V.shape[-2]
+        v_stride = S * K if V.dim() == 3 else 0
+    need = lib().ctm_weighted_laplacian_rand_workspace_bytes(mlp.handle, N, K, S, s_stride, v_stride)
+    if need == 0:
+        raise CtmError(-2, ctm_last_error())
+    if u is None:
+        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if op is None:
+        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check(lib().ctm_weighted_laplacian_rand(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(sigma, mlp.dtype, "sigma"), K,
+                                             s_stride, _dev_ptr(V, mlp.dtype, "V"), S, v_stride, _dev_ptr(u, mlp.dtype, "u"),
+                                             _dev_ptr(op, mlp.dtype, "op"), c_void_p(workspace.data_ptr()),
+                                             workspace.numel() * workspace.element_size(), _stream_ptr()))
     return u, op

@@ -444,6 +444,60 @@ int ctm_biharmonic_rand(const ctm_mlp *m, const void *x, long N, const void *V, 
   return run_operator(m, 4, x, N, V, S, v_point_stride, D, 1, scale, u, op, ws, ws_bytes, stream, "ctm_biharmonic_rand");
 }
 
+size_t ctm_weighted_laplacian_rand_workspace_bytes(const ctm_mlp *m, long N, int K, int S, long sigma_point_stride,
+                                                   long v_point_stride) {
+  if (!m) { fail(CTM_ERR_NULL, "ctm_weighted_laplacian_rand_workspace_bytes: mlp handle is NULL"); return 0; }
+  if (N < 1 || K < 1 || S < 0) {
+    fail(CTM_ERR_SHAPE, "ctm_weighted_laplacian_rand_workspace_bytes: need N >= 1, K >= 1, S >= 0");
+    return 0;
+  }
+  const int R = S > 0 ? S : K;
+  const size_t base = workspace_layout(m, 2, N, split_dirs(2, R).first).total;
+  if (S == 0) return base;  // exact: the directions are columns of sigma, read in place
+  const bool per_point = sigma_point_stride != 0 || v_point_stride != 0;
+  return base + round256((size_t)(per_point ? N : 1) * S * m->dims[0] * elem_size(m->dtype));
+}
+
+int ctm_weighted_laplacian_rand(const ctm_mlp *m, const void *x, long N, const void *sigma, int K, long sigma_point_stride,
+                                const void *V, int S, long v_point_stride, void *u, void *op, void *ws, size_t ws_bytes,
+                                void *stream) {
+  const char *who = "ctm_weighted_laplacian_rand";
+  if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
+  if (!sigma) return fail(CTM_ERR_NULL, "%s: sigma is NULL", who);
+  if (K < 1) return fail(CTM_ERR_SHAPE, "%s: sigma has %d columns, need at least 1", who, K);
+  const long D = m->dims[0];
+  if (sigma_point_stride != 0 && sigma_point_stride != D * K)
+    return fail(CTM_ERR_SHAPE, "%s: sigma_point_stride = %ld, must be 0 (shared) or D*K = %ld", who, sigma_point_stride, D * K);
+  if (!V) {
+    if (S != 0) return fail(CTM_ERR_SHAPE, "%s: V = NULL selects the exact operator, so S must be 0 (got %d)", who, S);
+    // directions are the K columns of sigma_n: element (n, k, d) at sigma[n*stride + d*K + k]
+    return run_operator(m, 2, x, N, sigma, K, sigma_point_stride, 1, K, 1.0, u, op, ws, ws_bytes, stream, who);
+  }
+  if (S < 1) return fail(CTM_ERR_SHAPE, "%s: %d samples, need at least 1", who, S);
+  if (v_point_stride != 0 && v_point_stride != (long)S * K)
+    return fail(CTM_ERR_SHAPE, "%s: v_point_stride = %ld, must be 0 (shared) or S*K = %ld", who, v_point_stride, (long)S * K);
+  if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
+  if (!ws) return fail(CTM_ERR_NULL, "%s: workspace is NULL", who);
+  const size_t need = ctm_weighted_laplacian_rand_workspace_bytes(m, N, K, S, sigma_point_stride, v_point_stride);
+  if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: workspace must be 256-byte aligned", who);
+  if (misaligned(sigma, es) || misaligned(V, es))
+    return fail(CTM_ERR_ALIGN, "%s: sigma and V must be aligned to the element size", who);
+  const bool per_point = sigma_point_stride != 0 || v_point_stride != 0;
+  const long Nd = per_point ? N : 1;
+  const size_t dbytes = round256((size_t)Nd * S * D * es);
+  void *dirs = (char *)ws + (need - dbytes);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  hipError_t e = (m->dtype == CTM_F64)
+                     ? launch_sigma_dirs<double>((const double *)sigma, sigma_point_stride, (const double *)V, v_point_stride,
+                                                 (double *)dirs, Nd, S, (int)D, K, st)
+                     : launch_sigma_dirs<float>((const float *)sigma, sigma_point_stride, (const float *)V, v_point_stride,
+                                                (float *)dirs, Nd, S, (int)D, K, st);
+  if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
+  return run_operator(m, 2, x, N, dirs, S, per_point ? (long)S * D : 0, D, 1, 1.0 / S, u, op, ws, need - dbytes, stream, who);
+}
+
 int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, long long *den) {
   if (!i || !j || !num || !den) return fail(CTM_ERR_NULL, "ctm_interpolation_gamma: NULL argument");
   if (I < 1 || I > 4) return fail(CTM_ERR_SHAPE, "ctm_interpolation_gamma: I = %d, need 1..4", I);

@@ -85,6 +85,11 @@ hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp
 // family 1: 3 e_d1 + e_d2, d1 != d2 (D(D-1) rows); family 2: 2 e_d1 + 2 e_d2, d1 < d2 (D(D-1)/2 rows).
 template <typename T> hipError_t launch_biharm_dirs(T *V, int D, int family, hipStream_t s);
 
+// out[n][s][:] = sigma_n v_{n,s}; sigma_n = sigma + n*sig_stride ([D][K]), v_{n,s} = V + n*v_stride + s*K; Nd = N or 1
+template <typename T>
+hipError_t launch_sigma_dirs(const T *sigma, long sig_stride, const T *V, long v_stride, T *out, long Nd, int S, int D, int K,
+                             hipStream_t s);
+
 template <typename T> struct FinalArgs {
   const T *pair;  // [N][2][ld] : h_0 and the collapsed h_K of the last hidden layer
   const T *w;     // [ld] zero-padded last-layer weights

@@ -103,6 +103,34 @@ template <typename T> hipError_t launch_biharm_dirs(T *V, int D, int family, hip
 template hipError_t launch_biharm_dirs<float>(float *, int, int, hipStream_t);
 template hipError_t launch_biharm_dirs<double>(double *, int, int, hipStream_t);
 
+// ---- directions of the stochastic weighted Laplacian (Sec. 3.2, Eq. 8, stochastic case): sigma_n v_{n,s}
+template <typename T>
+__global__ void sigma_dirs_kernel(const T *sigma, long sig_stride, const T *V, long v_stride, T *out, long Nd, int S, int D, int K) {
+  const long total = Nd * S * D;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int d = (int)(i % D);
+    const long ns = i / D;
+    const int sidx = (int)(ns % S);
+    const long n = ns / S;
+    const T *sg = sigma + n * sig_stride + (long)d * K;
+    const T *v = V + n * v_stride + (long)sidx * K;
+    T acc = T(0);
+    for (int k = 0; k < K; ++k) acc += sg[k] * v[k];
+    out[i] = acc;
+  }
+}
+
+template <typename T>
+hipError_t launch_sigma_dirs(const T *sigma, long sig_stride, const T *V, long v_stride, T *out, long Nd, int S, int D, int K,
+                             hipStream_t s) {
+  long blocks = (Nd * S * D + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(sigma_dirs_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, sigma, sig_stride, V, v_stride, out, Nd, S, D, K);
+  return hipGetLastError();
+}
+template hipError_t launch_sigma_dirs<float>(const float *, long, const float *, long, float *, long, int, int, int, hipStream_t);
+template hipError_t launch_sigma_dirs<double>(const double *, long, const double *, long, double *, long, int, int, int, hipStream_t);
+
 // ---- last layer (App. H: g is linear, bias on the 0-th coefficient only) ------------------
 //   u_n = w . h_0(n) + b        op_n = scale * (w . h_K(n))
 // One wavefront per point; lanes stride the features and the 64 partial sums are folded

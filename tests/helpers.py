@@ -24,6 +24,8 @@ def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None):
         u, o = ctm.ctm_biharmonic_rand(mlp, x, t(arrs["V"]))
     elif op == "biharmonic_exact":
         u, o = ctm.ctm_biharmonic_exact(mlp, x)
+    elif op == "weighted_laplacian_rand":
+        u, o = ctm.ctm_weighted_laplacian_rand(mlp, x, t(arrs["sigma"]), t(arrs.get("Vk")))
     else:
         raise ValueError(op)
     torch.cuda.synchronize()
@@ -50,6 +52,12 @@ def oracle_run(arrs, op, act="tanh", idx=None, mode="directional"):
         return orc.weighted_laplacian(arrs["Ws"], arrs["bs"], x, arrs["sigma"], act=act, mode=mode)
     if op == "biharmonic_rand":
         return orc.biharmonic_rand(arrs["Ws"], arrs["bs"], x, V, act=act)
+    if op == "weighted_laplacian_rand":
+        sg, Vk = arrs["sigma"], arrs.get("Vk")
+        if idx is not None:
+            sg = sg[sel] if sg.ndim == 3 else sg
+            Vk = Vk[sel] if Vk is not None and Vk.ndim == 3 else Vk
+        return orc.weighted_laplacian_rand(arrs["Ws"], arrs["bs"], x, sg, Vk, act=act)
     if op == "biharmonic_exact":
         return orc.value(arrs["Ws"], arrs["bs"], x, act=act), orc.biharmonic_exact(arrs["Ws"], arrs["bs"], x, act=act)
     raise ValueError(op)

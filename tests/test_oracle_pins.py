@@ -330,6 +330,30 @@ def test_estimators_are_unbiased_statistically():
     assert np.all(se4 < 0.25 * np.abs(bi) + 0.05)
 
 
+def test_stochastic_weighted_laplacian_special_cases_and_mean():
+    # Eq. 8: directions sigma v_s.  V = I_K gives K * (1/K) ... i.e. the exact operator; a point-dependent sigma
+    # must equal a loop over points; the sample mean converges to Tr(sigma sigma^T H).
+    Ws, bs = tiny_mlp((4, 10, 10, 1), 21)
+    rng = np.random.default_rng(21)
+    x = rng.random((3, 4))
+    sig = rng.standard_normal((3, 4, 2))
+    _, exact = orc.weighted_laplacian_rand(Ws, bs, x, sig)
+    for n in range(3):
+        np.testing.assert_allclose(exact[n], orc.weighted_laplacian(Ws, bs, x[n:n + 1], sig[n])[1][0], rtol=1e-12)
+    _, viaI = orc.weighted_laplacian_rand(Ws, bs, x, sig, np.eye(2))
+    np.testing.assert_allclose(viaI * 2, exact, rtol=1e-12)
+    S = 20000
+    V = rng.standard_normal((3, S, 2))
+    H = orc.hessian(Ws, bs, x)
+    dirs = np.einsum("ndk,nsk->nsd", sig, V)
+    samples = np.einsum("nsd,nde,nse->ns", dirs, H, dirs)
+    _, est = orc.weighted_laplacian_rand(Ws, bs, x, sig, V)
+    np.testing.assert_allclose(est, samples.mean(axis=1), rtol=1e-12)
+    assert np.all(np.abs(est - exact) <= 5 * samples.std(axis=1) / math.sqrt(S))
+    _, shared = orc.weighted_laplacian_rand(Ws, bs, x, sig[0], V[0])
+    np.testing.assert_allclose(shared[0], est[0], rtol=1e-12)
+
+
 def test_biharmonic_exact_equals_laplacian_of_laplacian_by_finite_differences():
     Ws, bs = tiny_mlp((3, 8, 1), 14)
     x = np.random.default_rng(14).random((2, 3))

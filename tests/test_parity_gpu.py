@@ -153,6 +153,21 @@ def test_biharmonic_shapes(dtype, dims, N, S, per_point):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("sigma_per_point,v_mode", [(False, "shared"), (False, "per_point"), (True, "shared"), (True, "per_point"),
+                                                    (True, None), (False, None)])
+def test_stochastic_and_point_dependent_weighted_laplacian(dtype, sigma_per_point, v_mode):
+    # Eq. 8 stochastic case: directions sigma_n v_{n,s}; v_mode None = exact operator with the columns of sigma_n
+    dims, N, K, S = (9, 40, 24, 1), 27, 3, 7
+    rng = np.random.default_rng(5)
+    arrs = small_case(dims, N, dtype, seed=K)
+    arrs["sigma"] = (rng.standard_normal((N, 9, K) if sigma_per_point else (9, K)) / 3).astype(dtype)
+    arrs["Vk"] = None if v_mode is None else rng.standard_normal((N, S, K) if v_mode == "per_point" else (S, K)).astype(dtype)
+    print(f"case weighted rand sigma_per_point={sigma_per_point} v={v_mode} {dtype.__name__}", flush=True)
+    check(gpu_run(arrs, "weighted_laplacian_rand"), oracle_run(arrs, "weighted_laplacian_rand"), tol_of(dtype),
+          f"weighted rand {sigma_per_point} {v_mode}")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("dims,N", [((1, 12, 1), 9), ((2, 16, 16, 1), 21), ((5, 32, 24, 1), 13), ((7, 20, 1), 5)])
 def test_exact_biharmonic_by_interpolation(dtype, dims, N):
     # three collapsed 4-jet families combined with gamma_{(2,2),j} (Sec. 3.3, App. E.1) against the full
