@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", help="c1..c5 (c2 is the configuration the metric is quoted on)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 skips it")
+    ap.add_argument("--taylor", choices=["collapsed", "standard"], default="collapsed",
+                    help="standard = the un-collapsed comparison path (1 + K*R rows per point); c1..c5 only")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -113,10 +115,19 @@ def main():
         ws_bytes = ctm.binding.lib().ctm_biharmonic_exact_workspace_bytes(mlp.handle, w.N)
     else:
         ws_bytes = ctm.ctm_workspace_bytes(mlp, K, w.N, R)
+    std = args.taylor == "standard"
+    if std:
+        if w.op not in ("laplacian", "biharmonic_rand", "weighted_laplacian"):
+            sys.exit("bench.py: --taylor standard covers the laplacian / weighted_laplacian / biharmonic_rand workloads")
+        ws_bytes = ctm.binding.lib().ctm_workspace_bytes_standard(mlp.handle, K, w.N, R)
+        Vstd = sigma.t().contiguous() if w.op == "weighted_laplacian" else V
+        std_scale = 1.0 / (3.0 * R) if K == 4 else arrs.get("scale", 1.0)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
     def step():
-        if w.op == "laplacian":
+        if std:
+            ctm.ctm_taylor_standard(mlp, K, x, Vstd, std_scale, u, op, ws)
+        elif w.op == "laplacian":
             ctm.ctm_laplacian(mlp, x, V, arrs.get("scale", 1.0), u, op, ws)
         elif w.op == "weighted_laplacian":
             ctm.ctm_weighted_laplacian(mlp, x, sigma, u, op, ws)
@@ -148,7 +159,7 @@ def main():
     for _ in range(args.steps):
         step()
     ms, launches = ctm.ctm_profile_end()
-    rho = ctm.ctm_rows_per_point(K, R)
+    rho = 1 + K * R if std else ctm.ctm_rows_per_point(K, R)
     if w.op == "biharmonic_exact":
         D = w.dims[0]
         fams = [D, D * (D - 1), D * (D - 1) // 2]
@@ -172,7 +183,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.op}, tanh MLP {'-'.join(map(str, w.dims))}, N={w.N}, "
-                               f"{w.directions} directions R={R}, collapsed order-{K} Taylor mode, {rho} rows/point"},
+                               f"{w.directions} directions R={R}, {args.taylor} order-{K} Taylor mode, {rho} rows/point"},
         "roofline": roofline,
     }
     if args.cpu_seconds > 0:

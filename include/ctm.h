@@ -147,6 +147,19 @@ int ctm_biharmonic_rand(const ctm_mlp *mlp, const void *x, long N, const void *V
                         size_t workspace_bytes, void *stream);
 
 /*
+ * The same sums computed by STANDARD (un-collapsed) Taylor mode, for comparison only: every direction
+ * carries its own order-K coefficient through the network (1 + K*R rows per point, Sec. 3.1) and the sum
+ * over directions is taken after the last layer.  K = 2 or 4; other arguments as in ctm_laplacian
+ * (K = 4: op = scale * sum_r <d^4 f, v_r^4>, pass scale = 1/(3S) for the biharmonic estimator).
+ * Mathematically equal to the collapsed calls; it exists to measure what collapsing saves on this GPU.
+ * Workspace: ctm_workspace_bytes_standard(mlp, K, N, R).
+ */
+size_t ctm_workspace_bytes_standard(const ctm_mlp *mlp, int K, long N, int R);
+int ctm_taylor_standard(const ctm_mlp *mlp, int K, const void *x, long N, const void *V, int R,
+                        long v_point_stride, double scale, void *u, void *op, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
  * Exact biharmonic  op[n] = sum_{d1,d2} d^4 f / dx_{d1}^2 dx_{d2}^2 (x_n)          (Sec. 3.3, Eq. 9 exact case)
  * by interpolation with three collapsed families of 4-jets (Sec. 3.3 Eq. 12; App. E.1, last display):
  *   op = 1/24 [ (2 D g40 + 2 g31 + g22) sum_d <d^4 f,(4 e_d)^4> + 2 g31 sum_{d1 != d2} <d^4 f,(3 e_d1 + e_d2)^4>

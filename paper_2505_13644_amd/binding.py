@@ -37,6 +37,9 @@ SIGNATURES = {
     "ctm_weighted_laplacian_rand_workspace_bytes": (c_size_t, [c_void_p, c_long, c_int, c_int, c_long, c_long]),
     "ctm_weighted_laplacian_rand": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_int, c_long,
                                             c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "ctm_workspace_bytes_standard": (c_size_t, [c_void_p, c_int, c_long, c_int]),
+    "ctm_taylor_standard": (c_int, [c_void_p, c_int, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p,
+                                    c_void_p, c_size_t, c_void_p]),
     "ctm_biharmonic_exact_workspace_bytes": (c_size_t, [c_void_p, c_long]),
     "ctm_biharmonic_exact": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "ctm_interpolation_gamma": (c_int, [c_int, POINTER(c_int), POINTER(c_int), POINTER(ctypes.c_longlong),
@@ -321,4 +324,31 @@ def ctm_weighted_laplacian_rand(mlp: Mlp, x, sigma, V=None, u=None, op=None, wor
                                              s_stride, _dev_ptr(V, mlp.dtype, "V"), S, v_stride, _dev_ptr(u, mlp.dtype, "u"),
                                              _dev_ptr(op, mlp.dtype, "op"), c_void_p(workspace.data_ptr()),
                                              workspace.numel() * workspace.element_size(), _stream_ptr()))
+    return u, op
+
+
+def ctm_taylor_standard(mlp: Mlp, K, x, V=None, scale=1.0, u=None, op=None, workspace=None):
+    """Un-collapsed Taylor mode of order K (comparison path).  V as in ctm_laplacian.  Returns (u, op)."""
+    torch = _torch()
+    _check_shapes(mlp, x, V)
+    N, D = x.shape
+    if V is None:
+        R, stride = D, 0
+    elif V.dim() == 2:
+        R, stride = V.shape[0], 0
+    else:
+        R, stride = V.shape[1], V.shape[1] * V.shape[2]
+    need = lib().ctm_workspace_bytes_standard(mlp.handle, K, N, R)
+    if need == 0:
+        raise CtmError(-2, ctm_last_error())
+    if u is None:
+        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if op is None:
+        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    _check(lib().ctm_taylor_standard(mlp.handle, K, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(V, mlp.dtype, "V"), R, stride,
+                                     float(scale), _dev_ptr(u, mlp.dtype, "u"), _dev_ptr(op, mlp.dtype, "op"),
+                                     c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                     _stream_ptr()))
     return u, op

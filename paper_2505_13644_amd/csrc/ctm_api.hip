@@ -57,14 +57,19 @@ hipError_t prof_mark(hipStream_t st, int cls_of_preceding) {
   return hipSuccess;
 }
 
-long rows_per_point(int K, int R) { return 1L + (long)(K - 1) * R + 1L; }
+// collapsed: 1 + (K-1) R + 1 rows; un-collapsed ("standard"): 1 + K R rows (Sec. 3.1)
+long rows_per_point(int K, int R, bool standard = false) {
+  return standard ? 1L + (long)K * R : 1L + (long)(K - 1) * R + 1L;
+}
 
 // Largest direction count whose rows fit one tile of kMaxRowBlocks MFMA row blocks.
-int max_dirs_per_pass(int K) { return (16 * kMaxRowBlocks - 2) / (K - 1); }
+int max_dirs_per_pass(int K, bool standard = false) {
+  return standard ? (16 * kMaxRowBlocks - 1) / K : (16 * kMaxRowBlocks - 2) / (K - 1);
+}
 
 // Pick the row-block count that wastes the fewest MFMA rows (ties: the taller tile).
-PassPlan plan_pass(int K, int R) {
-  PassPlan best{R, (int)rows_per_point(K, R), 0, 0};
+PassPlan plan_pass(int K, int R, bool standard = false) {
+  PassPlan best{R, (int)rows_per_point(K, R, standard), 0, 0};
   double best_eff = -1.0;
   static const int kChoices[] = {4, 8, 9, 12, 13, 16};
   for (int MB : kChoices) {  // ascending, so a tie goes to the taller tile
@@ -131,8 +136,8 @@ Frac interp_gamma(int I, const int *iv, const int *jv) {
 struct Split {
   int n_passes, first, lastR;  // passes 0..n-2 take `first` directions, the last one `lastR`
 };
-Split split_dirs(int K, int R) {
-  const int cap = max_dirs_per_pass(K);
+Split split_dirs(int K, int R, bool standard = false) {
+  const int cap = max_dirs_per_pass(K, standard);
   Split s;
   s.n_passes = (R + cap - 1) / cap;
   s.first = (R + s.n_passes - 1) / s.n_passes;
@@ -161,13 +166,13 @@ int tile_cols_of(ctm_dtype t) { return t == CTM_F64 ? tile_cols<double>() : tile
 struct Layout {
   size_t block_bytes, pair_bytes, dirs_bytes, total;
 };
-Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
+Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass, bool standard = false) {
   const size_t es = elem_size(m->dtype);
   int maxld = 0;
   for (int l = 0; l + 1 < m->L; ++l) maxld = m->ld[l] > maxld ? m->ld[l] : maxld;  // inputs of hidden layers
   Layout lo;
-  lo.block_bytes = round256((size_t)N * (size_t)rows_per_point(K, Rpass) * (size_t)maxld * es);
-  lo.pair_bytes = round256((size_t)N * 2 * (size_t)m->ld[m->L - 1] * es);
+  lo.block_bytes = round256((size_t)N * (size_t)rows_per_point(K, Rpass, standard) * (size_t)maxld * es);
+  lo.pair_bytes = round256((size_t)N * (standard ? 1 + (size_t)Rpass : 2) * (size_t)m->ld[m->L - 1] * es);
   lo.dirs_bytes = round256((size_t)Rpass * (size_t)m->ld[1] * es);  // W_1 v_r rows
   lo.total = 2 * lo.block_bytes + lo.pair_bytes + lo.dirs_bytes;
   return lo;
@@ -175,9 +180,10 @@ Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass) {
 
 template <typename T>
 int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, long sr, long sd,
-               double scale, T *u, T *op, void *ws, hipStream_t st, bool accumulate_first = false) {
-  const Split sp = split_dirs(K, R);
-  const Layout lo = workspace_layout(m, K, N, sp.first);
+               double scale, T *u, T *op, void *ws, hipStream_t st, bool accumulate_first = false,
+               bool standard = false) {
+  const Split sp = split_dirs(K, R, standard);
+  const Layout lo = workspace_layout(m, K, N, sp.first, standard);
   T *buf[2] = {reinterpret_cast<T *>(ws), reinterpret_cast<T *>((char *)ws + lo.block_bytes)};
   T *pair = reinterpret_cast<T *>((char *)ws + 2 * lo.block_bytes);
   T *dirs = reinterpret_cast<T *>((char *)ws + 2 * lo.block_bytes + lo.pair_bytes);
@@ -185,7 +191,8 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
   if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
   for (int pass = 0; pass < sp.n_passes; ++pass) {
     const int Rp = (pass == sp.n_passes - 1) ? sp.lastR : sp.first;
-    const PassPlan pl = plan_pass(K, Rp);
+    const PassPlan pl = plan_pass(K, Rp, standard);
+    const int last_rows = standard ? 1 + Rp : 2;
     const bool fast_first = first_layer_fast_path(m->dims[0], sn);
     const T *in = buf[1];
     int l_begin = 0;
@@ -200,6 +207,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       fa.N = N; fa.v_sr = sr; fa.v_sd = sd;
       fa.D = m->dims[0]; fa.ld0 = m->ld[0]; fa.ld1 = m->ld[1]; fa.rho = pl.rho; fa.order = K; fa.R = Rp;
       fa.r0 = pass * sp.first; fa.last = last ? 1 : 0; fa.act = (int)m->act;
+      fa.standard = standard ? 1 : 0; fa.out_rows = last ? last_rows : pl.rho;
       e = launch_first<T>(fa, st);
       if (e != hipSuccess) return fail_hip(e, "first-layer kernel launch");
       (void)prof_mark(st, 0);
@@ -210,6 +218,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       sa.x = x; sa.V = V; sa.out = buf[1]; sa.N = N;
       sa.v_sn = sn; sa.v_sr = sr; sa.v_sd = sd;
       sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = pass * sp.first;
+      sa.standard = standard ? 1 : 0; sa.R = Rp;
       e = launch_seed<T>(sa, st);
       if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
       (void)prof_mark(st, 0);
@@ -222,13 +231,14 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       la.n_points = N; la.n_row_tiles = (N + pl.P - 1) / pl.P; la.n_col_tiles = m->col_tiles[l];
       la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[l]; la.ldout = m->ld[l + 1];
       la.order = K; la.R = Rp; la.last = last ? 1 : 0; la.act = (int)m->act;
+      la.standard = standard ? 1 : 0; la.out_rows = last ? last_rows : pl.rho;
       e = launch_layer<T>(la, pl.MB, st);
       if (e != hipSuccess) return fail_hip(e, "layer kernel launch");
       (void)prof_mark(st, 1);
       in = out;
     }
     FinalArgs<T> fa;
-    fa.pair = pair; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
+    fa.pair = pair; fa.nk = standard ? Rp : 1; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
     fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = (pass > 0 || accumulate_first) ? 1 : 0;
     e = launch_final<T>(fa, st);
     if (e != hipSuccess) return fail_hip(e, "final kernel launch");
@@ -237,18 +247,21 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
   return CTM_OK;
 }
 
+}  // namespace
+extern "C" size_t ctm_workspace_bytes_standard(const ctm_mlp *m, int K, long N, int R);
+namespace {
 bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 int run_operator(const ctm_mlp *m, int K, const void *x, long N, const void *V, int R, long sn, long sr,
                  long sd, double scale, void *u, void *op, void *ws, size_t ws_bytes, void *stream,
-                 const char *who) {
+                 const char *who, bool standard = false) {
   if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
   if (!x) return fail(CTM_ERR_NULL, "%s: x is NULL", who);
   if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
   if (R < 1) return fail(CTM_ERR_SHAPE, "%s: %d directions, need at least 1", who, R);
-  if (N > (1L << 40) / rows_per_point(K, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
+  if (N > (1L << 40) / rows_per_point(K, R, standard)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
   if (!ws) return fail(CTM_ERR_NULL, "%s: workspace is NULL", who);
-  const size_t need = ctm_workspace_bytes(m, K, N, R);
+  const size_t need = standard ? ctm_workspace_bytes_standard(m, K, N, R) : ctm_workspace_bytes(m, K, N, R);
   if (ws_bytes < need)
     return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
   const size_t es = elem_size(m->dtype);
@@ -258,9 +271,9 @@ int run_operator(const ctm_mlp *m, int K, const void *x, long N, const void *V, 
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
     return run_passes<double>(m, K, (const double *)x, N, (const double *)V, R, sn, sr, sd, scale, (double *)u,
-                              (double *)op, ws, st);
+                              (double *)op, ws, st, false, standard);
   return run_passes<float>(m, K, (const float *)x, N, (const float *)V, R, sn, sr, sd, scale, (float *)u,
-                           (float *)op, ws, st);
+                           (float *)op, ws, st, false, standard);
 }
 
 template <typename T> hipError_t pack_all(ctm_mlp *m, const void *const *W, const void *const *b, hipStream_t st) {
@@ -413,6 +426,28 @@ size_t ctm_workspace_bytes(const ctm_mlp *m, int K, long N, int R) {
     return 0;
   }
   return workspace_layout(m, K, N, split_dirs(K, R).first).total;
+}
+
+size_t ctm_workspace_bytes_standard(const ctm_mlp *m, int K, long N, int R) {
+  if (!m) { fail(CTM_ERR_NULL, "ctm_workspace_bytes_standard: mlp handle is NULL"); return 0; }
+  if ((K != 2 && K != 4) || N < 1 || R < 1) {
+    fail(CTM_ERR_SHAPE, "ctm_workspace_bytes_standard: need K in {2,4}, N >= 1, R >= 1 (got %d, %ld, %d)", K, N, R);
+    return 0;
+  }
+  return workspace_layout(m, K, N, split_dirs(K, R, true).first, true).total;
+}
+
+int ctm_taylor_standard(const ctm_mlp *m, int K, const void *x, long N, const void *V, int R, long v_point_stride,
+                        double scale, void *u, void *op, void *ws, size_t ws_bytes, void *stream) {
+  const char *who = "ctm_taylor_standard";
+  if (K != 2 && K != 4) return fail(CTM_ERR_UNSUPPORTED, "%s: order K = %d, only 2 and 4 are built", who, K);
+  if (m && !V && R != m->dims[0])
+    return fail(CTM_ERR_SHAPE, "%s: V = NULL selects the standard basis, so R must be D = %d (got %d)", who, m->dims[0], R);
+  if (m && R >= 1 && v_point_stride != 0 && v_point_stride != (long)R * m->dims[0])
+    return fail(CTM_ERR_SHAPE, "%s: v_point_stride = %ld, must be 0 (shared) or R*D = %ld", who, v_point_stride,
+                (long)R * m->dims[0]);
+  const long D = m ? m->dims[0] : 0;
+  return run_operator(m, K, x, N, V, R, v_point_stride, D, 1, scale, u, op, ws, ws_bytes, stream, who, true);
 }
 
 int ctm_laplacian(const ctm_mlp *m, const void *x, long N, const void *V, int R, long v_point_stride, double scale,

@@ -71,8 +71,8 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 
   const long ld = a.ld1;
   const int rho = a.rho;
-  T *o = a.last ? a.out + (n0 * 2) * ld + j : a.out + (n0 * rho) * ld + j;
-  const long pstep = (a.last ? 2 : rho) * ld;
+  T *o = a.out + (n0 * a.out_rows) * ld + j;
+  const long pstep = (long)a.out_rows * ld;
   const T tanh_on = a.act == 0 ? T(1) : T(0);
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
@@ -82,6 +82,29 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
     const T z1 = a.Z1[(long)r * ld + j];
     const T z1s = z1 * z1;
     mom += (a.order == 2) ? z1s : z1s * z1s;
+    if (a.standard) {
+      // un-collapsed layout: every direction has its own highest-order row, d_K * z1^K at this layer
+      const T zK = (a.order == 2) ? z1s : z1s * z1s;
+      const int K = a.order;
+      const long row1 = (K == 2) ? 1 + r : 1 + 4 * r;            // first-order row of direction r
+      const long rowK = a.last ? 1 + r : ((K == 2) ? 1 + a.R + r : 4 + 4 * r);
+#pragma unroll
+      for (int p = 0; p < kFirstPoints; ++p)
+        if (p < np) {
+          const T d2 = T(-2) * t[p] * d1[p] * tanh_on;
+          const T dK = (K == 2) ? d2 : T(8) * t[p] * d1[p] * (T(2) - T(3) * t[p] * t[p]) * tanh_on;
+          o[p * pstep + rowK * ld] = dK * zK;
+          if (!a.last) {
+            o[p * pstep + row1 * ld] = d1[p] * z1;
+            if (K == 4) {
+              const T d3 = d1[p] * (T(6) * t[p] * t[p] - T(2)) * tanh_on;
+              o[p * pstep + (row1 + 1) * ld] = d2 * z1s;
+              o[p * pstep + (row1 + 2) * ld] = d3 * z1s * z1;
+            }
+          }
+        }
+      continue;
+    }
     if (a.last) continue;
     if (a.order == 2) {
       T *orow = o + (long)(1 + r) * ld;
@@ -102,6 +125,7 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
         }
     }
   }
+  if (a.standard) return;  // no collapsed row
   T *olast = o + (long)(a.last ? 1 : rho - 1) * ld;
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
@@ -126,7 +150,7 @@ template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t
     const long nc = (chunks - c0) < 65535 ? (chunks - c0) : 65535;
     FirstArgs<T> b = a;
     b.x = a.x + c0 * kFirstPoints * a.D;
-    b.out = a.out + c0 * kFirstPoints * (a.last ? 2 : a.rho) * (long)a.ld1;
+    b.out = a.out + c0 * kFirstPoints * (long)a.out_rows * a.ld1;
     b.N = a.N - c0 * kFirstPoints;
     if (b.N > nc * kFirstPoints) b.N = nc * kFirstPoints;
     hipLaunchKernelGGL(first_layer_kernel<T>, dim3((a.ld1 + 255) / 256, (unsigned)nc), dim3(256), 0, s, b);

@@ -31,7 +31,7 @@ template <typename T> struct LayerArgs {
   const T *Hin;      // [n_points * rho][ldin] coefficient block entering the layer
   const T *W;        // [n_col_tiles * tile_cols][ldin] zero-padded weights
   const T *bias;     // [n_col_tiles * tile_cols] zero-padded bias
-  T *Hout;           // last == 0: [n_points * rho][ldout]; last == 1: [n_points][2][ldout]
+  T *Hout;           // [n_points * out_rows][ldout]
   long n_points;
   long n_row_tiles;  // ceil(n_points / P)
   int n_col_tiles;
@@ -41,8 +41,10 @@ template <typename T> struct LayerArgs {
   int ldout;
   int order;         // 2 or 4
   int R;             // directions in this pass
-  int last;          // emit only the 0-th and the collapsed row
+  int last;          // emit only the 0-th and the highest-order row(s)
   int act;           // 0 tanh, 1 identity
+  int standard;      // 1: un-collapsed Taylor mode (1 + K*R rows per point), for comparison
+  int out_rows;      // rows per point in Hout: rho, or when last: 2 (collapsed) / 1 + R (standard)
 };
 
 // Launch the stacked GEMM + fused jet rule for one layer.  MB in {4, 8, 9, 12, 13, 16}.
@@ -59,6 +61,8 @@ template <typename T> struct SeedArgs {
   long v_sd;
   int D, ld, rho, order;
   int r0;       // index of this pass's first direction
+  int standard; // row layout of un-collapsed Taylor mode
+  int R;        // directions in this pass
 };
 template <typename T> hipError_t launch_seed(const SeedArgs<T> &a, hipStream_t s);
 
@@ -73,6 +77,8 @@ template <typename T> struct FirstArgs {
   long N;
   long v_sr, v_sd;
   int D, ld0, ld1, rho, order, R, r0, last, act;
+  int standard;   // un-collapsed row layout
+  int out_rows;   // rows per point in out
 };
 bool first_layer_fast_path(int D, long v_point_stride);
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s);
@@ -91,7 +97,8 @@ hipError_t launch_sigma_dirs(const T *sigma, long sig_stride, const T *V, long v
                              hipStream_t s);
 
 template <typename T> struct FinalArgs {
-  const T *pair;  // [N][2][ld] : h_0 and the collapsed h_K of the last hidden layer
+  const T *pair;  // [N][1 + nk][ld] : h_0 and the nk highest-order rows of the last hidden layer
+  int nk;         // 1 (collapsed) or R (un-collapsed: summed here)
   const T *w;     // [ld] zero-padded last-layer weights
   const T *b;     // [1]
   T *u;           // may be nullptr

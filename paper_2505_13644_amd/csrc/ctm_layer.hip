@@ -258,7 +258,7 @@ void layer_kernel(const LayerArgs<T> a) {
     for (int p = wave; p < p_valid; p += kThreads / 64) {
       const T *c = Cs + (long)p * rho * CROW + j;
       const long n = p0 + p;
-      T *o = a.last ? a.Hout + (n * 2) * a.ldout + jg : a.Hout + (n * rho) * a.ldout + jg;
+      T *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
       const long ostep = a.ldout;
       const T z0 = c[0] + bias;
       T t, d1, d2;
@@ -272,7 +272,40 @@ void layer_kernel(const LayerArgs<T> a) {
         d2 = T(0);
       }
       o[0] = t;
-      if (a.order == 2) {
+      if (a.standard) {
+        // un-collapsed ("standard") Taylor mode, kept for comparison: every direction carries its own
+        // highest-order row (1 + K*R rows per point) and the sum over directions is taken after the last layer
+        if (a.order == 2) {  // rows 1..R first order, R+1..2R second order
+          for (int r = 0; r < R; ++r) {
+            const T z1 = c[(long)(1 + r) * CROW], z2 = c[(long)(1 + R + r) * CROW];
+            const T h2 = d1 * z2 + d2 * z1 * z1;
+            if (a.last) {
+              o[(1 + r) * ostep] = h2;
+            } else {
+              o[(1 + r) * ostep] = d1 * z1;
+              o[(1 + R + r) * ostep] = h2;
+            }
+          }
+        } else {  // rows 1+4r .. 4+4r: orders 1..4 of direction r
+          const T d3 = a.act == 0 ? d1 * (T(6) * t * t - T(2)) : T(0);
+          const T d4 = a.act == 0 ? T(8) * t * d1 * (T(2) - T(3) * t * t) : T(0);
+          for (int r = 0; r < R; ++r) {
+            const T *cr = c + (long)(1 + 4 * r) * CROW;
+            const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW], z4 = cr[3 * CROW];
+            const T z1s = z1 * z1;
+            const T h4 = d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2 + d1 * z4;
+            if (a.last) {
+              o[(1 + r) * ostep] = h4;
+            } else {
+              T *orow = o + (long)(1 + 4 * r) * ostep;
+              orow[0] = d1 * z1;
+              orow[ostep] = d2 * z1s + d1 * z2;
+              orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+              orow[3 * ostep] = h4;
+            }
+          }
+        }
+      } else if (a.order == 2) {
         T s = T(0);
         int r = 1;
         for (; r + 3 <= R; r += 4) {  // four independent LDS reads in flight per trip

@@ -19,9 +19,12 @@ template <typename T> __global__ void seed_kernel(const SeedArgs<T> a) {
     if (k < a.D) {
       if (c == 0) {
         v = a.x[n * a.D + k];
-      } else if (c < a.rho - 1) {
+      } else if (a.standard || c < a.rho - 1) {
         int r = -1;
-        if (a.order == 2) r = c - 1;
+        if (a.standard) {  // order 2: rows 1..R; order 4: rows 1 + 4r
+          if (a.order == 2) r = c <= a.R ? c - 1 : -1;
+          else if ((c - 1) % 4 == 0) r = (c - 1) / 4;
+        } else if (a.order == 2) r = c - 1;
         else if ((c - 1) % 3 == 0) r = (c - 1) / 3;
         if (r >= 0) {
           r += a.r0;
@@ -139,13 +142,14 @@ template <typename T> __global__ __launch_bounds__(256) void final_kernel(const 
   const int lane = threadIdx.x & 63;
   const long n = blockIdx.x * 4L + (threadIdx.x >> 6);
   if (n >= a.N) return;
-  const T *h0 = a.pair + n * 2 * a.ld;
-  const T *hk = h0 + a.ld;
+  const T *h0 = a.pair + n * (1 + a.nk) * a.ld;
   T s0 = T(0), sk = T(0);
   for (int k = lane; k < a.ld; k += 64) {
     const T w = a.w[k];
     s0 += w * h0[k];
-    sk += w * hk[k];
+    T hk = T(0);
+    for (int r = 1; r <= a.nk; ++r) hk += h0[(long)r * a.ld + k];  // nk > 1: the sum un-collapsed mode defers to the end
+    sk += w * hk;
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {

@@ -24,6 +24,11 @@ def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None):
         u, o = ctm.ctm_biharmonic_rand(mlp, x, t(arrs["V"]))
     elif op == "biharmonic_exact":
         u, o = ctm.ctm_biharmonic_exact(mlp, x)
+    elif op == "laplacian_standard":
+        u, o = ctm.ctm_taylor_standard(mlp, 2, x, t(arrs.get("V")), arrs.get("scale", 1.0))
+    elif op == "biharmonic_rand_standard":
+        V = t(arrs["V"])
+        u, o = ctm.ctm_taylor_standard(mlp, 4, x, V, 1.0 / (3.0 * V.shape[-2]))
     elif op == "weighted_laplacian_rand":
         u, o = ctm.ctm_weighted_laplacian_rand(mlp, x, t(arrs["sigma"]), t(arrs.get("Vk")))
     else:

@@ -153,6 +153,34 @@ def test_biharmonic_shapes(dtype, dims, N, S, per_point):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,R,per_point", [
+    ((5, 16, 16, 1), 8, None, False),       # c1's shape, standard basis
+    ((6, 40, 24, 1), 37, 9, False),         # shared directions
+    ((4, 48, 48, 48, 1), 33, 21, True),     # per-point directions
+    ((3, 100, 1), 20, 5, True),             # one hidden layer
+    ((6, 24, 16, 1), 11, 200, False),       # 1 + 2R rows exceed one tile: two passes
+])
+def test_standard_taylor_mode_equals_collapsed_and_oracle(dtype, dims, N, R, per_point):
+    # Sec. 3.1: propagating then summing (1 + K R rows) and propagating the sum (1 + (K-1) R + 1 rows) agree
+    arrs = small_case(dims, N, dtype, seed=N + len(dims), R=R, per_point=per_point)
+    print(f"case standard taylor dims={dims} N={N} R={R} {dtype.__name__}", flush=True)
+    std2 = gpu_run(arrs, "laplacian_standard")
+    check(std2, oracle_run(arrs, "laplacian"), tol_of(dtype), f"standard K=2 {dims}")
+    col2 = gpu_run(arrs, "laplacian")
+    assert err(std2[1], col2[1]) <= (1e-12 if dtype == np.float64 else 2e-5)
+    if R is not None and R <= 60:
+        std4 = gpu_run(arrs, "biharmonic_rand_standard")
+        check(std4, oracle_run(arrs, "biharmonic_rand"), tol_of(dtype), f"standard K=4 {dims}")
+        col4 = gpu_run(arrs, "biharmonic_rand")
+        assert err(std4[1], col4[1]) <= (1e-12 if dtype == np.float64 else 2e-5)
+
+
+def test_standard_taylor_mode_many_order4_directions():
+    arrs = small_case((5, 24, 16, 1), 6, np.float64, seed=100, R=100, per_point=False, bias=0.05)   # 401 rows: two passes
+    check(gpu_run(arrs, "biharmonic_rand_standard"), oracle_run(arrs, "biharmonic_rand"), TOL64, "standard K=4 S=100")
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("sigma_per_point,v_mode", [(False, "shared"), (False, "per_point"), (True, "shared"), (True, "per_point"),
                                                     (True, None), (False, None)])
 def test_stochastic_and_point_dependent_weighted_laplacian(dtype, sigma_per_point, v_mode):
