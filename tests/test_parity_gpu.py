@@ -315,3 +315,36 @@ def test_errors_from_the_library_with_a_live_handle():
     with pytest.raises(ValueError):
         ctm.ctm_laplacian(mlp, x[:, :4].contiguous())
     mlp.close()
+
+
+def test_operator_call_can_be_captured_in_a_hip_graph_and_replayed():
+    # serving loops replay captured graphs: the calls launch kernels only (no allocation, no sync, no memset node)
+    import torch
+    import paper_2505_13644_amd as ctm
+    w = synth.WORKLOADS["c3"]
+    N = 64
+    arrs = w.build(N)
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    x, V = t(arrs["x"]), t(arrs["V"])
+    u, op = torch.empty(N, device=dev), torch.empty(N, device=dev)
+    ws = torch.empty(ctm.ctm_workspace_bytes(mlp, 2, N, w.R), dtype=torch.uint8, device=dev)
+    ctm.ctm_laplacian(mlp, x, V, arrs["scale"], u, op, ws)          # warm-up outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ctm.ctm_laplacian(mlp, x, V, arrs["scale"], u, op, ws)
+    for rep in range(4):
+        xr = synth.make_points(N, 50, seed=100 + rep)
+        x.copy_(t(xr))
+        u.zero_(); op.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        gu, go = u.cpu().numpy().copy(), op.cpu().numpy().copy()
+        eu, eo = ctm.ctm_laplacian(mlp, x, V, arrs["scale"])          # eager, fresh outputs and workspace
+        torch.cuda.synchronize()
+        assert np.array_equal(gu, eu.cpu().numpy()) and np.array_equal(go, eo.cpu().numpy()), f"replay {rep}"
+        assert np.any(go != 0)
+    del g
+    mlp.close()
