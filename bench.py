@@ -15,7 +15,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 METRIC = "Laplacian evals/sec (50-D 768-768-512-512 tanh MLP, N=4096); % MFMA peak"
-PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}  # MI355X dense MFMA peaks
+PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6, "bf16": 2500.0, "bf16x3": 2500.0}  # MI355X dense MFMA peaks
 
 
 def gemm_flops(dims, N, rho, R, per_point_dirs):
@@ -87,6 +87,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", help="c1..c5 (c2 is the configuration the metric is quoted on)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle baseline; 0 skips it")
+    ap.add_argument("--mfma", choices=["native", "bf16x3", "bf16"], default="native",
+                    help="matrix cores used by the GEMMs of an fp32 workload: native fp32 (default), split bf16 or plain bf16")
     ap.add_argument("--taylor", choices=["collapsed", "standard"], default="collapsed",
                     help="standard = the un-collapsed comparison path (1 + K*R rows per point); c1..c5 only")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -105,7 +107,8 @@ def main():
     arrs = w.build()
     dev = torch.device("cuda:0")
     t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
-    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    mfma = {"native": None, "bf16x3": ctm.CTM_F32_BF16X3, "bf16": ctm.CTM_F32_BF16}[args.mfma]
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]], mfma=mfma)
     x, V, sigma = t(arrs["x"]), t(arrs.get("V")), t(arrs.get("sigma"))
     K = 4 if w.op.startswith("biharmonic") else 2
     R = w.dims[0] if w.directions == "basis" else w.R
@@ -169,6 +172,10 @@ def main():
         flops = gemm_flops(w.dims, w.N, rho, R, w.directions in ("rademacher", "gaussian"))
     layer_ms_per_step = ms["layer"] / args.steps
     dt = "f64" if w.dtype == np.float64 else "f32"
+    if args.mfma != "native":
+        dt = args.mfma
+        # executed matrix-core flops: 3 bf16 MFMAs per product for the split variant
+        flops *= 3 if args.mfma == "bf16x3" else 1
     achieved = flops / (layer_ms_per_step * 1e-3) / 1e12
     roofline = {
         "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",

@@ -20,7 +20,7 @@
  *   - "dev" pointers are device memory of the GPU that is current when the call is
  *     made; "host" pointers are ordinary host memory.  All matrices are dense,
  *     row-major, with no padding; element type is the handle's storage type
- *     (double for CTM_F64, float for CTM_F32).
+ *     (double for CTM_F64, float for CTM_F32 and its bf16-MFMA variants).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *     only enqueue work on it and return; results are valid once the stream has
  *     reached that point.  No call synchronises the device except ctm_destroy_mlp.
@@ -46,8 +46,11 @@ extern "C" {
 typedef struct ctm_mlp ctm_mlp; /* opaque */
 
 typedef enum {
-  CTM_F64 = 0, /* fp64 storage, fp64 MFMA accumulate                       */
-  CTM_F32 = 1  /* fp32 storage, fp32 MFMA accumulate (the benchmarked path) */
+  CTM_F64 = 0,        /* fp64 storage, fp64 MFMA                                            */
+  CTM_F32 = 1,        /* fp32 storage, fp32 MFMA (the benchmarked path)                     */
+  CTM_F32_BF16X3 = 2, /* fp32 storage; GEMMs on the bf16 matrix cores with every operand split
+                         into hi + lo bf16 parts (3 MFMAs per product, fp32 accumulate)      */
+  CTM_F32_BF16 = 3    /* fp32 storage; GEMM inputs rounded to bf16 (1 MFMA, fp32 accumulate) */
 } ctm_dtype;
 
 typedef enum {

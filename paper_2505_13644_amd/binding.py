@@ -13,7 +13,7 @@ from ctypes import POINTER, c_char_p, c_double, c_int, c_long, c_size_t, c_void_
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libctm.so")
 
-CTM_F64, CTM_F32 = 0, 1
+CTM_F64, CTM_F32, CTM_F32_BF16X3, CTM_F32_BF16 = 0, 1, 2, 3
 CTM_ACT_TANH, CTM_ACT_IDENTITY = 0, 1
 CTM_OK = 0
 STATUS_NAMES = {
@@ -168,8 +168,9 @@ class Mlp:
             pass
 
 
-def ctm_create_mlp(Ws, bs=None, act=CTM_ACT_TANH) -> Mlp:
-    """Ws[l]: device tensor [d_out, d_in]; bs[l]: device tensor [d_out] or None."""
+def ctm_create_mlp(Ws, bs=None, act=CTM_ACT_TANH, mfma=None) -> Mlp:
+    """Ws[l]: device tensor [d_out, d_in]; bs[l]: device tensor [d_out] or None.
+    mfma: None (matrix cores of the storage type) or CTM_F32_BF16X3 / CTM_F32_BF16 for fp32 tensors."""
     L = len(Ws)
     dtype = Ws[0].dtype
     dims = [Ws[0].shape[1]] + [W.shape[0] for W in Ws]
@@ -186,7 +187,12 @@ def ctm_create_mlp(Ws, bs=None, act=CTM_ACT_TANH) -> Mlp:
                 raise ValueError(f"b[{l}] has shape {tuple(b.shape)}, expected [{dims[l + 1]}]")
         c_b = (c_void_p * L)(*[_dev_ptr(b, dtype, f"b[{l}]") for l, b in enumerate(bs)])
     out = c_void_p(None)
-    _check(lib().ctm_create_mlp(L, c_dims, c_W, c_b, _dtype_code(dtype), act, _stream_ptr(), ctypes.byref(out)))
+    code = _dtype_code(dtype)
+    if mfma is not None:
+        if code != CTM_F32 or mfma not in (CTM_F32, CTM_F32_BF16X3, CTM_F32_BF16):
+            raise CtmError(-3, "the bf16 matrix-core variants need fp32 tensors")
+        code = mfma
+    _check(lib().ctm_create_mlp(L, c_dims, c_W, c_b, code, act, _stream_ptr(), ctypes.byref(out)))
     return Mlp(out, dims, dtype, act)
 
 

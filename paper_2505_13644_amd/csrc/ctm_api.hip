@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <new>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/ctm.h"
@@ -157,11 +158,14 @@ struct ctm_mlp {
   int device = 0;
   void *arena = nullptr;
   std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: padded vector and scalar bias
+  std::vector<void *> Whi, Wlo;  // bf16 variants: split weights of the hidden layers
 };
 
 namespace {
 
 int tile_cols_of(ctm_dtype t) { return t == CTM_F64 ? tile_cols<double>() : tile_cols<float>(); }
+bool is_bf16(ctm_dtype t) { return t == CTM_F32_BF16X3 || t == CTM_F32_BF16; }
+bool known_dtype(ctm_dtype t) { return t == CTM_F64 || t == CTM_F32 || is_bf16(t); }
 
 struct Layout {
   size_t block_bytes, pair_bytes, dirs_bytes, total;
@@ -232,7 +236,16 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[l]; la.ldout = m->ld[l + 1];
       la.order = K; la.R = Rp; la.last = last ? 1 : 0; la.act = (int)m->act;
       la.standard = standard ? 1 : 0; la.out_rows = last ? last_rows : pl.rho;
-      e = launch_layer<T>(la, pl.MB, st);
+      la.Whi = nullptr; la.Wlo = nullptr;
+      bool done = false;
+      if constexpr (std::is_same<T, float>::value) {
+        if (is_bf16(m->dtype)) {
+          la.Whi = m->Whi[l]; la.Wlo = m->Wlo[l];
+          e = launch_layer_bf16(la, pl.MB, m->dtype == CTM_F32_BF16X3 ? 3 : 1, st);
+          done = true;
+        }
+      }
+      if (!done) e = launch_layer<T>(la, pl.MB, st);
       if (e != hipSuccess) return fail_hip(e, "layer kernel launch");
       (void)prof_mark(st, 1);
       in = out;
@@ -333,7 +346,7 @@ long ctm_rows_per_point(int K, int R) {
 
 int ctm_tile_plan(ctm_dtype dtype, int K, int R, int *points_per_tile, int *row_blocks, int *dirs_per_pass,
                   int *n_passes) {
-  if (dtype != CTM_F64 && dtype != CTM_F32) return fail(CTM_ERR_DTYPE, "ctm_tile_plan: unknown dtype %d", (int)dtype);
+  if (!known_dtype(dtype)) return fail(CTM_ERR_DTYPE, "ctm_tile_plan: unknown dtype %d", (int)dtype);
   if (K != 2 && K != 4) return fail(CTM_ERR_UNSUPPORTED, "ctm_tile_plan: order K = %d, only 2 and 4 are built", K);
   if (R < 1) return fail(CTM_ERR_SHAPE, "ctm_tile_plan: %d directions, need at least 1", R);
   const Split sp = split_dirs(K, R);
@@ -350,7 +363,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   if (!out) return fail(CTM_ERR_NULL, "ctm_create_mlp: out is NULL");
   *out = nullptr;
   if (!dims || !W) return fail(CTM_ERR_NULL, "ctm_create_mlp: dims or W is NULL");
-  if (dtype != CTM_F64 && dtype != CTM_F32) return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown dtype %d", (int)dtype);
+  if (!known_dtype(dtype)) return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown dtype %d", (int)dtype);
   if (act != CTM_ACT_TANH && act != CTM_ACT_IDENTITY)
     return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown activation %d", (int)act);
   if (n_layers < 2 || n_layers > 64)
@@ -373,7 +386,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   m->act = act;
   const int bn = tile_cols_of(dtype);
   size_t total = 0;
-  std::vector<size_t> woff(n_layers), boff(n_layers);
+  std::vector<size_t> woff(n_layers), boff(n_layers), hoff(n_layers, 0), loff(n_layers, 0);
   for (int l = 0; l < n_layers; ++l) {
     m->ld.push_back(pad_ld(dims[l]));
     const bool lastl = (l == n_layers - 1);
@@ -384,6 +397,12 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
     total += round256(rows_pad * m->ld[l] * es);
     boff[l] = total;
     total += round256(rows_pad * es);
+    if (is_bf16(dtype) && !lastl) {
+      hoff[l] = total;
+      total += round256(rows_pad * m->ld[l] * 2);
+      loff[l] = total;
+      total += round256(rows_pad * m->ld[l] * 2);
+    }
   }
   hipError_t e = hipGetDevice(&m->device);
   if (e != hipSuccess) { delete m; return fail_hip(e, "ctm_create_mlp: hipGetDevice"); }
@@ -396,9 +415,13 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   for (int l = 0; l < n_layers; ++l) {
     m->Wp.push_back((char *)m->arena + woff[l]);
     m->bp.push_back((char *)m->arena + boff[l]);
+    m->Whi.push_back((char *)m->arena + hoff[l]);
+    m->Wlo.push_back((char *)m->arena + loff[l]);
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   e = (dtype == CTM_F64) ? pack_all<double>(m, W, b, st) : pack_all<float>(m, W, b, st);
+  for (int l = 0; e == hipSuccess && is_bf16(dtype) && l + 1 < n_layers; ++l)
+    e = launch_pack_bf16((const float *)W[l], dims[l + 1], dims[l], m->Whi[l], m->Wlo[l], m->col_tiles[l] * bn, m->ld[l], st);
   if (e != hipSuccess) {
     (void)hipFree(m->arena);
     delete m;

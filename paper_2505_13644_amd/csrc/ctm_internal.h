@@ -31,6 +31,8 @@ template <typename T> struct LayerArgs {
   const T *Hin;      // [n_points * rho][ldin] coefficient block entering the layer
   const T *W;        // [n_col_tiles * tile_cols][ldin] zero-padded weights
   const T *bias;     // [n_col_tiles * tile_cols] zero-padded bias
+  const void *Whi;   // bf16 kernels only: hi and lo parts of W, [n_col_tiles * 128][ldin] bf16 each
+  const void *Wlo;
   T *Hout;           // [n_points * out_rows][ldout]
   long n_points;
   long n_row_tiles;  // ceil(n_points / P)
@@ -50,6 +52,9 @@ template <typename T> struct LayerArgs {
 // Launch the stacked GEMM + fused jet rule for one layer.  MB in {4, 8, 9, 12, 13, 16}.
 template <typename T> hipError_t launch_layer(const LayerArgs<T> &a, int MB, hipStream_t s);
 bool row_blocks_supported(int MB);
+// fp32 storage, bf16 matrix cores: nsplit = 3 (hi*hi + hi*lo + lo*hi) or 1 (hi*hi only)
+hipError_t launch_layer_bf16(const LayerArgs<float> &a, int MB, int nsplit, hipStream_t s);
+hipError_t launch_pack_bf16(const float *W, int d_out, int d_in, void *hi, void *lo, int rows_pad, int ld, hipStream_t s);
 
 template <typename T> struct SeedArgs {
   const T *x;   // [N][D]

@@ -1,0 +1,284 @@
+// Stacked GEMM of one MLP layer on the bf16 matrix cores, fp32 storage and fp32 accumulation:
+// the reduced-precision variants of layer_kernel (same tile of whole points, same epilogue rule).
+//
+//   NSPLIT = 3  "split bf16": every fp32 operand x is written as hi + lo with hi = bf16(x),
+//               lo = bf16(x - hi); a*b is taken as a_hi*b_hi + a_hi*b_lo + a_lo*b_hi (the lo*lo
+//               term, relative size 2^-16, is dropped) -- three v_mfma_f32_16x16x32_bf16 per block pair.
+//   NSPLIT = 1  plain bf16 inputs: a_hi*b_hi only.
+//
+// The coefficient block stays fp32 in HBM; the A tile is split while it is copied to LDS, the
+// weights are split once at handle creation (Whi / Wlo, [rows_pad][ld] bf16).
+//
+// MFMA use: v_mfma_f32_16x16x32_bf16.  Lane l supplies 8 consecutive k values of A row l%16 and of
+// B column l%16 (k = 8*(l/16) .. +7, the same assignment for both) and receives D rows
+// 4*(l/16) .. +3 of column l%16.  Waves are arranged 2 x 2: each owns ceil(MB/2) row blocks and
+// 4 column blocks, which keeps the LDS traffic per MFMA low enough for the 16-cycle instruction.
+#include "ctm_internal.h"
+#include "ctm_rule.h"
+
+namespace ctm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreadsB = 256;
+constexpr int kXcdsB = 8;
+
+template <int MB, int NSPLIT> struct TileB {
+  static constexpr int MBH = (MB + 1) / 2;        // row blocks per wave
+  static constexpr int AROWS = 2 * MBH * 16;      // LDS rows of the A planes; rows >= 16*MB are never written
+  static constexpr int BM = 16 * MB;
+  static constexpr int BN = 128, BK = 32;
+  static constexpr int PITCH = BK + 8;            // bf16 elements per LDS row: 64 B of k + 16 B pad
+  static constexpr int PLANES = NSPLIT == 3 ? 2 : 1;
+  static constexpr int A_PLANE = AROWS * PITCH;
+  static constexpr int B_PLANE = BN * PITCH;
+  static constexpr int STAGE = PLANES * (A_PLANE + B_PLANE);   // bf16 elements
+  static constexpr int UPR = BK / 8;              // 8-element units per row (= 4)
+  static constexpr int A_LD = (BM * UPR + kThreadsB - 1) / kThreadsB;
+  static constexpr int B_LD = (BN * UPR) / kThreadsB;          // per plane
+  static constexpr int CROW = 64 + 4;
+  static constexpr size_t kStageBytes = 2 * (size_t)STAGE * 2;
+  static constexpr size_t kCBytes = (size_t)BM * CROW * 4;
+  static constexpr size_t kLdsBytes = kStageBytes > kCBytes ? kStageBytes : kCBytes;
+  static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
+};
+
+__device__ __forceinline__ void split8(const f32x4 &x0, const f32x4 &x1, bf16x8 &hi, bf16x8 &lo) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const __bf16 h0 = (__bf16)x0[i], h1 = (__bf16)x1[i];
+    hi[i] = h0;
+    hi[4 + i] = h1;
+    lo[i] = (__bf16)(x0[i] - (float)h0);
+    lo[4 + i] = (__bf16)(x1[i] - (float)h1);
+  }
+}
+
+template <int MB, int NSPLIT>
+__global__ __launch_bounds__(kThreadsB) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void layer_kernel_bf16(const LayerArgs<float> a) {
+  using TL = TileB<MB, NSPLIT>;
+  constexpr int MBH = TL::MBH, BN = TL::BN, BK = TL::BK, PITCH = TL::PITCH, UPR = TL::UPR, CROW = TL::CROW;
+  constexpr bool SPLIT = NSPLIT == 3;
+
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  __bf16 *lds = reinterpret_cast<__bf16 *>(lds_raw);
+  float *Cs = reinterpret_cast<float *>(lds_raw);   // reuses the stages after the k loop
+
+  const long n_tiles = a.n_row_tiles * a.n_col_tiles;
+  const int xcd = blockIdx.x % kXcdsB;
+  const long slot = blockIdx.x / kXcdsB;
+  const long base = n_tiles / kXcdsB, rem = n_tiles % kXcdsB;
+  const long mine = base + (xcd < rem ? 1 : 0);
+  if (slot >= mine) return;
+  const long tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  const long row_tile = tile / a.n_col_tiles;
+  const int col_tile = (int)(tile % a.n_col_tiles);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int wr = wave >> 1, wc = wave & 1;   // wave grid: row half, column half
+
+  const long p0 = row_tile * a.P;
+  const int p_valid = (int)((a.n_points - p0) < a.P ? (a.n_points - p0) : a.P);
+  const int rows_valid = p_valid * a.rho;
+  const float *Ag = a.Hin + p0 * a.rho * (long)a.ldin;
+  const __bf16 *Bhi = reinterpret_cast<const __bf16 *>(a.Whi) + (long)col_tile * BN * a.ldin;
+  const __bf16 *Blo = reinterpret_cast<const __bf16 *>(a.Wlo) + (long)col_tile * BN * a.ldin;
+
+  // global -> LDS copy slots: 8 consecutive k values each (32 B of fp32 for A, 16 B of bf16 per weight plane);
+  // unconditional, clamped as in layer_kernel
+  int a_off[TL::A_LD];
+  const float *a_src[TL::A_LD];
+#pragma unroll
+  for (int i = 0; i < TL::A_LD; ++i) {
+    int u = tid + i * kThreadsB;
+    u = u < TL::BM * UPR ? u : TL::BM * UPR - 1;
+    const int row = u / UPR, q = u % UPR;
+    a_off[i] = row * PITCH + q * 8;
+    const int grow = row < rows_valid ? row : rows_valid - 1;
+    a_src[i] = Ag + (long)grow * a.ldin + q * 8;
+  }
+  int b_off[TL::B_LD];
+  long b_src[TL::B_LD];
+#pragma unroll
+  for (int i = 0; i < TL::B_LD; ++i) {
+    const int u = tid + i * kThreadsB;
+    const int row = u / UPR, q = u % UPR;
+    b_off[i] = row * PITCH + q * 8;
+    b_src[i] = (long)row * a.ldin + q * 8;
+  }
+
+  f32x4 ga[TL::A_LD][2];
+  bf16x8 gbh[TL::B_LD], gbl[TL::B_LD];
+  auto load_global = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < TL::A_LD; ++i) {
+      ga[i][0] = *reinterpret_cast<const f32x4 *>(a_src[i] + k0);
+      ga[i][1] = *reinterpret_cast<const f32x4 *>(a_src[i] + k0 + 4);
+    }
+#pragma unroll
+    for (int i = 0; i < TL::B_LD; ++i) {
+      gbh[i] = *reinterpret_cast<const bf16x8 *>(Bhi + b_src[i] + k0);
+      if (SPLIT) gbl[i] = *reinterpret_cast<const bf16x8 *>(Blo + b_src[i] + k0);
+    }
+  };
+  // stage layout: [A hi][A lo][B hi][B lo] (lo planes only when SPLIT)
+  auto store_lds = [&](int stage) {
+    __bf16 *S = lds + stage * TL::STAGE;
+    __bf16 *Ah = S, *Al = S + TL::A_PLANE;
+    __bf16 *Bh = S + TL::PLANES * TL::A_PLANE, *Bl = Bh + TL::B_PLANE;
+#pragma unroll
+    for (int i = 0; i < TL::A_LD; ++i) {
+      bf16x8 hi, lo;
+      split8(ga[i][0], ga[i][1], hi, lo);
+      *reinterpret_cast<bf16x8 *>(Ah + a_off[i]) = hi;
+      if (SPLIT) *reinterpret_cast<bf16x8 *>(Al + a_off[i]) = lo;
+    }
+#pragma unroll
+    for (int i = 0; i < TL::B_LD; ++i) {
+      *reinterpret_cast<bf16x8 *>(Bh + b_off[i]) = gbh[i];
+      if (SPLIT) *reinterpret_cast<bf16x8 *>(Bl + b_off[i]) = gbl[i];
+    }
+  };
+
+  f32x4 acc[MBH][4];
+#pragma unroll
+  for (int m = 0; m < MBH; ++m)
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) acc[m][nb] = f32x4{0, 0, 0, 0};
+
+  const int nk = a.ldin / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int stage = kt & 1;
+    const int k_next = (kt + 1 < nk) ? (kt + 1) * BK : kt * BK;   // last stage re-fetches itself (unused)
+    load_global(k_next);
+
+    const __bf16 *S = lds + stage * TL::STAGE;
+    const __bf16 *Ah = S + (wr * MBH * 16 + lr) * PITCH + lg * 8;
+    const __bf16 *Al = Ah + TL::A_PLANE;
+    const __bf16 *Bh = S + TL::PLANES * TL::A_PLANE + (wc * 64 + lr) * PITCH + lg * 8;
+    const __bf16 *Bl = Bh + TL::B_PLANE;
+    bf16x8 bh[4], bl[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+      bh[nb] = *reinterpret_cast<const bf16x8 *>(Bh + nb * 16 * PITCH);
+      if (SPLIT) bl[nb] = *reinterpret_cast<const bf16x8 *>(Bl + nb * 16 * PITCH);
+    }
+    bf16x8 ah[2], al[2];
+    ah[0] = *reinterpret_cast<const bf16x8 *>(Ah);
+    if (SPLIT) al[0] = *reinterpret_cast<const bf16x8 *>(Al);
+#pragma unroll
+    for (int m = 0; m < MBH; ++m) {
+      if (m + 1 < MBH) {  // next row block's fragments, fetched ahead of this block's MFMAs
+        ah[(m + 1) & 1] = *reinterpret_cast<const bf16x8 *>(Ah + (m + 1) * 16 * PITCH);
+        if (SPLIT) al[(m + 1) & 1] = *reinterpret_cast<const bf16x8 *>(Al + (m + 1) * 16 * PITCH);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int nb = 0; nb < 4; ++nb) {
+        acc[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[m & 1], bh[nb], acc[m][nb], 0, 0, 0);
+        if (SPLIT) {
+          acc[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[m & 1], bl[nb], acc[m][nb], 0, 0, 0);
+          acc[m][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[m & 1], bh[nb], acc[m][nb], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+
+    store_lds(stage ^ 1);   // every wave finished reading that stage before the previous barrier
+    __syncthreads();
+  }
+
+  // ---- epilogue: 64 output columns at a time.  Chunk c holds the columns of the waves with wc == c.
+  const int rho = a.rho;
+  const int j = tid & 63;
+#pragma unroll
+  for (int chunk = 0; chunk < 2; ++chunk) {
+    if (chunk > 0) __syncthreads();
+    if (wc == chunk) {
+#pragma unroll
+      for (int m = 0; m < MBH; ++m) {
+        const int mb = wr * MBH + m;
+        if (mb < MB) {
+#pragma unroll
+          for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Cs[(mb * 16 + lg * 4 + v) * CROW + nb * 16 + lr] = acc[m][nb][v];
+        }
+      }
+    }
+    __syncthreads();
+    const long jg = (long)col_tile * BN + chunk * 64 + j;
+    if (jg >= a.ldout) continue;
+    const float bias = a.bias[jg];
+    for (int p = wave; p < p_valid; p += kThreadsB / 64) {
+      const float *c = Cs + (long)p * rho * CROW + j;
+      const long n = p0 + p;
+      float *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
+      jet_rule<float>(c, CROW, bias, o, a.ldout, a);
+    }
+  }
+}
+
+template <int MB, int NSPLIT> static hipError_t launch_one_b(const LayerArgs<float> &a, hipStream_t s) {
+  using TL = TileB<MB, NSPLIT>;
+  static bool attr_set = false;  // benign race: every thread sets the same value
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&layer_kernel_bf16<MB, NSPLIT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)TL::kLdsBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const long n_tiles = a.n_row_tiles * a.n_col_tiles;
+  const long grid = (n_tiles + kXcdsB - 1) / kXcdsB * kXcdsB;
+  if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((layer_kernel_bf16<MB, NSPLIT>), dim3((unsigned)grid), dim3(kThreadsB), TL::kLdsBytes, s, a);
+  return hipGetLastError();
+}
+
+template <int NSPLIT> static hipError_t dispatch_b(const LayerArgs<float> &a, int MB, hipStream_t s) {
+  switch (MB) {
+    case 4: return launch_one_b<4, NSPLIT>(a, s);
+    case 8: return launch_one_b<8, NSPLIT>(a, s);
+    case 9: return launch_one_b<9, NSPLIT>(a, s);
+    case 12: return launch_one_b<12, NSPLIT>(a, s);
+    case 13: return launch_one_b<13, NSPLIT>(a, s);
+    case 16: return launch_one_b<16, NSPLIT>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_layer_bf16(const LayerArgs<float> &a, int MB, int nsplit, hipStream_t s) {
+  return nsplit == 3 ? dispatch_b<3>(a, MB, s) : dispatch_b<1>(a, MB, s);
+}
+
+// ---- weights for the bf16 kernels: hi = bf16(w), lo = bf16(w - hi), zero-padded [rows_pad][ld]
+__global__ void pack_bf16_kernel(const float *W, int d_out, int d_in, __bf16 *hi, __bf16 *lo, int rows_pad, int ld) {
+  const long total = (long)rows_pad * ld;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(i % ld);
+    const int jrow = (int)(i / ld);
+    const float w = (jrow < d_out && k < d_in) ? W[(long)jrow * d_in + k] : 0.f;
+    const __bf16 h = (__bf16)w;
+    hi[i] = h;
+    lo[i] = (__bf16)(w - (float)h);
+  }
+}
+
+hipError_t launch_pack_bf16(const float *W, int d_out, int d_in, void *hi, void *lo, int rows_pad, int ld, hipStream_t s) {
+  const long total = (long)rows_pad * ld;
+  long blocks = (total + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, s, W, d_out, d_in,
+                     reinterpret_cast<__bf16 *>(hi), reinterpret_cast<__bf16 *>(lo), rows_pad, ld);
+  return hipGetLastError();
+}
+
+}  // namespace ctm

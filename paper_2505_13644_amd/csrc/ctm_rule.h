@@ -1,0 +1,116 @@
+// The collapsed (or, for comparison, un-collapsed) Taylor-mode rule of the activation for one
+// (point, feature) pair: shared by the fp32/fp64 and the bf16-MFMA stacked-GEMM kernels.
+//
+//   order 2:  t = tanh z_0 ; d1 = 1 - t^2 ; d2 = -2 t d1                     (App. H)
+//             h_0 = t ;  h_{1,r} = d1 z_{1,r} ;  h_2 = d1 z_2 + d2 * sum_r z_{1,r}^2      (Sec. 3.1, Eq. 6)
+//   order 4:  d3 = d1 (6 t^2 - 2) ; d4 = 8 t d1 (2 - 3 t^2)
+//             h_{1,r} = d1 z1 ; h_{2,r} = d2 z1^2 + d1 z2 ; h_{3,r} = d3 z1^3 + 3 d2 z1 z2 + d1 z3
+//             h_4 = d1 z_4 + sum_r [ d4 z1^4 + 6 d3 z1^2 z2 + 4 d2 z1 z3 + 3 d2 z2^2 ]     (App. A multiplicities)
+#pragma once
+
+#include "ctm_internal.h"
+
+namespace ctm {
+
+__device__ __forceinline__ float act_tanh(float z) { return tanhf(z); }
+__device__ __forceinline__ double act_tanh(double z) { return tanh(z); }
+
+// c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows);
+// o: the pair's column in the output block (row pitch ostep elements).
+template <typename T>
+__device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, long ostep, const LayerArgs<T> &a) {
+  const int R = a.R;
+  const T z0 = c[0] + bias;
+  T t, d1, d2;
+  if (a.act == 0) {
+    t = act_tanh(z0);
+    d1 = T(1) - t * t;
+    d2 = T(-2) * t * d1;
+  } else {
+    t = z0;
+    d1 = T(1);
+    d2 = T(0);
+  }
+  o[0] = t;
+  if (a.standard) {
+    // un-collapsed ("standard") Taylor mode, kept for comparison: every direction carries its own
+    // highest-order row (1 + K*R rows per point) and the sum over directions is taken after the last layer
+    if (a.order == 2) {  // rows 1..R first order, R+1..2R second order
+      for (int r = 0; r < R; ++r) {
+        const T z1 = c[(long)(1 + r) * CROW], z2 = c[(long)(1 + R + r) * CROW];
+        const T h2 = d1 * z2 + d2 * z1 * z1;
+        if (a.last) {
+          o[(1 + r) * ostep] = h2;
+        } else {
+          o[(1 + r) * ostep] = d1 * z1;
+          o[(1 + R + r) * ostep] = h2;
+        }
+      }
+    } else {  // rows 1+4r .. 4+4r: orders 1..4 of direction r
+      const T d3 = a.act == 0 ? d1 * (T(6) * t * t - T(2)) : T(0);
+      const T d4 = a.act == 0 ? T(8) * t * d1 * (T(2) - T(3) * t * t) : T(0);
+      for (int r = 0; r < R; ++r) {
+        const T *cr = c + (long)(1 + 4 * r) * CROW;
+        const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW], z4 = cr[3 * CROW];
+        const T z1s = z1 * z1;
+        const T h4 = d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2 + d1 * z4;
+        if (a.last) {
+          o[(1 + r) * ostep] = h4;
+        } else {
+          T *orow = o + (long)(1 + 4 * r) * ostep;
+          orow[0] = d1 * z1;
+          orow[ostep] = d2 * z1s + d1 * z2;
+          orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+          orow[3 * ostep] = h4;
+        }
+      }
+    }
+  } else if (a.order == 2) {
+    T s = T(0);
+    int r = 1;
+    for (; r + 3 <= R; r += 4) {  // four independent LDS reads in flight per trip
+      T z1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z1[i] = c[(long)(r + i) * CROW];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        s += z1[i] * z1[i];
+        if (!a.last) o[(r + i) * ostep] = d1 * z1[i];
+      }
+    }
+    for (; r <= R; ++r) {
+      const T z1 = c[(long)r * CROW];
+      s += z1 * z1;
+      if (!a.last) o[r * ostep] = d1 * z1;
+    }
+    const T z2 = c[(long)(R + 1) * CROW];
+    const T h2 = d1 * z2 + d2 * s;
+    o[(a.last ? 1 : R + 1) * ostep] = h2;
+  } else {
+    T d3, d4;
+    if (a.act == 0) {
+      d3 = d1 * (T(6) * t * t - T(2));
+      d4 = T(8) * t * d1 * (T(2) - T(3) * t * t);
+    } else {
+      d3 = T(0);
+      d4 = T(0);
+    }
+    T s = T(0);
+    for (int r = 0; r < R; ++r) {
+      const T *cr = c + (long)(1 + 3 * r) * CROW;
+      const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW];
+      const T z1s = z1 * z1;
+      s += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
+      if (!a.last) {
+        T *orow = o + (long)(1 + 3 * r) * ostep;
+        orow[0] = d1 * z1;
+        orow[ostep] = d2 * z1s + d1 * z2;
+        orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+      }
+    }
+    const T z4 = c[(long)(3 * R + 1) * CROW];
+    o[(a.last ? 1 : 3 * R + 1) * ostep] = d1 * z4 + s;
+  }
+}
+
+}  // namespace ctm

@@ -3,7 +3,7 @@ through the C-ABI binding, and through the CPU oracle."""
 import numpy as np
 
 
-def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None):
+def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None, mfma=None):
     """arrs: dict from synth.Workload.build() (numpy).  Returns (u, op) as fp64 numpy arrays."""
     import torch
 
@@ -14,7 +14,7 @@ def gpu_run(arrs, op, act=None, return_mlp=False, mlp=None):
     own = mlp is None
     if own:
         mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]],
-                                 ctm.CTM_ACT_TANH if act is None else act)
+                                 ctm.CTM_ACT_TANH if act is None else act, mfma)
     x = t(arrs["x"])
     if op == "laplacian":
         u, o = ctm.ctm_laplacian(mlp, x, t(arrs.get("V")), arrs.get("scale", 1.0))

@@ -90,6 +90,52 @@ def test_named_workloads_full_size_sampled(name, n_sample):
 
 
 # ---------------------------------------------------------------------------
+# bf16 matrix-core variants of the fp32 path (bar for these: 2e-2)
+# ---------------------------------------------------------------------------
+def mfma_modes():
+    import paper_2505_13644_amd as ctm
+    # split bf16 (3 MFMAs per product) keeps about 16 bits per operand: held to the fp32 bar as well
+    return {"bf16x3": (ctm.CTM_F32_BF16X3, 2e-4), "bf16": (ctm.CTM_F32_BF16, 2e-2)}
+
+
+@pytest.mark.parametrize("mode", ["bf16x3", "bf16"])
+@pytest.mark.parametrize("name,N", [("c2", 37), ("c3", 45), ("c4", 50), ("c5", 23)])
+def test_bf16_mfma_variants_reduced_batch(mode, name, N):
+    code, tol = mfma_modes()[mode]
+    w = synth.WORKLOADS[name]
+    arrs = w.build(N)
+    print(f"case {name} N={N} {mode}", flush=True)
+    check(gpu_run(arrs, w.op, mfma=code), oracle_run(arrs, w.op), tol, f"{name} N={N} {mode}")
+
+
+@pytest.mark.parametrize("mode", ["bf16x3", "bf16"])
+@pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c5", 48)])
+def test_bf16_mfma_variants_full_size_sampled(mode, name, n_sample):
+    code, tol = mfma_modes()[mode]
+    w = synth.WORKLOADS[name]
+    arrs = w.build()
+    print(f"case {name} full N={w.N} {mode}", flush=True)
+    gu, go, mlp = gpu_run(arrs, w.op, return_mlp=True, mfma=code)
+    idx = np.sort(np.random.default_rng(7).choice(w.N, n_sample, replace=False))
+    check((gu[idx], go[idx]), oracle_run(arrs, w.op, idx=idx), tol, f"{name} full-size sample {mode}")
+    gu2, go2 = gpu_run(arrs, w.op, mlp=mlp)
+    assert np.array_equal(gu, gu2) and np.array_equal(go, go2)
+    mlp.close()
+
+
+@pytest.mark.parametrize("mode", ["bf16x3", "bf16"])
+@pytest.mark.parametrize("dims,N,R,per_point", [((7, 33, 65, 1), 19, None, False), ((3, 100, 1), 130, None, False),
+                                                ((4, 48, 48, 48, 1), 33, 21, True), ((6, 24, 16, 1), 21, 300, False)])
+def test_bf16_mfma_variants_shapes(mode, dims, N, R, per_point):
+    code, tol = mfma_modes()[mode]
+    arrs = small_case(dims, N, np.float32, seed=N, R=R, per_point=per_point)
+    print(f"case bf16 shapes dims={dims} N={N} R={R} {mode}", flush=True)
+    check(gpu_run(arrs, "laplacian", mfma=code), oracle_run(arrs, "laplacian"), tol, f"laplacian {dims} {mode}")
+    if R is not None and R <= 60:
+        check(gpu_run(arrs, "biharmonic_rand", mfma=code), oracle_run(arrs, "biharmonic_rand"), tol, f"biharmonic {dims} {mode}")
+
+
+# ---------------------------------------------------------------------------
 # shapes that stress tiling: odd widths, one hidden layer, N = 1, R = 1, many directions
 # ---------------------------------------------------------------------------
 def small_case(dims, N, dtype, seed, R=None, kind="gaussian", per_point=True, bias=0.1):
