@@ -38,7 +38,11 @@ template <int MB, int NSPLIT> struct TileB {
   static constexpr int A_LD = (BM * UPR + kThreadsB - 1) / kThreadsB;
   static constexpr int B_LD = (BN * UPR) / kThreadsB;          // per plane
   static constexpr int CROW = 64 + 4;
-  static constexpr size_t kStageBytes = 2 * (size_t)STAGE * 2;
+  // The split variant keeps ONE stage in LDS (two barriers per k step) so that two workgroups fit a
+  // CU and cover each other's barriers, conversions and load latency; the plain variant's stage is
+  // half as large and is double-buffered.
+  static constexpr int NSTAGE = NSPLIT == 3 ? 1 : 2;
+  static constexpr size_t kStageBytes = NSTAGE * (size_t)STAGE * 2;
   static constexpr size_t kCBytes = (size_t)BM * CROW * 4;
   static constexpr size_t kLdsBytes = kStageBytes > kCBytes ? kStageBytes : kCBytes;
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
@@ -156,7 +160,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
-    const int stage = kt & 1;
+    const int stage = TL::NSTAGE == 2 ? (kt & 1) : 0;
     const int k_next = (kt + 1 < nk) ? (kt + 1) * BK : kt * BK;   // last stage re-fetches itself (unused)
     load_global(k_next);
 
@@ -192,7 +196,12 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    store_lds(stage ^ 1);   // every wave finished reading that stage before the previous barrier
+    if (TL::NSTAGE == 2) {
+      store_lds(stage ^ 1);   // every wave finished reading that stage before the previous barrier
+    } else {
+      __syncthreads();        // every wave finished reading the only stage
+      store_lds(0);
+    }
     __syncthreads();
   }
 
