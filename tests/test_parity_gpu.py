@@ -394,3 +394,41 @@ def test_operator_call_can_be_captured_in_a_hip_graph_and_replayed():
         assert np.any(go != 0)
     del g
     mlp.close()
+
+
+@pytest.mark.parametrize("op_name,N", [("laplacian", 37), ("biharmonic_rand", 23), ("biharmonic_exact", 9)])
+def test_calls_stay_inside_their_buffers(op_name, N):
+    # guard words before and after u, op and the workspace must survive a call untouched
+    import torch
+    import paper_2505_13644_amd as ctm
+    dims = (6, 40, 24, 1)
+    arrs = small_case(dims, N, np.float32, seed=N, R=5, per_point=True)
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    x, V = t(arrs["x"]), t(arrs["V"])
+    G = 64                                           # guard elements
+    ubuf = torch.full((N + 2 * G,), 7.25, device=dev)
+    obuf = torch.full((N + 2 * G,), -3.5, device=dev)
+    if op_name == "laplacian":
+        need = ctm.ctm_workspace_bytes(mlp, 2, N, 5)
+    elif op_name == "biharmonic_rand":
+        need = ctm.ctm_workspace_bytes(mlp, 4, N, 5)
+    else:
+        need = ctm.binding.lib().ctm_biharmonic_exact_workspace_bytes(mlp.handle, N)
+    wbuf = torch.full((need + 512,), 0x5A, dtype=torch.uint8, device=dev)
+    off = (-wbuf.data_ptr()) % 256 + 256             # 256-byte aligned start with at least 256 guard bytes in front
+    ws = wbuf[off:off + need]
+    u, op = ubuf[G:G + N], obuf[G:G + N]
+    if op_name == "laplacian":
+        ctm.ctm_laplacian(mlp, x, V, 0.2, u, op, ws)
+    elif op_name == "biharmonic_rand":
+        ctm.ctm_biharmonic_rand(mlp, x, V, u, op, ws)
+    else:
+        ctm.ctm_biharmonic_exact(mlp, x, u, op, ws)
+    torch.cuda.synchronize()
+    assert torch.all(ubuf[:G] == 7.25) and torch.all(ubuf[G + N:] == 7.25)
+    assert torch.all(obuf[:G] == -3.5) and torch.all(obuf[G + N:] == -3.5)
+    assert torch.all(wbuf[:off] == 0x5A) and torch.all(wbuf[off + need:] == 0x5A)
+    assert torch.all(torch.isfinite(u)) and torch.all(torch.isfinite(op)) and not torch.any(u == 7.25)
+    mlp.close()
