@@ -185,6 +185,15 @@ def main():
         "avg_launch_ms": ms["layer"] / max(1, launches["layer"]),
         "stage_ms_per_step": {{"seed": "first_layer_or_seed"}.get(k, k): v / args.steps for k, v in ms.items()},
     }
+    # the elementwise first layer (shared directions) is bound by writing the [N*rho, d_1] block once
+    es = 8 if w.dtype == np.float64 else 4
+    shared_first = w.directions in ("basis", "sigma") and w.dims[0] <= 64 and w.op != "biharmonic_exact"
+    if shared_first:
+        first_bytes = (w.N * rho * w.dims[1] + w.N * w.dims[0]) * es
+        first_ms = ms["seed"] / args.steps
+        roofline["first_layer"] = {"bound": "hbm", "achieved": first_bytes / (first_ms * 1e-3) / 1e9, "peak": 8000.0,
+                                   "unit": "GB/s", "frac": first_bytes / (first_ms * 1e-3) / 1e9 / 8000.0,
+                                   "bytes_per_step": first_bytes, "ms_per_step": first_ms}
     out = {
         "metric": METRIC, "value": w.N / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
