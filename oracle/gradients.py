@@ -1,0 +1,51 @@
+"""fp64 CPU oracle for parameter gradients of Laplacian-type losses.  TEST INFRASTRUCTURE ONLY.
+
+For  L = sum_n [ gu_n * u(x_n) + gop_n * op(x_n) ],  op(x_n) = scale * sum_r v_r^T H(x_n) v_r  (Sec. 3.2, Eq. 7-8),
+it returns dL/dW_l and dL/db_l.  The operator is written from its definition with nested first-order
+automatic differentiation (PyTorch CPU, fp64): the Hessian of the scalar network by forward-over-reverse,
+contracted with the directions, then one reverse sweep to the parameters.  No Taylor-mode rule and no code of
+the HIP path is involved.  The paper calls evaluating the operator so that it can be differentiated again the
+"differentiable" setting of its benchmark (Sec. 4).
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+
+def _mlp(params, x, act):
+    Ws, bs = params
+    h = x
+    for l, (W, b) in enumerate(zip(Ws, bs)):
+        h = h @ W.T + b
+        if l < len(Ws) - 1:
+            h = torch.tanh(h) if act == "tanh" else h
+    return h[..., 0]
+
+
+def laplacian_loss_grads(Ws, bs, x, V, scale, gu, gop, act="tanh"):
+    """Returns (L, [dL/dW_l], [dL/db_l]) as fp64 numpy.  V: None (standard basis), [R, D] or [N, R, D]."""
+    t = lambda a: torch.as_tensor(np.asarray(a, dtype=np.float64))
+    Ws_t = [t(W).requires_grad_(True) for W in Ws]
+    bs_t = [t(b).requires_grad_(True) for b in bs]
+    xt, gut, gopt = t(x), t(gu), t(gop)
+    N, D = xt.shape
+    if V is None:
+        Vt = torch.eye(D, dtype=torch.float64).expand(N, D, D)
+    else:
+        Vt = t(V)
+        if Vt.dim() == 2:
+            Vt = Vt.expand(N, *Vt.shape)
+
+    def loss(params):
+        f = lambda p: _mlp(params, p, act)                       # scalar function of one point
+        H = torch.func.vmap(torch.func.hessian(f))(xt)            # [N, D, D]
+        u = _mlp(params, xt, act)
+        op = scale * torch.einsum("nrd,nde,nre->n", Vt, H, Vt)
+        return (gut * u + gopt * op).sum()
+
+    L = loss((Ws_t, bs_t))
+    grads = torch.autograd.grad(L, Ws_t + bs_t, allow_unused=True)
+    gW = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[:len(Ws_t)], Ws_t)]
+    gb = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[len(Ws_t):], bs_t)]
+    return float(L.detach()), gW, gb
