@@ -150,6 +150,35 @@ int ctm_biharmonic_rand(const ctm_mlp *mlp, const void *x, long N, const void *V
                         size_t workspace_bytes, void *stream);
 
 /*
+ * Gradients with respect to the weights ("differentiable" evaluation, Sec. 4) for second-order operators.
+ *
+ * ctm_laplacian_fwd computes the same (u, op) as ctm_laplacian (collapsed order-2 Taylor mode) and records, in
+ * the caller's `tape`, what the reverse pass needs: the input coefficient block and, per hidden layer, the
+ * pre-activation rows and the output rows.  One pass only: R <= 254.  CTM_F32 and CTM_F64 handles.
+ *   tape    dev, ctm_tape_bytes(mlp, N, R) bytes (0 on invalid arguments), 256-byte aligned
+ *
+ * ctm_laplacian_bwd takes dL/du and dL/dop of a scalar L and the tape of the matching forward call (same mlp
+ * weights, N, R, scale) and writes dL/dW_l and dL/db_l:
+ *   gu, gop   dev [N], either may be NULL (= zeros)
+ *   gW, gb    host arrays of n_layers dev pointers, gW[l] is [dims[l+1], dims[l]] row-major, gb[l] is [dims[l+1]];
+ *             the arrays or single entries may be NULL (gradient not wanted).  Outputs are overwritten, not
+ *             accumulated; all sums over points use fixed partitions and orders (bitwise reproducible).
+ *   workspace dev, ctm_backward_workspace_bytes(mlp, N, R) bytes, 256-byte aligned
+ * Per hidden layer it runs: the cotangent GEMM Zbar W fused with the reverse of the activation rule (the same
+ * stacked-GEMM kernel), the weight gradient Zbar^T H over all N * rho rows, and the bias gradient.
+ *
+ * ctm_update_mlp re-packs new weights (same shapes) into an existing handle, e.g. after an optimizer step.
+ */
+size_t ctm_tape_bytes(const ctm_mlp *mlp, long N, int R);
+size_t ctm_backward_workspace_bytes(const ctm_mlp *mlp, long N, int R);
+int ctm_laplacian_fwd(const ctm_mlp *mlp, const void *x, long N, const void *V, int R, long v_point_stride,
+                      double scale, void *u, void *op, void *tape, size_t tape_bytes, void *stream);
+int ctm_laplacian_bwd(const ctm_mlp *mlp, long N, int R, double scale, const void *tape, size_t tape_bytes,
+                      const void *gu, const void *gop, void *const *gW, void *const *gb, void *workspace,
+                      size_t workspace_bytes, void *stream);
+int ctm_update_mlp(ctm_mlp *mlp, const void *const *W, const void *const *b, void *stream);
+
+/*
  * The same sums computed by STANDARD (un-collapsed) Taylor mode, for comparison only: every direction
  * carries its own order-K coefficient through the network (1 + K*R rows per point, Sec. 3.1) and the sum
  * over directions is taken after the last layer.  K = 2 or 4; other arguments as in ctm_laplacian

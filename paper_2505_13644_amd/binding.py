@@ -37,6 +37,13 @@ SIGNATURES = {
     "ctm_weighted_laplacian_rand_workspace_bytes": (c_size_t, [c_void_p, c_long, c_int, c_int, c_long, c_long]),
     "ctm_weighted_laplacian_rand": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_int, c_long,
                                             c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "ctm_tape_bytes": (c_size_t, [c_void_p, c_long, c_int]),
+    "ctm_backward_workspace_bytes": (c_size_t, [c_void_p, c_long, c_int]),
+    "ctm_laplacian_fwd": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p, c_void_p,
+                                  c_size_t, c_void_p]),
+    "ctm_laplacian_bwd": (c_int, [c_void_p, c_long, c_int, c_double, c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_void_p),
+                                  POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
+    "ctm_update_mlp": (c_int, [c_void_p, POINTER(c_void_p), POINTER(c_void_p), c_void_p]),
     "ctm_workspace_bytes_standard": (c_size_t, [c_void_p, c_int, c_long, c_int]),
     "ctm_taylor_standard": (c_int, [c_void_p, c_int, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]),
@@ -358,3 +365,85 @@ def ctm_taylor_standard(mlp: Mlp, K, x, V=None, scale=1.0, u=None, op=None, work
                                      c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                      _stream_ptr()))
     return u, op
+
+
+def _dirs_of(x, V):
+    N, D = x.shape
+    if V is None:
+        return D, 0
+    if V.dim() == 2:
+        return V.shape[0], 0
+    return V.shape[1], V.shape[1] * V.shape[2]
+
+
+def ctm_tape_bytes(mlp: Mlp, N: int, R: int) -> int:
+    n = lib().ctm_tape_bytes(mlp.handle, N, R)
+    if n == 0:
+        raise CtmError(-4, ctm_last_error())
+    return n
+
+
+def ctm_backward_workspace_bytes(mlp: Mlp, N: int, R: int) -> int:
+    n = lib().ctm_backward_workspace_bytes(mlp.handle, N, R)
+    if n == 0:
+        raise CtmError(-4, ctm_last_error())
+    return n
+
+
+def ctm_laplacian_fwd(mlp: Mlp, x, V=None, scale=1.0, u=None, op=None, tape=None):
+    """Forward that records a tape for ctm_laplacian_bwd.  Returns (u, op, tape)."""
+    torch = _torch()
+    _check_shapes(mlp, x, V)
+    N = x.shape[0]
+    R, stride = _dirs_of(x, V)
+    if u is None:
+        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if op is None:
+        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    if tape is None:
+        tape = torch.empty(ctm_tape_bytes(mlp, N, R), dtype=torch.uint8, device=x.device)
+    _check(lib().ctm_laplacian_fwd(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(V, mlp.dtype, "V"), R, stride, float(scale),
+                                   _dev_ptr(u, mlp.dtype, "u"), _dev_ptr(op, mlp.dtype, "op"), c_void_p(tape.data_ptr()),
+                                   tape.numel(), _stream_ptr()))
+    return u, op, tape
+
+
+def ctm_laplacian_bwd(mlp: Mlp, N, R, scale, tape, gu, gop, gW=None, gb=None, workspace=None):
+    """dL/dW_l, dL/db_l from dL/du (gu) and dL/dop (gop).  gW / gb: lists of preallocated tensors or None entries;
+    omitted lists are allocated.  Returns (gW, gb)."""
+    torch = _torch()
+    L = len(mlp.dims) - 1
+    dev = tape.device
+    if gW is None:
+        gW = [torch.empty(mlp.dims[l + 1], mlp.dims[l], dtype=mlp.dtype, device=dev) for l in range(L)]
+    if gb is None:
+        gb = [torch.empty(mlp.dims[l + 1], dtype=mlp.dtype, device=dev) for l in range(L)]
+    for l in range(L):
+        if gW[l] is not None and tuple(gW[l].shape) != (mlp.dims[l + 1], mlp.dims[l]):
+            raise ValueError(f"gW[{l}] has shape {tuple(gW[l].shape)}")
+        if gb[l] is not None and tuple(gb[l].shape) != (mlp.dims[l + 1],):
+            raise ValueError(f"gb[{l}] has shape {tuple(gb[l].shape)}")
+    for name, t in (("gu", gu), ("gop", gop)):
+        if t is not None and tuple(t.shape) != (N,):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected [{N}]")
+    if workspace is None:
+        workspace = torch.empty(ctm_backward_workspace_bytes(mlp, N, R), dtype=torch.uint8, device=dev)
+    c_gW = (c_void_p * L)(*[_dev_ptr(g, mlp.dtype, f"gW[{l}]") for l, g in enumerate(gW)])
+    c_gb = (c_void_p * L)(*[_dev_ptr(g, mlp.dtype, f"gb[{l}]") for l, g in enumerate(gb)])
+    _check(lib().ctm_laplacian_bwd(mlp.handle, N, R, float(scale), c_void_p(tape.data_ptr()), tape.numel(),
+                                   _dev_ptr(gu, mlp.dtype, "gu"), _dev_ptr(gop, mlp.dtype, "gop"), c_gW, c_gb,
+                                   c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr()))
+    return gW, gb
+
+
+def ctm_update_mlp(mlp: Mlp, Ws, bs=None):
+    """Re-pack new weights of the same shapes into the handle."""
+    L = len(Ws)
+    if L != len(mlp.dims) - 1:
+        raise ValueError("wrong number of layers")
+    for l, W in enumerate(Ws):
+        if tuple(W.shape) != (mlp.dims[l + 1], mlp.dims[l]):
+            raise ValueError(f"W[{l}] has shape {tuple(W.shape)}")
+    c_W = (c_void_p * L)(*[_dev_ptr(W, mlp.dtype, f"W[{l}]") for l, W in enumerate(Ws)])
+    c_b = None if bs is None else (c_void_p * L)(*[_dev_ptr(b, mlp.dtype, f"b[{l}]") for l, b in enumerate(bs)])
+    _check(lib().ctm_update_mlp(mlp.handle, c_W, c_b, _stream_ptr()))

@@ -159,6 +159,7 @@ struct ctm_mlp {
   void *arena = nullptr;
   std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: padded vector and scalar bias
   std::vector<void *> Whi, Wlo;  // bf16 variants: split weights of the hidden layers
+  std::vector<void *> WT;        // l = 1..L-2: W_l transposed, [pad(dims[l])][ld(dims[l+1])], for the reverse pass
 };
 
 namespace {
@@ -236,7 +237,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[l]; la.ldout = m->ld[l + 1];
       la.order = K; la.R = Rp; la.last = last ? 1 : 0; la.act = (int)m->act;
       la.standard = standard ? 1 : 0; la.out_rows = last ? last_rows : pl.rho;
-      la.Whi = nullptr; la.Wlo = nullptr;
+      la.Whi = nullptr; la.Wlo = nullptr; la.Zout = nullptr; la.Zsaved = nullptr; la.bwd = 0;
       bool done = false;
       if constexpr (std::is_same<T, float>::value) {
         if (is_bf16(m->dtype)) {
@@ -299,6 +300,181 @@ template <typename T> hipError_t pack_all(ctm_mlp *m, const void *const *W, cons
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+hipError_t pack_everything(ctm_mlp *m, const void *const *W, const void *const *b, hipStream_t st) {
+  hipError_t e = (m->dtype == CTM_F64) ? pack_all<double>(m, W, b, st) : pack_all<float>(m, W, b, st);
+  const int bn = tile_cols_of(m->dtype);
+  for (int l = 0; e == hipSuccess && is_bf16(m->dtype) && l + 1 < m->L; ++l)
+    e = launch_pack_bf16((const float *)W[l], m->dims[l + 1], m->dims[l], m->Whi[l], m->Wlo[l], m->col_tiles[l] * bn, m->ld[l], st);
+  for (int l = 1; e == hipSuccess && l + 1 < m->L; ++l) {
+    const int rows_pad = m->col_tiles[l - 1] * bn;
+    if (m->dtype == CTM_F64)
+      e = launch_pack<double>((const double *)W[l], nullptr, m->dims[l], m->dims[l + 1], (double *)m->WT[l], nullptr, rows_pad,
+                              m->ld[l + 1], st, 1);
+    else
+      e = launch_pack<float>((const float *)W[l], nullptr, m->dims[l], m->dims[l + 1], (float *)m->WT[l], nullptr, rows_pad,
+                             m->ld[l + 1], st, 1);
+  }
+  return e;
+}
+
+// ---- tape of a recording forward pass (order 2, collapsed, one pass) ---------------------------------
+struct TapeLayout {
+  size_t h0;                  // seed block [M][ld0]
+  std::vector<size_t> z, h;   // per hidden layer i (width dims[i+1]): pre-activations; outputs (all but the last hidden layer)
+  size_t pair, total;
+};
+TapeLayout tape_layout(const ctm_mlp *m, long N, int R) {
+  const size_t es = elem_size(m->dtype);
+  const size_t M = (size_t)N * (size_t)rows_per_point(2, R);
+  TapeLayout t;
+  size_t off = 0;
+  t.h0 = off;
+  off += round256(M * m->ld[0] * es);
+  for (int i = 0; i + 1 < m->L; ++i) {
+    t.z.push_back(off);
+    off += round256(M * m->ld[i + 1] * es);
+    t.h.push_back(off);
+    if (i + 2 < m->L) off += round256(M * m->ld[i + 1] * es);
+  }
+  t.pair = off;
+  off += round256((size_t)N * 2 * m->ld[m->L - 1] * es);
+  t.total = off;
+  return t;
+}
+
+struct BwdLayout {
+  size_t block_bytes, scratch, partials, total;
+};
+BwdLayout bwd_layout(const ctm_mlp *m, long N, int R) {
+  const size_t es = elem_size(m->dtype);
+  const long M = N * rows_per_point(2, R);
+  int maxld = 0;
+  size_t maxpart = 0;
+  for (int i = 0; i + 1 < m->L; ++i) {
+    maxld = m->ld[i + 1] > maxld ? m->ld[i + 1] : maxld;
+    const size_t pe = wgrad_partial_elems(M, m->dims[i + 1], m->dims[i]);
+    maxpart = pe > maxpart ? pe : maxpart;
+  }
+  BwdLayout b;
+  b.block_bytes = round256((size_t)M * maxld * es);
+  b.scratch = 2 * b.block_bytes;
+  b.partials = b.scratch + round256((size_t)(66 * maxld + 64) * es);
+  b.total = b.partials + round256(maxpart * es);
+  return b;
+}
+
+int check_tape_call(const ctm_mlp *m, long N, int R, const char *who) {
+  if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
+  if (m->dtype != CTM_F64 && m->dtype != CTM_F32)
+    return fail(CTM_ERR_UNSUPPORTED, "%s: the recording forward and the reverse pass are built for CTM_F32 and CTM_F64", who);
+  if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
+  if (R < 1) return fail(CTM_ERR_SHAPE, "%s: %d directions, need at least 1", who, R);
+  if (R > max_dirs_per_pass(2))
+    return fail(CTM_ERR_UNSUPPORTED, "%s: %d directions; the recording forward keeps one pass and takes at most %d", who, R,
+                max_dirs_per_pass(2));
+  if (N > (1L << 40) / rows_per_point(2, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
+  return CTM_OK;
+}
+
+template <typename T>
+int run_fwd_tape(const ctm_mlp *m, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
+                 hipStream_t st) {
+  const TapeLayout tl = tape_layout(m, N, R);
+  const PassPlan pl = plan_pass(2, R);
+  const int L = m->L;
+  char *tp = (char *)tape;
+  SeedArgs<T> sa;
+  sa.x = x; sa.V = V; sa.out = (T *)(tp + tl.h0); sa.N = N;
+  sa.v_sn = sn; sa.v_sr = m->dims[0]; sa.v_sd = 1;
+  sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = 2; sa.r0 = 0; sa.standard = 0; sa.R = R;
+  if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
+  hipError_t e = launch_seed<T>(sa, st);
+  if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
+  (void)prof_mark(st, 0);
+  const T *in = sa.out;
+  T *pair = (T *)(tp + tl.pair);
+  for (int i = 0; i + 1 < L; ++i) {
+    const bool last = (i == L - 2);
+    LayerArgs<T> la;
+    la.Hin = in; la.W = (const T *)m->Wp[i]; la.bias = (const T *)m->bp[i]; la.Whi = nullptr; la.Wlo = nullptr;
+    la.Hout = last ? pair : (T *)(tp + tl.h[i]);
+    la.n_points = N; la.n_row_tiles = (N + pl.P - 1) / pl.P; la.n_col_tiles = m->col_tiles[i];
+    la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[i]; la.ldout = m->ld[i + 1];
+    la.order = 2; la.R = R; la.last = last ? 1 : 0; la.act = (int)m->act; la.standard = 0;
+    la.out_rows = last ? 2 : pl.rho;
+    la.Zout = (T *)(tp + tl.z[i]); la.Zsaved = nullptr; la.bwd = 0;
+    e = launch_layer<T>(la, pl.MB, st);
+    if (e != hipSuccess) return fail_hip(e, "layer kernel launch");
+    (void)prof_mark(st, 1);
+    in = la.Hout;
+  }
+  FinalArgs<T> fa;
+  fa.pair = pair; fa.nk = 1; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
+  fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = 0;
+  e = launch_final<T>(fa, st);
+  if (e != hipSuccess) return fail_hip(e, "final kernel launch");
+  (void)prof_mark(st, 2);
+  return CTM_OK;
+}
+
+template <typename T>
+int run_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, const T *gu, const T *gop, void *const *gW,
+            void *const *gb, void *ws, hipStream_t st) {
+  const TapeLayout tl = tape_layout(m, N, R);
+  const BwdLayout bl = bwd_layout(m, N, R);
+  const PassPlan pl = plan_pass(2, R);
+  const int L = m->L;
+  const long M = N * pl.rho;
+  const char *tp = (const char *)tape;
+  T *zb[2] = {(T *)ws, (T *)((char *)ws + bl.block_bytes)};
+  T *scratch = (T *)((char *)ws + bl.scratch);
+  T *partials = (T *)((char *)ws + bl.partials);
+  int maxld = 0;
+  for (int i = 0; i + 1 < L; ++i) maxld = m->ld[i + 1] > maxld ? m->ld[i + 1] : maxld;
+  T *dummy = scratch + 65 * (size_t)maxld;  // maxld + 64 spare elements for gradients the caller does not want
+  if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
+
+  int cur = 0;
+  BwdLastArgs<T> ba;
+  ba.Z = (const T *)(tp + tl.z[L - 2]); ba.w = (const T *)m->Wp[L - 1]; ba.gu = gu; ba.gop = gop; ba.Zbar = zb[cur];
+  ba.N = N; ba.ld = m->ld[L - 1]; ba.rho = pl.rho; ba.R = R; ba.act = (int)m->act; ba.scale = scale;
+  hipError_t e = launch_bwd_last<T>(ba, st);
+  if (e != hipSuccess) return fail_hip(e, "reverse last-layer kernel launch");
+  T *gw_last = (gW && gW[L - 1]) ? (T *)gW[L - 1] : dummy;
+  T *gb_last = (gb && gb[L - 1]) ? (T *)gb[L - 1] : dummy + maxld;
+  e = launch_last_grads<T>((const T *)(tp + tl.pair), gu, gop, scale, N, m->ld[L - 1], m->dims[L - 1], gw_last, gb_last, scratch, st);
+  if (e != hipSuccess) return fail_hip(e, "last-layer gradient kernel launch");
+  (void)prof_mark(st, 0);
+
+  for (int i = L - 2; i >= 0; --i) {
+    const T *Zb = zb[cur];
+    if (gb && gb[i]) {
+      e = launch_bias_grad<T>(Zb, N, pl.rho, m->ld[i + 1], m->dims[i + 1], (T *)gb[i], scratch, st);
+      if (e != hipSuccess) return fail_hip(e, "bias gradient kernel launch");
+    }
+    if (gW && gW[i]) {
+      const T *Hprev = (const T *)(tp + (i == 0 ? tl.h0 : tl.h[i - 1]));
+      e = launch_wgrad<T>(Zb, m->ld[i + 1], Hprev, m->ld[i], M, m->dims[i + 1], m->dims[i], (T *)gW[i], partials, st);
+      if (e != hipSuccess) return fail_hip(e, "weight gradient kernel launch");
+    }
+    (void)prof_mark(st, 2);
+    if (i >= 1) {
+      LayerArgs<T> la;
+      la.Hin = Zb; la.W = (const T *)m->WT[i]; la.bias = (const T *)m->bp[i - 1]; la.Whi = nullptr; la.Wlo = nullptr;
+      la.Hout = zb[cur ^ 1];
+      la.n_points = N; la.n_row_tiles = (N + pl.P - 1) / pl.P; la.n_col_tiles = m->col_tiles[i - 1];
+      la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[i + 1]; la.ldout = m->ld[i];
+      la.order = 2; la.R = R; la.last = 0; la.act = (int)m->act; la.standard = 0; la.out_rows = pl.rho;
+      la.Zout = nullptr; la.Zsaved = (const T *)(tp + tl.z[i - 1]); la.bwd = 1;
+      e = launch_layer<T>(la, pl.MB, st);
+      if (e != hipSuccess) return fail_hip(e, "reverse layer kernel launch");
+      (void)prof_mark(st, 1);
+      cur ^= 1;
+    }
+  }
+  return CTM_OK;
 }
 
 }  // namespace
@@ -386,7 +562,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   m->act = act;
   const int bn = tile_cols_of(dtype);
   size_t total = 0;
-  std::vector<size_t> woff(n_layers), boff(n_layers), hoff(n_layers, 0), loff(n_layers, 0);
+  std::vector<size_t> woff(n_layers), boff(n_layers), hoff(n_layers, 0), loff(n_layers, 0), toff(n_layers, 0);
   for (int l = 0; l < n_layers; ++l) {
     m->ld.push_back(pad_ld(dims[l]));
     const bool lastl = (l == n_layers - 1);
@@ -403,6 +579,10 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
       loff[l] = total;
       total += round256(rows_pad * m->ld[l] * 2);
     }
+    if (l >= 1 && !lastl) {  // transposed copy: rows = padded dims[l], k extent = ld of dims[l+1]
+      toff[l] = total;
+      total += round256((size_t)((dims[l] + bn - 1) / bn) * bn * pad_ld(dims[l + 1]) * es);
+    }
   }
   hipError_t e = hipGetDevice(&m->device);
   if (e != hipSuccess) { delete m; return fail_hip(e, "ctm_create_mlp: hipGetDevice"); }
@@ -417,11 +597,10 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
     m->bp.push_back((char *)m->arena + boff[l]);
     m->Whi.push_back((char *)m->arena + hoff[l]);
     m->Wlo.push_back((char *)m->arena + loff[l]);
+    m->WT.push_back((char *)m->arena + toff[l]);
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  e = (dtype == CTM_F64) ? pack_all<double>(m, W, b, st) : pack_all<float>(m, W, b, st);
-  for (int l = 0; e == hipSuccess && is_bf16(dtype) && l + 1 < n_layers; ++l)
-    e = launch_pack_bf16((const float *)W[l], dims[l + 1], dims[l], m->Whi[l], m->Wlo[l], m->col_tiles[l] * bn, m->ld[l], st);
+  e = pack_everything(m, W, b, st);
   if (e != hipSuccess) {
     (void)hipFree(m->arena);
     delete m;
@@ -554,6 +733,71 @@ int ctm_weighted_laplacian_rand(const ctm_mlp *m, const void *x, long N, const v
                                                 (float *)dirs, Nd, S, (int)D, K, st);
   if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
   return run_operator(m, 2, x, N, dirs, S, per_point ? (long)S * D : 0, D, 1, 1.0 / S, u, op, ws, need - dbytes, stream, who);
+}
+
+int ctm_update_mlp(ctm_mlp *m, const void *const *W, const void *const *b, void *stream) {
+  if (!m || !W) return fail(CTM_ERR_NULL, "ctm_update_mlp: mlp handle or W is NULL");
+  const size_t es = elem_size(m->dtype);
+  for (int l = 0; l < m->L; ++l) {
+    if (!W[l]) return fail(CTM_ERR_NULL, "ctm_update_mlp: W[%d] is NULL", l);
+    if (misaligned(W[l], es) || (b && misaligned(b[l], es)))
+      return fail(CTM_ERR_ALIGN, "ctm_update_mlp: W[%d] / b[%d] not aligned to the element size", l, l);
+  }
+  hipError_t e = pack_everything(m, W, b, reinterpret_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(e, "ctm_update_mlp: weight packing");
+  return CTM_OK;
+}
+
+size_t ctm_tape_bytes(const ctm_mlp *m, long N, int R) {
+  if (check_tape_call(m, N, R, "ctm_tape_bytes") != CTM_OK) return 0;
+  return tape_layout(m, N, R).total;
+}
+
+size_t ctm_backward_workspace_bytes(const ctm_mlp *m, long N, int R) {
+  if (check_tape_call(m, N, R, "ctm_backward_workspace_bytes") != CTM_OK) return 0;
+  return bwd_layout(m, N, R).total;
+}
+
+int ctm_laplacian_fwd(const ctm_mlp *m, const void *x, long N, const void *V, int R, long v_point_stride, double scale, void *u,
+                      void *op, void *tape, size_t tape_bytes, void *stream) {
+  const char *who = "ctm_laplacian_fwd";
+  int rc = check_tape_call(m, N, R, who);
+  if (rc != CTM_OK) return rc;
+  if (!x || !tape) return fail(CTM_ERR_NULL, "%s: x or tape is NULL", who);
+  if (!V && R != m->dims[0]) return fail(CTM_ERR_SHAPE, "%s: V = NULL selects the standard basis, so R must be D = %d (got %d)", who, m->dims[0], R);
+  if (v_point_stride != 0 && v_point_stride != (long)R * m->dims[0])
+    return fail(CTM_ERR_SHAPE, "%s: v_point_stride = %ld, must be 0 (shared) or R*D = %ld", who, v_point_stride, (long)R * m->dims[0]);
+  const size_t need = tape_layout(m, N, R).total;
+  if (tape_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: tape has %zu bytes, need %zu", who, tape_bytes, need);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(tape, 256)) return fail(CTM_ERR_ALIGN, "%s: tape must be 256-byte aligned", who);
+  if (misaligned(x, es) || misaligned(V, es) || misaligned(u, es) || misaligned(op, es))
+    return fail(CTM_ERR_ALIGN, "%s: x, directions, u and op must be aligned to the element size", who);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (m->dtype == CTM_F64)
+    return run_fwd_tape<double>(m, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st);
+  return run_fwd_tape<float>(m, (const float *)x, N, (const float *)V, R, v_point_stride, scale, (float *)u, (float *)op, tape, st);
+}
+
+int ctm_laplacian_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, size_t tape_bytes, const void *gu,
+                      const void *gop, void *const *gW, void *const *gb, void *ws, size_t ws_bytes, void *stream) {
+  const char *who = "ctm_laplacian_bwd";
+  int rc = check_tape_call(m, N, R, who);
+  if (rc != CTM_OK) return rc;
+  if (!tape || !ws) return fail(CTM_ERR_NULL, "%s: tape or workspace is NULL", who);
+  if (tape_bytes < tape_layout(m, N, R).total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than ctm_tape_bytes() says", who);
+  const size_t need = bwd_layout(m, N, R).total;
+  if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(tape, 256) || misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: tape and workspace must be 256-byte aligned", who);
+  if (misaligned(gu, es) || misaligned(gop, es)) return fail(CTM_ERR_ALIGN, "%s: gu and gop must be aligned to the element size", who);
+  for (int l = 0; l < m->L; ++l)
+    if ((gW && misaligned(gW[l], es)) || (gb && misaligned(gb[l], es)))
+      return fail(CTM_ERR_ALIGN, "%s: gW[%d] / gb[%d] not aligned to the element size", who, l, l);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (m->dtype == CTM_F64)
+    return run_bwd<double>(m, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st);
+  return run_bwd<float>(m, N, R, scale, tape, (const float *)gu, (const float *)gop, gW, gb, ws, st);
 }
 
 int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, long long *den) {

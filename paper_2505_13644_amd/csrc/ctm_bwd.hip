@@ -1,0 +1,317 @@
+// Reverse pass of the order-2 collapsed propagation (gradients with respect to the weights):
+// everything except the cotangent GEMM, which reuses layer_kernel with its reverse-rule epilogue.
+//
+// With L = sum_n gu_n u_n + gop_n op_n, u = w.h_0 + b, op = scale * w.h_2 at the last layer and, per hidden
+// layer, Z = H_prev W^T (+ bias on the order-0 rows) followed by the rule (ctm_rule.h):
+//   cotangents at the last hidden layer:  hb_0 = gu w,  hb_{1,r} = 0,  hb_2 = scale gop w      -> bwd_last_kernel
+//   dL/dw = sum_n gu_n h_0(n) + scale gop_n h_2(n),  dL/db_last = sum_n gu_n                  -> last_grads
+//   per hidden layer:  dL/db = sum_n Zbar[order-0 row of n]                                    -> bias_grad
+//                      dL/dW = Zbar^T H_prev   (a GEMM whose k index runs over all N*rho rows)  -> wgrad_kernel
+//                      Hbar_prev = Zbar W, then the reverse rule                                -> layer_kernel (bwd)
+// All reductions over points use fixed partitions and a fixed summation order (no atomics).
+#include "ctm_internal.h"
+#include "ctm_rule.h"
+
+namespace ctm {
+
+// ---- cotangents of the last hidden layer's pre-activations ------------------------------------
+template <typename T> __global__ void bwd_last_kernel(const BwdLastArgs<T> a) {
+  const long total = a.N * a.ld;
+  const int R = a.R, rho = a.rho;
+  const long step = a.ld;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int j = (int)(i % a.ld);
+    const long n = i / a.ld;
+    const T *zs = a.Z + (n * rho) * step + j;
+    T *o = a.Zbar + (n * rho) * step + j;
+    const T w = a.w[j];
+    const T hb0 = (a.gu ? a.gu[n] : T(0)) * w;
+    const T hb2 = (T)(a.scale * (double)(a.gop ? a.gop[n] : T(0))) * w;
+    T d1, d2, d3;
+    if (a.act == 0) {
+      const T t = act_tanh(zs[0]);
+      d1 = T(1) - t * t;
+      d2 = T(-2) * t * d1;
+      d3 = d1 * (T(6) * t * t - T(2));
+    } else {
+      d1 = T(1);
+      d2 = T(0);
+      d3 = T(0);
+    }
+    T s = T(0);
+    for (int r = 1; r <= R; ++r) {
+      const T z1 = zs[r * step];
+      s += z1 * z1;
+      o[r * step] = T(2) * d2 * z1 * hb2;
+    }
+    o[(R + 1) * step] = d1 * hb2;
+    o[0] = d1 * hb0 + d2 * hb2 * zs[(R + 1) * step] + d3 * s * hb2;
+  }
+}
+
+template <typename T> hipError_t launch_bwd_last(const BwdLastArgs<T> &a, hipStream_t s) {
+  long blocks = (a.N * a.ld + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(bwd_last_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+template hipError_t launch_bwd_last<float>(const BwdLastArgs<float> &, hipStream_t);
+template hipError_t launch_bwd_last<double>(const BwdLastArgs<double> &, hipStream_t);
+
+// ---- column sums over the points, two stages with a fixed partition --------------------------------
+constexpr int kSumChunks = 64;
+
+// stage 1: partial[c][j] = sum over the rows n of chunk c of
+//   weighted == 0:  X[n*row_stride + j]
+//   weighted == 1:  ca[n] * X[n*row_stride + j] + sb * cb[n] * X[n*row_stride + second + j]   (a NULL vector counts as zeros)
+template <typename T>
+__global__ void colsum_stage1(const T *X, long row_stride, long second, int weighted, const T *ca, const T *cb, double sb, long N,
+                              int ld, T *partial) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int c = blockIdx.y;
+  if (j >= ld) return;
+  const long per = (N + kSumChunks - 1) / kSumChunks;
+  const long n0 = c * per, n1 = (n0 + per < N) ? n0 + per : N;
+  T acc = T(0);
+  for (long n = n0; n < n1; ++n) {
+    const T *row = X + n * row_stride + j;
+    T v = row[0];
+    if (weighted) v = (ca ? ca[n] : T(0)) * row[0] + (T)(sb * (double)(cb ? cb[n] : T(0))) * row[second];
+    acc += v;
+  }
+  partial[(long)c * ld + j] = acc;
+}
+
+// stage 2: out[j] = sum_c partial[c][j], j < d.  Block 0 / thread 0 also folds `extra` (sum of an N-vector) if asked.
+template <typename T>
+__global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *vec, long N, T *vec_sum) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < d) {
+    T acc = T(0);
+    for (int c = 0; c < kSumChunks; ++c) acc += partial[(long)c * ld + j];
+    out[j] = acc;
+  }
+  if (vec_sum != nullptr && blockIdx.x == 0) {
+    // one wavefront sums the vector in a fixed order
+    __shared__ T red[256];
+    T acc = T(0);
+    if (vec != nullptr)
+      for (long n = threadIdx.x; n < N; n += blockDim.x) acc += vec[n];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = 128; off >= 1; off >>= 1) {
+      if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) vec_sum[0] = red[0];
+  }
+}
+
+template <typename T>
+hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, T *gw, T *gbias,
+                             T *scratch, hipStream_t s) {
+  // the order-0 row weighted by gu plus the collapsed row weighted by scale * gop
+  hipLaunchKernelGGL(colsum_stage1<T>, dim3((ld + 255) / 256, kSumChunks), dim3(256), 0, s, pair, (long)2 * ld, (long)ld, 1, gu, gop,
+                     scale, N, ld, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gw, gu, N, gbias);
+  return hipGetLastError();
+}
+template hipError_t launch_last_grads<float>(const float *, const float *, const float *, double, long, int, int, float *, float *,
+                                             float *, hipStream_t);
+template hipError_t launch_last_grads<double>(const double *, const double *, const double *, double, long, int, int, double *,
+                                              double *, double *, hipStream_t);
+
+template <typename T>
+hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s) {
+  hipLaunchKernelGGL(colsum_stage1<T>, dim3((ld + 255) / 256, kSumChunks), dim3(256), 0, s, Zbar, (long)rho * ld, (long)0, 0,
+                     (const T *)nullptr, (const T *)nullptr, 0.0, N, ld, scratch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gb, (const T *)nullptr, (long)0,
+                     (T *)nullptr);
+  return hipGetLastError();
+}
+template hipError_t launch_bias_grad<float>(const float *, long, int, int, int, float *, float *, hipStream_t);
+template hipError_t launch_bias_grad<double>(const double *, long, int, int, int, double *, double *, hipStream_t);
+
+// ---- weight gradient: C[i][j] = sum_m Zbar[m][i] H[m][j] ---------------------------------------------
+// Both operands are read as stored (k = row index m, feature index contiguous), so an LDS stage is
+// [16 k][128 features] per operand and a lane picks single elements: A[i = l%16][k = l/16] = stage[k][i].
+// A workgroup owns a 128 x 128 output tile over one range of rows; waves are 2 x 2, 4 x 4 MFMA blocks each.
+typedef float wf32x4 __attribute__((ext_vector_type(4)));
+typedef double wf64x4 __attribute__((ext_vector_type(4)));
+template <typename T> struct WVec;
+template <> struct WVec<float> {
+  using acc = wf32x4;
+  using ld4 = wf32x4;
+  static __device__ __forceinline__ int out_row(int g, int v) { return g * 4 + v; }
+  static __device__ __forceinline__ acc mfma(float a, float b, acc c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+};
+template <> struct WVec<double> {
+  using acc = wf64x4;
+  using ld4 = wf64x4;
+  static __device__ __forceinline__ int out_row(int g, int v) { return v * 4 + g; }
+  static __device__ __forceinline__ acc mfma(double a, double b, acc c) { return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0); }
+};
+
+constexpr int kWgTile = 128;
+constexpr int kWgK = 16;               // rows per stage
+constexpr int kWgPitch = kWgTile + 16; // LDS row pitch in elements: the four k rows a wave reads land in distinct banks
+constexpr int kWgTargetBlocks = 2048;
+
+struct WgradPlan {
+  int ti, tj, ksplit;
+  long rows_per;
+};
+static WgradPlan wgrad_plan(long M, int d_out, int d_in) {
+  WgradPlan p;
+  p.ti = (d_out + kWgTile - 1) / kWgTile;
+  p.tj = (d_in + kWgTile - 1) / kWgTile;
+  long ks = kWgTargetBlocks / ((long)p.ti * p.tj);
+  const long max_ks = (M + 4 * kWgK - 1) / (4 * kWgK);  // at least four stages per block
+  if (ks > max_ks) ks = max_ks;
+  if (ks > 1024) ks = 1024;
+  if (ks < 1) ks = 1;
+  p.rows_per = ((M + ks - 1) / ks + kWgK - 1) / kWgK * kWgK;
+  p.ksplit = (int)((M + p.rows_per - 1) / p.rows_per);
+  return p;
+}
+size_t wgrad_partial_elems(long M, int d_out, int d_in) {
+  const WgradPlan p = wgrad_plan(M, d_out, d_in);
+  return (size_t)p.ksplit * p.ti * kWgTile * p.tj * kWgTile;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_kernel(const T *Zb, int ld_out, const T *H, int ld_in, long M, long rows_per, int tj,
+                                                    T *partials) {
+  using V = WVec<T>;
+  using vacc = typename V::acc;
+  using v4 = typename V::ld4;
+  extern __shared__ __align__(16) unsigned char wg_lds[];
+  T(*As)[kWgK][kWgPitch] = reinterpret_cast<T(*)[kWgK][kWgPitch]>(wg_lds);
+  T(*Bs)[kWgK][kWgPitch] = As + 2;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int tile = blockIdx.x;
+  const int ti = tile / tj, tjx = tile % tj;
+  const int ks = blockIdx.y;
+  const long m0 = ks * rows_per;
+  const long m1 = (m0 + rows_per < M) ? m0 + rows_per : M;
+  const int i0 = ti * kWgTile, j0 = tjx * kWgTile;
+
+  // copy slots: 16 rows x 128 columns per operand = 512 four-element units, two per thread
+  int srow[2], scol[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int u = tid + q * 256;
+    srow[q] = u / 32;
+    scol[q] = (u % 32) * 4;
+  }
+  v4 ra[2], rb[2];
+  auto load_global = [&](long m) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const long row = m + srow[q];
+      v4 za = {0, 0, 0, 0}, zb = {0, 0, 0, 0};
+      if (row < m1) {
+        if (i0 + scol[q] < ld_out) za = *reinterpret_cast<const v4 *>(Zb + row * ld_out + i0 + scol[q]);
+        if (j0 + scol[q] < ld_in) zb = *reinterpret_cast<const v4 *>(H + row * ld_in + j0 + scol[q]);
+      }
+      ra[q] = za;
+      rb[q] = zb;
+    }
+  };
+  auto store_lds = [&](int st) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      *reinterpret_cast<v4 *>(&As[st][srow[q]][scol[q]]) = ra[q];
+      *reinterpret_cast<v4 *>(&Bs[st][srow[q]][scol[q]]) = rb[q];
+    }
+  };
+
+  vacc acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = vacc{0, 0, 0, 0};
+
+  const long nst = (m1 - m0 + kWgK - 1) / kWgK;
+  load_global(m0);
+  store_lds(0);
+  __syncthreads();
+  for (long st = 0; st < nst; ++st) {
+    const int cur = (int)(st & 1);
+    if (st + 1 < nst) load_global(m0 + (st + 1) * kWgK);
+#pragma unroll
+    for (int kk = 0; kk < kWgK / 4; ++kk) {
+      T af[4], bf[4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) af[a] = As[cur][kk * 4 + lg][wi * 64 + a * 16 + lr];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) bf[b] = Bs[cur][kk * 4 + lg][wj * 64 + b * 16 + lr];
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = V::mfma(af[a], bf[b], acc[a][b]);
+    }
+    if (st + 1 < nst) store_lds(cur ^ 1);
+    __syncthreads();
+  }
+
+  // partial tile -> partials[ks][i][j] (padded to whole tiles)
+  const long pi = (long)gridDim.x / tj * kWgTile;  // padded rows
+  const long pj = (long)tj * kWgTile;
+  T *P = partials + (long)ks * pi * pj;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const long i = i0 + wi * 64 + a * 16 + V::out_row(lg, v);
+        const long j = j0 + wj * 64 + b * 16 + lr;
+        P[i * pj + j] = acc[a][b][v];
+      }
+}
+
+template <typename T>
+__global__ void wgrad_reduce_kernel(const T *partials, int ksplit, long pi, long pj, int d_out, int d_in, T *gW) {
+  const long total = (long)d_out * d_in;
+  for (long idx = blockIdx.x * (long)blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+    const long i = idx / d_in, j = idx % d_in;
+    T acc = T(0);
+    for (int k = 0; k < ksplit; ++k) acc += partials[((long)k * pi + i) * pj + j];
+    gW[idx] = acc;
+  }
+}
+
+template <typename T>
+hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M, int d_out, int d_in, T *gW, T *partials,
+                        hipStream_t s) {
+  const WgradPlan p = wgrad_plan(M, d_out, d_in);
+  constexpr size_t lds = 4 * (size_t)kWgK * kWgPitch * sizeof(T);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)lds);
+    if (ea != hipSuccess) return ea;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(wgrad_kernel<T>, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
+                     p.rows_per, p.tj, partials);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  long blocks = ((long)d_out * d_in + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(wgrad_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, partials, p.ksplit, (long)p.ti * kWgTile,
+                     (long)p.tj * kWgTile, d_out, d_in, gW);
+  return hipGetLastError();
+}
+template hipError_t launch_wgrad<float>(const float *, int, const float *, int, long, int, int, float *, float *, hipStream_t);
+template hipError_t launch_wgrad<double>(const double *, int, const double *, int, long, int, int, double *, double *, hipStream_t);
+
+}  // namespace ctm

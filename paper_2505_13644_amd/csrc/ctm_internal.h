@@ -47,6 +47,10 @@ template <typename T> struct LayerArgs {
   int act;           // 0 tanh, 1 identity
   int standard;      // 1: un-collapsed Taylor mode (1 + K*R rows per point), for comparison
   int out_rows;      // rows per point in Hout: rho, or when last: 2 (collapsed) / 1 + R (standard)
+  T *Zout;           // forward that records a tape: the pre-activation rows [n_points * rho][ldout] go here too (else nullptr)
+  const T *Zsaved;   // bwd == 1: recorded pre-activations of the layer whose rule is reversed, [n_points * rho][ldout]
+  int bwd;           // 1: Hin holds cotangents, W the transposed weights, and the epilogue is the reverse of the
+                     //    order-2 collapsed rule (writes the cotangents of the pre-activations)
 };
 
 // Launch the stacked GEMM + fused jet rule for one layer.  MB in {4, 8, 9, 12, 13, 16}.
@@ -88,9 +92,38 @@ template <typename T> struct FirstArgs {
 bool first_layer_fast_path(int D, long v_point_stride);
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s);
 
+// transpose == 0: Wp[j][k] = W[j][k] (W is [d_out][d_in]); transpose == 1: Wp[j][k] = W[k][j] (W is [d_in][d_out]).
+// bp may be nullptr.
 template <typename T>
 hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad,
-                       int ld, hipStream_t s);
+                       int ld, hipStream_t s, int transpose = 0);
+
+// ---- reverse pass (order 2, collapsed) -----------------------------------------------------
+template <typename T> struct BwdLastArgs {
+  const T *Z;     // recorded pre-activations of the last hidden layer [N * rho][ld]
+  const T *w;     // last-layer weights [ld]
+  const T *gu;    // dL/du [N] or nullptr
+  const T *gop;   // dL/dop [N] or nullptr
+  T *Zbar;        // out: cotangents of those pre-activations [N * rho][ld]
+  long N;
+  int ld, rho, R, act;
+  double scale;
+};
+template <typename T> hipError_t launch_bwd_last(const BwdLastArgs<T> &a, hipStream_t s);
+
+// gw[j] = sum_n gu[n] pair[n][0][j] + scale gop[n] pair[n][1][j] (j < d), gbias[0] = sum_n gu[n]; scratch >= 65 * ld elements
+template <typename T>
+hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, T *gw, T *gbias,
+                             T *scratch, hipStream_t s);
+// gb[j] = sum_n Zbar[n * rho][j] (j < d); scratch >= 64 * ld elements
+template <typename T>
+hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s);
+// gW[i][j] = sum_m Zbar[m][i] * H[m][j], i < d_out, j < d_in (gW row-major [d_out][d_in]); split over row ranges,
+// partial sums in `partials` (wgrad_partial_elems elements), added in a fixed order
+size_t wgrad_partial_elems(long M, int d_out, int d_in);
+template <typename T>
+hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M, int d_out, int d_in, T *gW, T *partials,
+                        hipStream_t s);
 
 // Direction families of the exact biharmonic (interpolation with 4-jets): family 0: 4 e_d (D rows);
 // family 1: 3 e_d1 + e_d2, d1 != d2 (D(D-1) rows); family 2: 2 e_d1 + 2 e_d2, d1 < d2 (D(D-1)/2 rows).

@@ -258,7 +258,12 @@ void layer_kernel(const LayerArgs<T> a) {
       const long n = p0 + p;
       T *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
       const long ostep = a.ldout;
-      jet_rule<T>(c, CROW, bias, o, ostep, a);
+      if (a.bwd) {
+        jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg, a.ldout, o, ostep, a);
+      } else {
+        if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
+        jet_rule<T>(c, CROW, bias, o, ostep, a);
+      }
     }
   }
 }

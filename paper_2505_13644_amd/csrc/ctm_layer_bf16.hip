@@ -231,6 +231,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
       const float *c = Cs + (long)p * rho * CROW + j;
       const long n = p0 + p;
       float *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
+      if (a.Zout) save_preactivations<float>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
       jet_rule<float>(c, CROW, bias, o, a.ldout, a);
     }
   }

@@ -49,26 +49,29 @@ template hipError_t launch_seed<double>(const SeedArgs<double> &, hipStream_t);
 
 // ---- weights: [d_out][d_in] -> zero-padded [rows_pad][ld]; bias -> [rows_pad] ---------------
 template <typename T>
-__global__ void pack_kernel(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad, int ld) {
+__global__ void pack_kernel(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad, int ld, int transpose) {
   const long total = (long)rows_pad * ld;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
     const int k = (int)(i % ld);
     const int j = (int)(i / ld);
-    Wp[i] = (j < d_out && k < d_in) ? W[(long)j * d_in + k] : T(0);
-    if (k == 0) bp[j] = (b != nullptr && j < d_out) ? b[j] : T(0);
+    T v = T(0);
+    if (j < d_out && k < d_in) v = transpose ? W[(long)k * d_out + j] : W[(long)j * d_in + k];
+    Wp[i] = v;
+    if (k == 0 && bp != nullptr) bp[j] = (b != nullptr && j < d_out) ? b[j] : T(0);
   }
 }
 
 template <typename T>
-hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad, int ld, hipStream_t s) {
+hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad, int ld, hipStream_t s,
+                       int transpose) {
   const long total = (long)rows_pad * ld;
   long blocks = (total + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(pack_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, W, b, d_out, d_in, Wp, bp, rows_pad, ld);
+  hipLaunchKernelGGL(pack_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, W, b, d_out, d_in, Wp, bp, rows_pad, ld, transpose);
   return hipGetLastError();
 }
-template hipError_t launch_pack<float>(const float *, const float *, int, int, float *, float *, int, int, hipStream_t);
-template hipError_t launch_pack<double>(const double *, const double *, int, int, double *, double *, int, int, hipStream_t);
+template hipError_t launch_pack<float>(const float *, const float *, int, int, float *, float *, int, int, hipStream_t, int);
+template hipError_t launch_pack<double>(const double *, const double *, int, int, double *, double *, int, int, hipStream_t, int);
 
 // ---- direction sets of the exact biharmonic (Sec. 3.3 / App. E.1: 4-jets along 4 e_d, 3 e_d1 + e_d2, 2 e_d1 + 2 e_d2)
 template <typename T> __global__ void biharm_dirs_kernel(T *V, int D, int family, long rows) {

@@ -113,4 +113,46 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
   }
 }
 
+// Record the pre-activation rows of one (point, feature) pair (bias on the order-0 row only).
+template <typename T>
+__device__ __forceinline__ void save_preactivations(const T *c, int CROW, T bias, T *zo, long zstep, int rho) {
+  zo[0] = c[0] + bias;
+  for (int r = 1; r < rho; ++r) zo[r * zstep] = c[(long)r * CROW];
+}
+
+// Reverse of the order-2 collapsed rule for one (point, feature) pair.  With z the recorded pre-activations,
+// hb the cotangents of (h_0, h_{1,r}, h_2) and d3 the third derivative of tanh, d1 (6 t^2 - 2):
+//   zb_2     = d1 hb_2
+//   zb_{1,r} = d1 hb_{1,r} + 2 d2 z_{1,r} hb_2
+//   zb_0     = d1 hb_0 + d2 (sum_r hb_{1,r} z_{1,r} + hb_2 z_2) + d3 hb_2 sum_r z_{1,r}^2
+// (differentiate h_0 = t, h_{1,r} = d1 z_{1,r}, h_2 = d1 z_2 + d2 sum_r z_{1,r}^2; d1 and d2 depend on z_0 with
+// derivatives d2 and d3).  c: cotangent column in the staged C tile; zs: recorded column; o: output column.
+template <typename T>
+__device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, long zstep, T *o, long ostep, const LayerArgs<T> &a) {
+  const int R = a.R;
+  const T z0 = zs[0];
+  T d1, d2, d3;
+  if (a.act == 0) {
+    const T t = act_tanh(z0);
+    d1 = T(1) - t * t;
+    d2 = T(-2) * t * d1;
+    d3 = d1 * (T(6) * t * t - T(2));
+  } else {
+    d1 = T(1);
+    d2 = T(0);
+    d3 = T(0);
+  }
+  const T hb0 = c[0], hb2 = c[(long)(R + 1) * CROW];
+  const T z2 = zs[(long)(R + 1) * zstep];
+  T s = T(0), dot = T(0);
+  for (int r = 1; r <= R; ++r) {
+    const T z1 = zs[(long)r * zstep], hb1 = c[(long)r * CROW];
+    s += z1 * z1;
+    dot += hb1 * z1;
+    o[r * ostep] = d1 * hb1 + T(2) * d2 * z1 * hb2;
+  }
+  o[(R + 1) * ostep] = d1 * hb2;
+  o[0] = d1 * hb0 + d2 * (dot + hb2 * z2) + d3 * s * hb2;
+}
+
 }  // namespace ctm

@@ -1,0 +1,118 @@
+"""GPU parity of the reverse pass: dL/dW_l and dL/db_l of L = sum_n gu_n u_n + gop_n op_n from the HIP path against
+the nested-autograd fp64 oracle, on identical seeded inputs.  Metric: per tensor, max |got - ref| / max |ref|."""
+import numpy as np
+import pytest
+
+from paper_2505_13644_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu(arrs, scale, gu, gop, dtype):
+    import torch
+    import paper_2505_13644_amd as ctm
+    dev = torch.device("cuda:0")
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    x, V = t(arrs["x"]), t(arrs.get("V"))
+    N = x.shape[0]
+    R = x.shape[1] if V is None else V.shape[-2]
+    u, op, tape = ctm.ctm_laplacian_fwd(mlp, x, V, scale)
+    u2, op2 = ctm.ctm_laplacian(mlp, x, V, scale)
+    gW, gb = ctm.ctm_laplacian_bwd(mlp, N, R, scale, tape, t(gu.astype(dtype)), t(gop.astype(dtype)))
+    torch.cuda.synchronize()
+    # the plain call takes the GEMM-free first layer for shared directions, so the two differ by rounding only
+    tol = 1e-12 if dtype == np.float64 else 2e-5
+    den_u, den_o = u2.abs().max().item(), op2.abs().max().item()
+    same = (u - u2).abs().max().item() <= tol * den_u and (op - op2).abs().max().item() <= tol * den_o
+    out = ([g.double().cpu().numpy() for g in gW], [g.double().cpu().numpy() for g in gb], same)
+    mlp.close()
+    return out
+
+
+def rel(got, ref):
+    den = np.max(np.abs(ref))
+    return np.max(np.abs(got - ref)) / (den if den > 0 else 1.0)
+
+
+def case(dims, N, dtype, seed, R, per_point, bias=0.1):
+    Ws, bs = synth.make_mlp(dims, seed, bias, dtype)
+    arrs = {"Ws": Ws, "bs": bs, "x": synth.make_points(N, dims[0], seed, dtype)}
+    arrs["V"] = None if R is None else synth.make_directions("gaussian", (N, R, dims[0]) if per_point else (R, dims[0]), seed, dtype)
+    return arrs
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,R,per_point", [
+    ((5, 16, 16, 1), 8, None, False),        # c1's network
+    ((6, 40, 24, 1), 37, 9, False),          # shared directions, ragged tiles
+    ((4, 48, 48, 48, 1), 33, 7, True),       # three hidden layers, per-point directions
+    ((3, 100, 1), 130, None, False),         # one hidden layer
+    ((7, 33, 65, 1), 19, 3, True),           # odd widths
+    ((50, 160, 144, 1), 300, None, False),   # widths over one 128-column tile, many row ranges in the weight gradient
+])
+def test_weight_gradients_against_the_autograd_oracle(dtype, dims, N, R, per_point):
+    from oracle import gradients as og
+    arrs = case(dims, N, dtype, seed=N + len(dims), R=R, per_point=per_point)
+    rng = np.random.default_rng(N)
+    gu, gop = rng.standard_normal(N), rng.standard_normal(N)
+    scale = 0.37
+    print(f"case backward dims={dims} N={N} R={R} {dtype.__name__}", flush=True)
+    gW, gb, same = run_gpu(arrs, scale, gu, gop, dtype)
+    assert same, "the recording forward must agree with ctm_laplacian"
+    _, rW, rb = og.laplacian_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], arrs["V"], scale,
+                                        gu.astype(dtype).astype(np.float64), gop.astype(dtype).astype(np.float64))
+    tol = 1e-9 if dtype == np.float64 else 2e-4
+    for l in range(len(dims) - 1):
+        eW, eb = rel(gW[l], rW[l]), rel(gb[l], rb[l])
+        print(f"  layer {l}: dW err {eW:.2e}  db err {eb:.2e}", flush=True)
+        assert eW <= tol and eb <= tol, (l, eW, eb)
+
+
+def test_backward_on_the_benchmark_network_and_determinism():
+    from oracle import gradients as og
+    w = synth.WORKLOADS["c2"]
+    N = 24
+    arrs = w.build(N)
+    rng = np.random.default_rng(3)
+    gu, gop = rng.standard_normal(N), rng.standard_normal(N)
+    gW, gb, same = run_gpu(arrs, 1.0, gu, gop, np.float32)
+    gW2, gb2, _ = run_gpu(arrs, 1.0, gu, gop, np.float32)
+    assert same
+    for a, b in zip(gW + gb, gW2 + gb2):
+        assert np.array_equal(a, b)
+    _, rW, rb = og.laplacian_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], None, 1.0, gu.astype(np.float32).astype(np.float64),
+                                        gop.astype(np.float32).astype(np.float64))
+    for l in range(5):
+        eW, eb = rel(gW[l], rW[l]), rel(gb[l], rb[l])
+        print(f"  c2 net layer {l}: dW err {eW:.2e}  db err {eb:.2e}", flush=True)
+        assert eW <= 2e-4 and eb <= 2e-4
+
+
+def test_only_some_gradients_and_missing_cotangents():
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import gradients as og
+    arrs = case((6, 40, 24, 1), 21, np.float64, 5, 4, True)
+    dev = torch.device("cuda:0")
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    x, V = t(arrs["x"]), t(arrs["V"])
+    u, op, tape = ctm.ctm_laplacian_fwd(mlp, x, V, 0.25)
+    gop = np.random.default_rng(1).standard_normal(21)
+    gW = [None, torch.full((24, 40), 9.0, dtype=torch.float64, device=dev), None]
+    gb = [torch.full((40,), 9.0, dtype=torch.float64, device=dev), None, None]
+    ctm.ctm_laplacian_bwd(mlp, 21, 4, 0.25, tape, None, t(gop), gW, gb)       # gu = NULL: zeros
+    torch.cuda.synchronize()
+    _, rW, rb = og.laplacian_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], arrs["V"], 0.25, np.zeros(21), gop)
+    assert rel(gW[1].cpu().numpy(), rW[1]) <= 1e-9 and rel(gb[0].cpu().numpy(), rb[0]) <= 1e-9
+    # new weights through ctm_update_mlp give the gradients of the new network
+    Ws2, bs2 = synth.make_mlp((6, 40, 24, 1), 77, 0.1, np.float64)
+    ctm.ctm_update_mlp(mlp, [t(W) for W in Ws2], [t(b) for b in bs2])
+    u, op, tape = ctm.ctm_laplacian_fwd(mlp, x, V, 0.25)
+    gWn, gbn = ctm.ctm_laplacian_bwd(mlp, 21, 4, 0.25, tape, None, t(gop))
+    torch.cuda.synchronize()
+    _, rW2, rb2 = og.laplacian_loss_grads(Ws2, bs2, arrs["x"], arrs["V"], 0.25, np.zeros(21), gop)
+    for l in range(3):
+        assert rel(gWn[l].cpu().numpy(), rW2[l]) <= 1e-9 and rel(gbn[l].cpu().numpy(), rb2[l]) <= 1e-9
+    mlp.close()
