@@ -91,6 +91,8 @@ def main():
                     help="matrix cores used by the GEMMs of an fp32 workload: native fp32 (default), split bf16 or plain bf16")
     ap.add_argument("--taylor", choices=["collapsed", "standard"], default="collapsed",
                     help="standard = the un-collapsed comparison path (1 + K*R rows per point); c1..c5 only")
+    ap.add_argument("--backward", action="store_true",
+                    help="time forward-with-tape plus the reverse pass to all weights (laplacian workloads, collapsed, native MFMA)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -127,8 +129,23 @@ def main():
         std_scale = 1.0 / (3.0 * R) if K == 4 else arrs.get("scale", 1.0)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
 
+    bwd = args.backward
+    if bwd:
+        if w.op != "laplacian" or std or args.mfma != "native":
+            sys.exit("bench.py: --backward covers the laplacian workloads with collapsed Taylor mode and native MFMA")
+        tape = torch.empty(ctm.ctm_tape_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
+        ws = torch.empty(ctm.ctm_backward_workspace_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
+        gu = torch.ones(w.N, dtype=x.dtype, device=dev)
+        gop = torch.ones(w.N, dtype=x.dtype, device=dev)
+        nl = len(w.dims) - 1
+        gW = [torch.empty(w.dims[l + 1], w.dims[l], dtype=x.dtype, device=dev) for l in range(nl)]
+        gb = [torch.empty(w.dims[l + 1], dtype=x.dtype, device=dev) for l in range(nl)]
+
     def step():
-        if std:
+        if bwd:
+            ctm.ctm_laplacian_fwd(mlp, x, V, arrs.get("scale", 1.0), u, op, tape)
+            ctm.ctm_laplacian_bwd(mlp, w.N, R, arrs.get("scale", 1.0), tape, gu, gop, gW, gb, ws)
+        elif std:
             ctm.ctm_taylor_standard(mlp, K, x, Vstd, std_scale, u, op, ws)
         elif w.op == "laplacian":
             ctm.ctm_laplacian(mlp, x, V, arrs.get("scale", 1.0), u, op, ws)
@@ -168,9 +185,15 @@ def main():
         fams = [D, D * (D - 1), D * (D - 1) // 2]
         flops = sum(gemm_flops(w.dims, w.N, ctm.ctm_rows_per_point(4, r), r, False) for r in fams if r)
         rho = sum(ctm.ctm_rows_per_point(4, r) for r in fams if r)
+    elif bwd:
+        # forward GEMMs over all rows (the recording forward always builds the input block), and per hidden layer
+        # one weight-gradient GEMM plus, except for the first layer, one cotangent GEMM
+        fwd = sum(2.0 * w.N * rho * w.dims[l] * w.dims[l + 1] for l in range(len(w.dims) - 2))
+        dgrad = sum(2.0 * w.N * rho * w.dims[l] * w.dims[l + 1] for l in range(1, len(w.dims) - 2))
+        flops = fwd + fwd + dgrad
     else:
         flops = gemm_flops(w.dims, w.N, rho, R, w.directions in ("rademacher", "gaussian"))
-    layer_ms_per_step = ms["layer"] / args.steps
+    layer_ms_per_step = (ms["layer"] + (ms["final"] if bwd else 0.0)) / args.steps   # reverse pass: class "final" holds the weight-gradient GEMMs
     dt = "f64" if w.dtype == np.float64 else "f32"
     if args.mfma != "native":
         dt = args.mfma
@@ -199,7 +222,8 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.op}, tanh MLP {'-'.join(map(str, w.dims))}, N={w.N}, "
-                               f"{w.directions} directions R={R}, {args.taylor} order-{K} Taylor mode, {rho} rows/point"},
+                               f"{w.directions} directions R={R}, {args.taylor} order-{K} Taylor mode, {rho} rows/point"
+                               + (", forward with tape + reverse pass to all weights" if bwd else "")},
         "roofline": roofline,
     }
     if args.cpu_seconds > 0:

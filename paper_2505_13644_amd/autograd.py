@@ -1,0 +1,37 @@
+"""torch.autograd glue around the recording forward and the reverse pass of libctm.so.
+
+    u, op = laplacian(mlp, Ws, bs, x, V=None, scale=1.0)
+
+returns tensors that are differentiable with respect to the weight tensors Ws / bs (not x or V).  Every number is
+produced by the library's kernels; this module only re-packs the current weights into the handle
+(ctm_update_mlp), keeps the tape alive between forward and backward, and hands the gradients to autograd.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class _Laplacian(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, mlp, x, V, scale, n_layers, *params):
+        Ws, bs = list(params[:n_layers]), list(params[n_layers:])
+        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        u, op, tape = B.ctm_laplacian_fwd(mlp, x, V, scale)
+        ctx.mlp, ctx.tape, ctx.scale, ctx.n_layers = mlp, tape, scale, n_layers
+        ctx.N = x.shape[0]
+        ctx.R = x.shape[1] if V is None else V.shape[-2]
+        return u, op
+
+    @staticmethod
+    def backward(ctx, gu, gop):
+        gu = None if gu is None else gu.contiguous()
+        gop = None if gop is None else gop.contiguous()
+        gW, gb = B.ctm_laplacian_bwd(ctx.mlp, ctx.N, ctx.R, ctx.scale, ctx.tape, gu, gop)
+        return (None, None, None, None, None, *gW, *gb)
+
+
+def laplacian(mlp, Ws, bs, x, V=None, scale=1.0):
+    """(u, op) of ctm_laplacian, differentiable with respect to the tensors in Ws and bs."""
+    return _Laplacian.apply(mlp, x, V, float(scale), len(Ws), *Ws, *bs)

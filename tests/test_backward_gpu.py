@@ -116,3 +116,49 @@ def test_only_some_gradients_and_missing_cotangents():
     for l in range(3):
         assert rel(gWn[l].cpu().numpy(), rW2[l]) <= 1e-9 and rel(gbn[l].cpu().numpy(), rb2[l]) <= 1e-9
     mlp.close()
+
+
+def test_autograd_wrapper_trains_a_small_pinn():
+    # Poisson problem  Lap u = f  on [0,1]^3 with the manufactured solution u* = sum_i sin(pi x_i):
+    # f = -pi^2 u*.  A few Adam steps on residual + boundary-free value loss must reduce the loss, and the
+    # gradients autograd receives must equal the oracle's.
+    import torch
+    import paper_2505_13644_amd as ctm
+    from paper_2505_13644_amd.autograd import laplacian
+    from oracle import gradients as og
+    dev = torch.device("cuda:0")
+    dims, N = (3, 32, 32, 1), 256
+    Wn, bn = synth.make_mlp(dims, 11, 0.05, np.float64)
+    Ws = [torch.tensor(W, device=dev, requires_grad=True) for W in Wn]
+    bs = [torch.tensor(b, device=dev, requires_grad=True) for b in bn]
+    xn = synth.make_points(N, 3, 11, np.float64)
+    x = torch.tensor(xn, device=dev)
+    ustar = torch.sin(np.pi * x).sum(1)
+    f = -np.pi ** 2 * ustar
+    mlp = ctm.ctm_create_mlp([W.detach() for W in Ws], [b.detach() for b in bs])
+
+    def loss_fn():
+        u, lap = laplacian(mlp, Ws, bs, x)
+        return ((lap - f) ** 2).mean() + ((u - ustar) ** 2).mean()
+
+    # gradient check against the oracle at the initial weights: dL/du = 2 (u - u*) / N, dL/dop = 2 (lap - f) / N
+    loss = loss_fn()
+    loss.backward()
+    with torch.no_grad():
+        u0, lap0 = ctm.ctm_laplacian(mlp, x)
+        gu = (2 * (u0 - ustar) / N).cpu().numpy()
+        gop = (2 * (lap0 - f) / N).cpu().numpy()
+    _, rW, rb = og.laplacian_loss_grads(Wn, bn, xn, None, 1.0, gu, gop)
+    for l in range(3):
+        assert rel(Ws[l].grad.cpu().numpy(), rW[l]) <= 1e-8 and rel(bs[l].grad.cpu().numpy(), rb[l]) <= 1e-8
+    opt = torch.optim.Adam(Ws + bs, lr=3e-3)
+    first = float(loss)
+    for _ in range(60):
+        opt.zero_grad()
+        loss = loss_fn()
+        loss.backward()
+        opt.step()
+    last = float(loss_fn())
+    print(f"  pinn loss {first:.4f} -> {last:.4f}", flush=True)
+    assert last < 0.5 * first
+    mlp.close()
