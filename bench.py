@@ -2,7 +2,12 @@
 
 One step = one operator call over the whole batch: seed the coefficient block, the stacked
 GEMM + jet rule of every hidden layer, and the last layer.  Inputs are resident in HBM before
-the timed region.  Prints one JSON line (see the design doc for the fields).
+the timed region.  Prints one JSON line:
+  value / unit        operator evaluations per second (N / time per step), whole job
+  roofline            the stacked-GEMM launches of a step: algorithmic flops / their HIP-event-timed duration
+                      against the dense MFMA peak of the arithmetic type; `traffic` = HBM bytes per launch from
+                      the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of the workload (null if none)
+  cpu_baseline        the fp64 numpy oracle timed on the host cores for a bounded sample of the same workload
 """
 import argparse
 import json

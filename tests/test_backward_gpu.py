@@ -152,13 +152,13 @@ def test_autograd_wrapper_trains_a_small_pinn():
     for l in range(3):
         assert rel(Ws[l].grad.cpu().numpy(), rW[l]) <= 1e-8 and rel(bs[l].grad.cpu().numpy(), rb[l]) <= 1e-8
     opt = torch.optim.Adam(Ws + bs, lr=3e-3)
-    first = float(loss)
+    first = loss.item()
     for _ in range(60):
         opt.zero_grad()
         loss = loss_fn()
         loss.backward()
         opt.step()
-    last = float(loss_fn())
+    last = loss_fn().item()
     print(f"  pinn loss {first:.4f} -> {last:.4f}", flush=True)
     assert last < 0.5 * first
     mlp.close()
