@@ -55,7 +55,8 @@ typedef enum {
 
 typedef enum {
   CTM_ACT_TANH = 0,
-  CTM_ACT_IDENTITY = 1 /* linear network: every operator is exactly 0 (a test hook) */
+  CTM_ACT_IDENTITY = 1, /* linear network: every operator is exactly 0 (a test hook)          */
+  CTM_ACT_SIN = 2       /* sin, the elementwise example of the paper's graph-rewrite appendix  */
 } ctm_act;
 
 typedef enum {

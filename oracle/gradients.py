@@ -19,7 +19,7 @@ def _mlp(params, x, act):
     for l, (W, b) in enumerate(zip(Ws, bs)):
         h = h @ W.T + b
         if l < len(Ws) - 1:
-            h = torch.tanh(h) if act == "tanh" else h
+            h = torch.tanh(h) if act == "tanh" else (torch.sin(h) if act == "sin" else h)
     return h[..., 0]
 
 

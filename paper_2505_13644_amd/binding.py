@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libctm.so")
 
 CTM_F64, CTM_F32, CTM_F32_BF16X3, CTM_F32_BF16 = 0, 1, 2, 3
-CTM_ACT_TANH, CTM_ACT_IDENTITY = 0, 1
+CTM_ACT_TANH, CTM_ACT_IDENTITY, CTM_ACT_SIN = 0, 1, 2
 CTM_OK = 0
 STATUS_NAMES = {
     0: "CTM_OK", -1: "CTM_ERR_NULL", -2: "CTM_ERR_SHAPE", -3: "CTM_ERR_DTYPE", -4: "CTM_ERR_UNSUPPORTED",

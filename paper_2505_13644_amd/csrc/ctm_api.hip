@@ -540,7 +540,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   *out = nullptr;
   if (!dims || !W) return fail(CTM_ERR_NULL, "ctm_create_mlp: dims or W is NULL");
   if (!known_dtype(dtype)) return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown dtype %d", (int)dtype);
-  if (act != CTM_ACT_TANH && act != CTM_ACT_IDENTITY)
+  if (act != CTM_ACT_TANH && act != CTM_ACT_IDENTITY && act != CTM_ACT_SIN)
     return fail(CTM_ERR_DTYPE, "ctm_create_mlp: unknown activation %d", (int)act);
   if (n_layers < 2 || n_layers > 64)
     return fail(CTM_ERR_SHAPE, "ctm_create_mlp: n_layers = %d, need 2..64 (at least one hidden layer)", n_layers);

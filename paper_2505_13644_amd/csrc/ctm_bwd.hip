@@ -27,17 +27,9 @@ template <typename T> __global__ void bwd_last_kernel(const BwdLastArgs<T> a) {
     const T w = a.w[j];
     const T hb0 = (a.gu ? a.gu[n] : T(0)) * w;
     const T hb2 = (T)(a.scale * (double)(a.gop ? a.gop[n] : T(0))) * w;
-    T d1, d2, d3;
-    if (a.act == 0) {
-      const T t = act_tanh(zs[0]);
-      d1 = T(1) - t * t;
-      d2 = T(-2) * t * d1;
-      d3 = d1 * (T(6) * t * t - T(2));
-    } else {
-      d1 = T(1);
-      d2 = T(0);
-      d3 = T(0);
-    }
+    T t, d1;
+    act_eval<T>(a.act, zs[0], t, d1);
+    const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
     T s = T(0);
     for (int r = 1; r <= R; ++r) {
       const T z1 = zs[r * step];

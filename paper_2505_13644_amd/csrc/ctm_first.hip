@@ -11,11 +11,9 @@
 // so the whole layer is bound by writing the [N * rho, d_1] block to HBM; no GEMM over the
 // rho rows of every point is needed.
 #include "ctm_internal.h"
+#include "ctm_rule.h"
 
 namespace ctm {
-
-__device__ __forceinline__ float tanh_of(float z) { return tanhf(z); }
-__device__ __forceinline__ double tanh_of(double z) { return tanh(z); }
 
 // z1[r][j] = sum_k W[j][k] v_r[k].  One thread per (direction, feature).
 template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
@@ -60,20 +58,13 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
     T z0 = bias;
 #pragma unroll
     for (int k = 0; k < kFirstDmax; ++k) z0 += w[k] * xs[p][k];   // k >= D: both factors are zero
-    if (a.act == 0) {
-      t[p] = tanh_of(z0);
-      d1[p] = T(1) - t[p] * t[p];
-    } else {
-      t[p] = z0;
-      d1[p] = T(1);
-    }
+    act_eval<T>(a.act, z0, t[p], d1[p]);
   }
 
   const long ld = a.ld1;
   const int rho = a.rho;
   T *o = a.out + (n0 * a.out_rows) * ld + j;
   const long pstep = (long)a.out_rows * ld;
-  const T tanh_on = a.act == 0 ? T(1) : T(0);
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
     if (p < np) o[p * pstep] = t[p];
@@ -91,13 +82,13 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 #pragma unroll
       for (int p = 0; p < kFirstPoints; ++p)
         if (p < np) {
-          const T d2 = T(-2) * t[p] * d1[p] * tanh_on;
-          const T dK = (K == 2) ? d2 : T(8) * t[p] * d1[p] * (T(2) - T(3) * t[p] * t[p]) * tanh_on;
+          const T d2 = act_d2<T>(a.act, t[p], d1[p]);
+          const T dK = (K == 2) ? d2 : act_d4<T>(a.act, t[p], d1[p]);
           o[p * pstep + rowK * ld] = dK * zK;
           if (!a.last) {
             o[p * pstep + row1 * ld] = d1[p] * z1;
             if (K == 4) {
-              const T d3 = d1[p] * (T(6) * t[p] * t[p] - T(2)) * tanh_on;
+              const T d3 = act_d3<T>(a.act, t[p], d1[p]);
               o[p * pstep + (row1 + 1) * ld] = d2 * z1s;
               o[p * pstep + (row1 + 2) * ld] = d3 * z1s * z1;
             }
@@ -117,8 +108,7 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 #pragma unroll
       for (int p = 0; p < kFirstPoints; ++p)
         if (p < np) {
-          const T d2 = T(-2) * t[p] * d1[p] * tanh_on;
-          const T d3 = d1[p] * (T(6) * t[p] * t[p] - T(2)) * tanh_on;
+          const T d2 = act_d2<T>(a.act, t[p], d1[p]), d3 = act_d3<T>(a.act, t[p], d1[p]);
           orow[p * pstep] = d1[p] * z1;
           orow[p * pstep + ld] = d2 * z1s;
           orow[p * pstep + 2 * ld] = d3 * z1c;
@@ -130,10 +120,8 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
     if (p < np) {
-      T dk;
-      if (a.order == 2) dk = T(-2) * t[p] * d1[p];
-      else dk = T(8) * t[p] * d1[p] * (T(2) - T(3) * t[p] * t[p]);
-      olast[p * pstep] = dk * tanh_on * mom;
+      const T dk = (a.order == 2) ? act_d2<T>(a.act, t[p], d1[p]) : act_d4<T>(a.act, t[p], d1[p]);
+      olast[p * pstep] = dk * mom;
     }
 }
 

@@ -1,9 +1,9 @@
 // The collapsed (or, for comparison, un-collapsed) Taylor-mode rule of the activation for one
 // (point, feature) pair: shared by the fp32/fp64 and the bf16-MFMA stacked-GEMM kernels.
 //
-//   order 2:  t = tanh z_0 ; d1 = 1 - t^2 ; d2 = -2 t d1                     (App. H)
+//   order 2:  t = phi(z_0) ; d1, d2, ... its derivatives (tanh: d1 = 1 - t^2, d2 = -2 t d1, App. H)
 //             h_0 = t ;  h_{1,r} = d1 z_{1,r} ;  h_2 = d1 z_2 + d2 * sum_r z_{1,r}^2      (Sec. 3.1, Eq. 6)
-//   order 4:  d3 = d1 (6 t^2 - 2) ; d4 = 8 t d1 (2 - 3 t^2)
+//   order 4:  (tanh: d3 = d1 (6 t^2 - 2) ; d4 = 8 t d1 (2 - 3 t^2))
 //             h_{1,r} = d1 z1 ; h_{2,r} = d2 z1^2 + d1 z2 ; h_{3,r} = d3 z1^3 + 3 d2 z1 z2 + d1 z3
 //             h_4 = d1 z_4 + sum_r [ d4 z1^4 + 6 d3 z1^2 z2 + 4 d2 z1 z3 + 3 d2 z2^2 ]     (App. A multiplicities)
 #pragma once
@@ -14,6 +14,33 @@ namespace ctm {
 
 __device__ __forceinline__ float act_tanh(float z) { return tanhf(z); }
 __device__ __forceinline__ double act_tanh(double z) { return tanh(z); }
+__device__ __forceinline__ void act_sincos(float z, float &s, float &c) { s = sinf(z); c = cosf(z); }
+__device__ __forceinline__ void act_sincos(double z, double &s, double &c) { s = sin(z); c = cos(z); }
+
+// Activation value t = phi(z) and first derivative d1; the higher derivatives follow from (t, d1):
+//   act 0, tanh:     d1 = 1 - t^2, d2 = -2 t d1, d3 = d1 (6 t^2 - 2), d4 = 8 t d1 (2 - 3 t^2)
+//   act 1, identity: d1 = 1, d2 = d3 = d4 = 0
+//   act 2, sin:      t = sin z, d1 = cos z, d2 = -t, d3 = -d1, d4 = t
+template <typename T> __device__ __forceinline__ void act_eval(int act, T z, T &t, T &d1) {
+  if (act == 0) {
+    t = act_tanh(z);
+    d1 = T(1) - t * t;
+  } else if (act == 2) {
+    act_sincos(z, t, d1);
+  } else {
+    t = z;
+    d1 = T(1);
+  }
+}
+template <typename T> __device__ __forceinline__ T act_d2(int act, T t, T d1) {
+  return act == 0 ? T(-2) * t * d1 : (act == 2 ? -t : T(0));
+}
+template <typename T> __device__ __forceinline__ T act_d3(int act, T t, T d1) {
+  return act == 0 ? d1 * (T(6) * t * t - T(2)) : (act == 2 ? -d1 : T(0));
+}
+template <typename T> __device__ __forceinline__ T act_d4(int act, T t, T d1) {
+  return act == 0 ? T(8) * t * d1 * (T(2) - T(3) * t * t) : (act == 2 ? t : T(0));
+}
 
 // c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows);
 // o: the pair's column in the output block (row pitch ostep elements).
@@ -21,16 +48,9 @@ template <typename T>
 __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, long ostep, const LayerArgs<T> &a) {
   const int R = a.R;
   const T z0 = c[0] + bias;
-  T t, d1, d2;
-  if (a.act == 0) {
-    t = act_tanh(z0);
-    d1 = T(1) - t * t;
-    d2 = T(-2) * t * d1;
-  } else {
-    t = z0;
-    d1 = T(1);
-    d2 = T(0);
-  }
+  T t, d1;
+  act_eval<T>(a.act, z0, t, d1);
+  const T d2 = act_d2<T>(a.act, t, d1);
   o[0] = t;
   if (a.standard) {
     // un-collapsed ("standard") Taylor mode, kept for comparison: every direction carries its own
@@ -47,8 +67,7 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
         }
       }
     } else {  // rows 1+4r .. 4+4r: orders 1..4 of direction r
-      const T d3 = a.act == 0 ? d1 * (T(6) * t * t - T(2)) : T(0);
-      const T d4 = a.act == 0 ? T(8) * t * d1 * (T(2) - T(3) * t * t) : T(0);
+      const T d3 = act_d3<T>(a.act, t, d1), d4 = act_d4<T>(a.act, t, d1);
       for (int r = 0; r < R; ++r) {
         const T *cr = c + (long)(1 + 4 * r) * CROW;
         const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW], z4 = cr[3 * CROW];
@@ -87,14 +106,7 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
     const T h2 = d1 * z2 + d2 * s;
     o[(a.last ? 1 : R + 1) * ostep] = h2;
   } else {
-    T d3, d4;
-    if (a.act == 0) {
-      d3 = d1 * (T(6) * t * t - T(2));
-      d4 = T(8) * t * d1 * (T(2) - T(3) * t * t);
-    } else {
-      d3 = T(0);
-      d4 = T(0);
-    }
+    const T d3 = act_d3<T>(a.act, t, d1), d4 = act_d4<T>(a.act, t, d1);
     T s = T(0);
     for (int r = 0; r < R; ++r) {
       const T *cr = c + (long)(1 + 3 * r) * CROW;
@@ -131,17 +143,9 @@ template <typename T>
 __device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, long zstep, T *o, long ostep, const LayerArgs<T> &a) {
   const int R = a.R;
   const T z0 = zs[0];
-  T d1, d2, d3;
-  if (a.act == 0) {
-    const T t = act_tanh(z0);
-    d1 = T(1) - t * t;
-    d2 = T(-2) * t * d1;
-    d3 = d1 * (T(6) * t * t - T(2));
-  } else {
-    d1 = T(1);
-    d2 = T(0);
-    d3 = T(0);
-  }
+  T t, d1;
+  act_eval<T>(a.act, z0, t, d1);
+  const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
   const T hb0 = c[0], hb2 = c[(long)(R + 1) * CROW];
   const T z2 = zs[(long)(R + 1) * zstep];
   T s = T(0), dot = T(0);

@@ -72,6 +72,7 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.ctm_create_mlp(2, None, fake, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -1
     assert L.ctm_create_mlp(2, dims, fake, None, 7, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -3
     assert L.ctm_create_mlp(2, dims, fake, None, B.CTM_F32, 9, None, ctypes.byref(out)) == -3
+    assert L.ctm_create_mlp(2, dims, fake, None, 4, B.CTM_ACT_SIN, None, ctypes.byref(out)) == -3
     assert L.ctm_create_mlp(1, dims, fake, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -2
     bad = (ctypes.c_int * 3)(5, 0, 1)
     assert L.ctm_create_mlp(2, bad, fake, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -2

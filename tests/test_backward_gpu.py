@@ -162,3 +162,24 @@ def test_autograd_wrapper_trains_a_small_pinn():
     print(f"  pinn loss {first:.4f} -> {last:.4f}", flush=True)
     assert last < 0.5 * first
     mlp.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_weight_gradients_sin_activation(dtype):
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import gradients as og
+    arrs = case((5, 24, 16, 1), 21, dtype, 9, 3, True)
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]], act=ctm.CTM_ACT_SIN)
+    rng = np.random.default_rng(2)
+    gu, gop = rng.standard_normal(21).astype(dtype), rng.standard_normal(21).astype(dtype)
+    u, op, tape = ctm.ctm_laplacian_fwd(mlp, t(arrs["x"]), t(arrs["V"]), 0.5)
+    gW, gb = ctm.ctm_laplacian_bwd(mlp, 21, 3, 0.5, tape, t(gu), t(gop))
+    torch.cuda.synchronize()
+    _, rW, rb = og.laplacian_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], arrs["V"], 0.5, gu.astype(np.float64), gop.astype(np.float64), act="sin")
+    tol = 1e-9 if dtype == np.float64 else 2e-4
+    for l in range(3):
+        assert rel(gW[l].double().cpu().numpy(), rW[l]) <= tol and rel(gb[l].double().cpu().numpy(), rb[l]) <= tol
+    mlp.close()
