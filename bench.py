@@ -184,6 +184,15 @@ def main():
     for _ in range(args.steps):
         step()
     ms, launches = ctm.ctm_profile_end()
+
+    # per-step times (the paper reports the minimum of 50 repetitions, Sec. 4): one event pair per step
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     rho = 1 + K * R if std else ctm.ctm_rows_per_point(K, R)
     if w.op == "biharmonic_exact":
         D = w.dims[0]
@@ -224,7 +233,8 @@ def main():
                                    "bytes_per_step": first_bytes, "ms_per_step": first_ms}
     out = {
         "metric": METRIC, "value": w.N / (ms_per_step * 1e-3), "unit": "evals/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_min": per_step[0], "ms_per_step_median": per_step[len(per_step) // 2], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.op}, tanh MLP {'-'.join(map(str, w.dims))}, N={w.N}, "
                                f"{w.directions} directions R={R}, {args.taylor} order-{K} Taylor mode, {rho} rows/point"

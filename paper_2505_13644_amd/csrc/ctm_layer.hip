@@ -1,15 +1,12 @@
 // Stacked GEMM of one MLP layer over the whole coefficient block, with the collapsed
 // Taylor-mode rule of the activation fused in as its epilogue (gfx950 MFMA).
 //
-// What one layer computes (Sec. 3.1, Eq. 6; App. D collapsed scheme; App. H for tanh):
-//   for every point n and every coefficient row c of the point:  z_c = W h_c  (+ b for c = 0)
-//   order 2:  t = tanh z_0 ; a = 1 - t^2 ; b2 = -2 t a
-//             h_0 = t ;  h_{1,r} = a z_{1,r} ;  h_2 = a z_2 + b2 * sum_r z_{1,r}^2
-//   order 4:  c3 = a (6 t^2 - 2) ; d4 = 8 t a (2 - 3 t^2)        (derivatives of tanh)
-//             h_{1,r} = a z1 ; h_{2,r} = b2 z1^2 + a z2 ; h_{3,r} = c3 z1^3 + 3 b2 z1 z2 + a z3
-//             h_4 = a z_4 + sum_r [ d4 z1^4 + 6 c3 z1^2 z2 + 4 b2 z1 z3 + 3 b2 z2^2 ]
-//   (multiplicities 1, 6, 4, 3, 1 of the order-4 Faa di Bruno formula, App. A), where z_2 / z_4
-//   and h_2 / h_4 are the coefficients already summed over the directions.
+// What one layer computes (Sec. 3.1, Eq. 6; App. D collapsed scheme):
+//   for every point n and every coefficient row c of the point:  z_c = W h_c  (+ b for c = 0),
+//   then the activation's Taylor rule on the rows of the point (ctm_rule.h), in which the
+//   highest-order row is the one already summed over the directions.
+// The same kernel runs the reverse pass: with cotangents as input rows and W transposed it
+// computes Hbar = Zbar W and applies the reverse of the order-2 rule as its epilogue.
 //
 // Layout.  The block is point-major: rows n*rho .. n*rho + rho - 1 belong to point n
 // (row 0: order 0; then the per-direction rows; last row: the collapsed one), each row
@@ -64,7 +61,7 @@ template <typename T, int MB> struct Tile {
   static constexpr int BN = 64 * NB;
   static constexpr int PADE = 16 / sizeof(T);     // 16 bytes of padding per LDS row
   static constexpr int LROW = BK + PADE;          // LDS row pitch of a stage, elements
-  static constexpr int UPR = BK / KV;             // 16-byte units per stage row (= 8)
+  static constexpr int UPR = BK / KV;             // 16-byte units per stage row (= 4)
   static constexpr int A_STAGE = BM * LROW;
   static constexpr int B_STAGE = BN * LROW;
   static constexpr int A_LD = (BM * UPR + kThreads - 1) / kThreads;
