@@ -217,7 +217,8 @@ int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, l
 /*
  * Host-side description of how an order-K, R-direction call is tiled: points per tile,
  * 16-row MFMA blocks per tile, directions in the first (largest) pass and number of
- * passes.  Pure host logic (no GPU needed); any output pointer may be NULL.
+ * passes, for a batch large enough to fill the GPU (small batches may get shorter tiles).
+ * Pure host logic (no GPU needed); any output pointer may be NULL.
  */
 int ctm_tile_plan(ctm_dtype dtype, int K, int R, int *points_per_tile, int *row_blocks,
                   int *dirs_per_pass, int *n_passes);

@@ -68,8 +68,11 @@ int max_dirs_per_pass(int K, bool standard = false) {
   return standard ? (16 * kMaxRowBlocks - 1) / K : (16 * kMaxRowBlocks - 2) / (K - 1);
 }
 
-// Pick the row-block count that wastes the fewest MFMA rows (ties: the taller tile).
-PassPlan plan_pass(int K, int R, bool standard = false) {
+// Pick the row-block count that wastes the fewest MFMA rows (ties: the taller tile).  When that tile
+// shape leaves the GPU under-filled (fewer tiles than resident workgroup slots: small batches), fall
+// back to the shortest tile whose row efficiency is within 7 % of the best and that fills the slots,
+// or to the shortest such tile if none does.  tiles_per_point_block = column tiles of the narrowest layer.
+PassPlan plan_pass(int K, int R, bool standard = false, long N = -1, int col_tiles = 1, int slots = 512) {
   PassPlan best{R, (int)rows_per_point(K, R, standard), 0, 0};
   double best_eff = -1.0;
   static const int kChoices[] = {4, 8, 9, 12, 13, 16};
@@ -83,7 +86,28 @@ PassPlan plan_pass(int K, int R, bool standard = false) {
       if (eff > best_eff) best_eff = eff;
     }
   }
-  return best;
+  if (N < 0) return best;
+  auto tiles_of = [&](int P) { return ((N + P - 1) / P) * (long)col_tiles; };
+  if (tiles_of(best.P) >= slots) return best;
+  PassPlan small = best;
+  bool have = false;
+  for (int MB : kChoices) {
+    const int P = 16 * MB / best.rho;
+    if (P < 1 || MB >= best.MB) continue;
+    const double eff = (double)P * best.rho / (16.0 * MB);
+    if (eff < best_eff - 0.07) continue;
+    if (!have) {  // shortest admissible tile
+      small.MB = MB;
+      small.P = P;
+      have = true;
+      if (tiles_of(P) < slots) return small;  // even the shortest does not fill the slots: take it
+    }
+    if (tiles_of(P) >= slots) {  // keep growing while the slots stay filled
+      small.MB = MB;
+      small.P = P;
+    }
+  }
+  return small;
 }
 
 // ---- interpolation coefficients gamma_{i,j} (App. E, Eq. "ttc_coeff"), exact rational arithmetic
@@ -159,6 +183,8 @@ struct ctm_mlp {
   void *arena = nullptr;
   std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: padded vector and scalar bias
   std::vector<void *> Whi, Wlo;  // bf16 variants: split weights of the hidden layers
+  int slots = 512;               // resident workgroups of the layer kernel: 2 per compute unit
+  int min_col_tiles = 1;         // fewest column tiles among the hidden layers
   std::vector<void *> WT;        // l = 1..L-2: W_l transposed, [pad(dims[l])][ld(dims[l+1])], for the reverse pass
 };
 
@@ -196,7 +222,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
   if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
   for (int pass = 0; pass < sp.n_passes; ++pass) {
     const int Rp = (pass == sp.n_passes - 1) ? sp.lastR : sp.first;
-    const PassPlan pl = plan_pass(K, Rp, standard);
+    const PassPlan pl = plan_pass(K, Rp, standard, N, m->min_col_tiles, m->slots);
     const int last_rows = standard ? 1 + Rp : 2;
     const bool fast_first = first_layer_fast_path(m->dims[0], sn);
     const T *in = buf[1];
@@ -382,7 +408,7 @@ template <typename T>
 int run_fwd_tape(const ctm_mlp *m, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
                  hipStream_t st) {
   const TapeLayout tl = tape_layout(m, N, R);
-  const PassPlan pl = plan_pass(2, R);
+  const PassPlan pl = plan_pass(2, R, false, N, m->min_col_tiles, m->slots);
   const int L = m->L;
   char *tp = (char *)tape;
   SeedArgs<T> sa;
@@ -424,7 +450,7 @@ int run_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, con
             void *const *gb, void *ws, hipStream_t st) {
   const TapeLayout tl = tape_layout(m, N, R);
   const BwdLayout bl = bwd_layout(m, N, R);
-  const PassPlan pl = plan_pass(2, R);
+  const PassPlan pl = plan_pass(2, R, false, N, m->min_col_tiles, m->slots);
   const int L = m->L;
   const long M = N * pl.rho;
   const char *tp = (const char *)tape;
@@ -586,6 +612,10 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   }
   hipError_t e = hipGetDevice(&m->device);
   if (e != hipSuccess) { delete m; return fail_hip(e, "ctm_create_mlp: hipGetDevice"); }
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device) == hipSuccess && cus > 0) m->slots = 2 * cus;
+  m->min_col_tiles = m->col_tiles[0];
+  for (int ct : m->col_tiles) m->min_col_tiles = ct < m->min_col_tiles ? ct : m->min_col_tiles;
   e = hipMalloc(&m->arena, total);
   if (e != hipSuccess) {
     delete m;
