@@ -7,12 +7,17 @@
  *
  *     op[n] = scale * sum_{r=1..R} < d^K f(x_n), v_r^{(x)K} >        (Sec. 3.1, Eq. 5)
  *
+ * one value per network output: for a network with C = d_L outputs u and op are [N, C]
+ * and the operator acts on every output component (Sec. 3.2, Eq. 7), sharing the whole
+ * propagation up to the last linear layer.  Wherever u, op (and gu, gop) are described as
+ * [N] below, read [N, C] row-major for C > 1.
+ *
  * for K = 2 (Laplacians, Sec. 3.2) or K = 4 (randomized biharmonic, Sec. 3.3).
  * The sum over r is taken inside the propagation ("collapsed", Sec. 3.1, Eq. 6):
  * every layer carries 1 + (K-1)R + 1 coefficient rows per point instead of 1 + K*R.
  *
- * The network is  f(x) = W_L act( ... act(W_1 x + b_1) ... ) + b_L  with a scalar
- * output (d_L = 1), the activation after every layer but the last, and biases that
+ * The network is  f(x) = W_L act( ... act(W_1 x + b_1) ... ) + b_L  with C = d_L >= 1
+ * outputs (1 in the paper's experiments), the activation after every layer but the last, and biases that
  * enter the 0-th coefficient only (App. H).  Coefficients are derivative-normalised
  * (Sec. 2: x(t) = sum_k t^k/k! x_k), so op is the K-th coefficient itself.
  *
@@ -73,8 +78,8 @@ typedef enum {
 
 /*
  * Build a handle for an MLP with n_layers linear layers (n_layers >= 2, i.e. at least one
- * hidden layer) of widths dims[0] = D, ..., dims[n_layers] = 1   (Sec. 4 setup; App. H model).
- *   dims  host, n_layers + 1 ints, all >= 1, dims[n_layers] must be 1
+ * hidden layer) of widths dims[0] = D, ..., dims[n_layers] = C   (Sec. 4 setup; App. H model).
+ *   dims  host, n_layers + 1 ints, all >= 1; dims[n_layers] = C, the number of outputs, at most 1024
  *   W     host array of n_layers dev pointers; W[l] is [dims[l+1], dims[l]] row-major
  *   b     host array of n_layers dev pointers to [dims[l+1]]; the array or any entry may
  *         be NULL, meaning a zero bias

@@ -1,7 +1,7 @@
 """fp64 CPU oracle for parameter gradients of Laplacian-type losses.  TEST INFRASTRUCTURE ONLY.
 
-For  L = sum_n [ gu_n * u(x_n) + gop_n * op(x_n) ],  op(x_n) = scale * sum_r v_r^T H(x_n) v_r  (Sec. 3.2, Eq. 7-8),
-it returns dL/dW_l and dL/db_l.  The operator is written from its definition with nested first-order
+For  L = sum_{n,c} [ gu_{n,c} * u_c(x_n) + gop_{n,c} * op_c(x_n) ],  op_c(x_n) = scale * sum_r v_r^T H_c(x_n) v_r
+(Sec. 3.2, Eq. 7-8; H_c the Hessian of output c), it returns dL/dW_l and dL/db_l.  The operator is written from its definition with nested first-order
 automatic differentiation (PyTorch CPU, fp64): the Hessian of the scalar network by forward-over-reverse,
 contracted with the directions, then one reverse sweep to the parameters.  No Taylor-mode rule and no code of
 the HIP path is involved.  The paper calls evaluating the operator so that it can be differentiated again the
@@ -20,16 +20,19 @@ def _mlp(params, x, act):
         h = h @ W.T + b
         if l < len(Ws) - 1:
             h = torch.tanh(h) if act == "tanh" else (torch.sin(h) if act == "sin" else h)
-    return h[..., 0]
+    return h  # [..., C]
 
 
 def laplacian_loss_grads(Ws, bs, x, V, scale, gu, gop, act="tanh"):
-    """Returns (L, [dL/dW_l], [dL/db_l]) as fp64 numpy.  V: None (standard basis), [R, D] or [N, R, D]."""
+    """Returns (L, [dL/dW_l], [dL/db_l]) as fp64 numpy.  V: None (standard basis), [R, D] or [N, R, D];
+    gu, gop: [N] for a scalar-output network, [N, C] otherwise."""
     t = lambda a: torch.as_tensor(np.asarray(a, dtype=np.float64))
     Ws_t = [t(W).requires_grad_(True) for W in Ws]
     bs_t = [t(b).requires_grad_(True) for b in bs]
     xt, gut, gopt = t(x), t(gu), t(gop)
     N, D = xt.shape
+    C = Ws_t[-1].shape[0]
+    gut, gopt = gut.reshape(N, C), gopt.reshape(N, C)
     if V is None:
         Vt = torch.eye(D, dtype=torch.float64).expand(N, D, D)
     else:
@@ -38,10 +41,10 @@ def laplacian_loss_grads(Ws, bs, x, V, scale, gu, gop, act="tanh"):
             Vt = Vt.expand(N, *Vt.shape)
 
     def loss(params):
-        f = lambda p: _mlp(params, p, act)                       # scalar function of one point
-        H = torch.func.vmap(torch.func.hessian(f))(xt)            # [N, D, D]
+        f = lambda p: _mlp(params, p, act)                       # the C outputs at one point
+        H = torch.func.vmap(torch.func.hessian(f))(xt)            # [N, C, D, D]
         u = _mlp(params, xt, act)
-        op = scale * torch.einsum("nrd,nde,nre->n", Vt, H, Vt)
+        op = scale * torch.einsum("nrd,ncde,nre->nc", Vt, H, Vt)
         return (gut * u + gopt * op).sum()
 
     L = loss((Ws_t, bs_t))

@@ -206,6 +206,26 @@ def biharmonic_exact(Ws, bs, x, act="tanh", fn=None):
     return out
 
 
+def per_output(fn, Ws, bs, *args, **kwargs):
+    """Apply a scalar-output operator `fn(Ws, bs, ...)` to every output of a C-output network.
+
+    The operators act on each output component on its own (Sec. 3.2, Eq. 7: the Laplacian of a
+    vector-valued function stacks the Hessian traces of its elements), so output c is the operator
+    of the scalar network whose last layer is row c of W_L and entry c of b_L.
+    Arrays come back with a trailing axis of length C.
+    """
+    C = np.asarray(Ws[-1]).shape[0]
+    cols = []
+    for c in range(C):
+        Wc = list(Ws[:-1]) + [np.asarray(Ws[-1])[c:c + 1]]
+        last_b = None if bs is None or bs[-1] is None else np.asarray(bs[-1])[c:c + 1]
+        bc = None if bs is None else list(bs[:-1]) + [last_b]
+        cols.append(fn(Wc, bc, *args, **kwargs))
+    if isinstance(cols[0], tuple):
+        return tuple(np.stack([col[i] for col in cols], axis=-1) for i in range(len(cols[0])))
+    return np.stack(cols, axis=-1)
+
+
 def scaled_max_err(got, ref):
     """max_n |got_n - ref_n| / max_n |ref_n| : the pass/fail error metric."""
     got = np.asarray(got, dtype=np.float64)

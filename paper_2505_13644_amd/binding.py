@@ -223,16 +223,29 @@ def _check_shapes(mlp, x, V, what="V"):
         raise ValueError(f"{what} has shape {tuple(V.shape)}, expected [R, {x.shape[1]}] or [{x.shape[0]}, R, {x.shape[1]}]")
 
 
+def _out_shape(mlp, N):
+    """[N] for a scalar-output network, [N, C] for C > 1 outputs."""
+    C = mlp.dims[-1]
+    return (N,) if C == 1 else (N, C)
+
+
+def _out_pair(mlp, x, u, op):
+    torch = _torch()
+    shape = _out_shape(mlp, x.shape[0])
+    for name, t in (("u", u), ("op", op)):
+        if t is not None and tuple(t.shape) != shape:
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {list(shape)}")
+    if u is None:
+        u = torch.empty(shape, dtype=mlp.dtype, device=x.device)
+    if op is None:
+        op = torch.empty(shape, dtype=mlp.dtype, device=x.device)
+    return u, op
+
+
 def _outputs(mlp, x, K, R, u, op, workspace):
     torch = _torch()
     N = x.shape[0]
-    for name, t in (("u", u), ("op", op)):
-        if t is not None and tuple(t.shape) != (N,):
-            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected [{N}]")
-    if u is None:
-        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
-    if op is None:
-        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    u, op = _out_pair(mlp, x, u, op)
     need = ctm_workspace_bytes(mlp, K, N, R)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
@@ -296,10 +309,7 @@ def ctm_biharmonic_exact(mlp: Mlp, x, u=None, op=None, workspace=None):
     need = lib().ctm_biharmonic_exact_workspace_bytes(mlp.handle, N)
     if need == 0:
         raise CtmError(-2, ctm_last_error())
-    if u is None:
-        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
-    if op is None:
-        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    u, op = _out_pair(mlp, x, u, op)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     _check(lib().ctm_biharmonic_exact(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(u, mlp.dtype, "u"),
@@ -327,10 +337,7 @@ def ctm_weighted_laplacian_rand(mlp: Mlp, x, sigma, V=None, u=None, op=None, wor
     need = lib().ctm_weighted_laplacian_rand_workspace_bytes(mlp.handle, N, K, S, s_stride, v_stride)
     if need == 0:
         raise CtmError(-2, ctm_last_error())
-    if u is None:
-        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
-    if op is None:
-        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    u, op = _out_pair(mlp, x, u, op)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     _check(lib().ctm_weighted_laplacian_rand(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(sigma, mlp.dtype, "sigma"), K,
@@ -354,10 +361,7 @@ def ctm_taylor_standard(mlp: Mlp, K, x, V=None, scale=1.0, u=None, op=None, work
     need = lib().ctm_workspace_bytes_standard(mlp.handle, K, N, R)
     if need == 0:
         raise CtmError(-2, ctm_last_error())
-    if u is None:
-        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
-    if op is None:
-        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    u, op = _out_pair(mlp, x, u, op)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     _check(lib().ctm_taylor_standard(mlp.handle, K, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(V, mlp.dtype, "V"), R, stride,
@@ -396,10 +400,7 @@ def ctm_laplacian_fwd(mlp: Mlp, x, V=None, scale=1.0, u=None, op=None, tape=None
     _check_shapes(mlp, x, V)
     N = x.shape[0]
     R, stride = _dirs_of(x, V)
-    if u is None:
-        u = torch.empty(N, dtype=mlp.dtype, device=x.device)
-    if op is None:
-        op = torch.empty(N, dtype=mlp.dtype, device=x.device)
+    u, op = _out_pair(mlp, x, u, op)
     if tape is None:
         tape = torch.empty(ctm_tape_bytes(mlp, N, R), dtype=torch.uint8, device=x.device)
     _check(lib().ctm_laplacian_fwd(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(V, mlp.dtype, "V"), R, stride, float(scale),
@@ -424,8 +425,8 @@ def ctm_laplacian_bwd(mlp: Mlp, N, R, scale, tape, gu, gop, gW=None, gb=None, wo
         if gb[l] is not None and tuple(gb[l].shape) != (mlp.dims[l + 1],):
             raise ValueError(f"gb[{l}] has shape {tuple(gb[l].shape)}")
     for name, t in (("gu", gu), ("gop", gop)):
-        if t is not None and tuple(t.shape) != (N,):
-            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected [{N}]")
+        if t is not None and tuple(t.shape) != _out_shape(mlp, N):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {list(_out_shape(mlp, N))}")
     if workspace is None:
         workspace = torch.empty(ctm_backward_workspace_bytes(mlp, N, R), dtype=torch.uint8, device=dev)
     c_gW = (c_void_p * L)(*[_dev_ptr(g, mlp.dtype, f"gW[{l}]") for l, g in enumerate(gW)])

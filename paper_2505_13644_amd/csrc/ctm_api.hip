@@ -181,7 +181,7 @@ struct ctm_mlp {
   ctm_act act = CTM_ACT_TANH;
   int device = 0;
   void *arena = nullptr;
-  std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: padded vector and scalar bias
+  std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: [dims[L]][ld] and [dims[L]]
   std::vector<void *> Whi, Wlo;  // bf16 variants: split weights of the hidden layers
   int slots = 512;               // resident workgroups of the layer kernel: 2 per compute unit
   int min_col_tiles = 1;         // fewest column tiles among the hidden layers
@@ -279,7 +279,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
     }
     FinalArgs<T> fa;
     fa.pair = pair; fa.nk = standard ? Rp : 1; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
-    fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = (pass > 0 || accumulate_first) ? 1 : 0;
+    fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.C = m->dims[L]; fa.scale = scale; fa.accumulate = (pass > 0 || accumulate_first) ? 1 : 0;
     e = launch_final<T>(fa, st);
     if (e != hipSuccess) return fail_hip(e, "final kernel launch");
     (void)prof_mark(st, 2);
@@ -319,7 +319,7 @@ int run_operator(const ctm_mlp *m, int K, const void *x, long N, const void *V, 
 template <typename T> hipError_t pack_all(ctm_mlp *m, const void *const *W, const void *const *b, hipStream_t st) {
   for (int l = 0; l < m->L; ++l) {
     const bool lastl = (l == m->L - 1);
-    const int rows_pad = lastl ? 1 : m->col_tiles[l] * tile_cols<T>();
+    const int rows_pad = lastl ? m->dims[m->L] : m->col_tiles[l] * tile_cols<T>();
     const T *bl = (b && b[l]) ? (const T *)b[l] : nullptr;
     hipError_t e = launch_pack<T>((const T *)W[l], bl, m->dims[l + 1], m->dims[l], (T *)m->Wp[l], (T *)m->bp[l],
                                   rows_pad, m->ld[l], st);
@@ -386,7 +386,7 @@ BwdLayout bwd_layout(const ctm_mlp *m, long N, int R) {
   BwdLayout b;
   b.block_bytes = round256((size_t)M * maxld * es);
   b.scratch = 2 * b.block_bytes;
-  b.partials = b.scratch + round256((size_t)(66 * maxld + 64) * es);
+  b.partials = b.scratch + round256(((size_t)(65 + m->dims[m->L]) * maxld + m->dims[m->L] + 64) * es);
   b.total = b.partials + round256(maxpart * es);
   return b;
 }
@@ -438,7 +438,7 @@ int run_fwd_tape(const ctm_mlp *m, const T *x, long N, const T *V, int R, long s
   }
   FinalArgs<T> fa;
   fa.pair = pair; fa.nk = 1; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
-  fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.scale = scale; fa.accumulate = 0;
+  fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.C = m->dims[L]; fa.scale = scale; fa.accumulate = 0;
   e = launch_final<T>(fa, st);
   if (e != hipSuccess) return fail_hip(e, "final kernel launch");
   (void)prof_mark(st, 2);
@@ -459,18 +459,19 @@ int run_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, con
   T *partials = (T *)((char *)ws + bl.partials);
   int maxld = 0;
   for (int i = 0; i + 1 < L; ++i) maxld = m->ld[i + 1] > maxld ? m->ld[i + 1] : maxld;
-  T *dummy = scratch + 65 * (size_t)maxld;  // maxld + 64 spare elements for gradients the caller does not want
+  const int C = m->dims[L];
+  T *dummy = scratch + 65 * (size_t)maxld;  // C * (maxld + 1) + 64 spare elements for gradients the caller does not want
   if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
 
   int cur = 0;
   BwdLastArgs<T> ba;
   ba.Z = (const T *)(tp + tl.z[L - 2]); ba.w = (const T *)m->Wp[L - 1]; ba.gu = gu; ba.gop = gop; ba.Zbar = zb[cur];
-  ba.N = N; ba.ld = m->ld[L - 1]; ba.rho = pl.rho; ba.R = R; ba.act = (int)m->act; ba.scale = scale;
+  ba.N = N; ba.ld = m->ld[L - 1]; ba.rho = pl.rho; ba.R = R; ba.act = (int)m->act; ba.scale = scale; ba.C = m->dims[L];
   hipError_t e = launch_bwd_last<T>(ba, st);
   if (e != hipSuccess) return fail_hip(e, "reverse last-layer kernel launch");
   T *gw_last = (gW && gW[L - 1]) ? (T *)gW[L - 1] : dummy;
-  T *gb_last = (gb && gb[L - 1]) ? (T *)gb[L - 1] : dummy + maxld;
-  e = launch_last_grads<T>((const T *)(tp + tl.pair), gu, gop, scale, N, m->ld[L - 1], m->dims[L - 1], gw_last, gb_last, scratch, st);
+  T *gb_last = (gb && gb[L - 1]) ? (T *)gb[L - 1] : dummy + (size_t)C * maxld;
+  e = launch_last_grads<T>((const T *)(tp + tl.pair), gu, gop, scale, N, m->ld[L - 1], m->dims[L - 1], C, gw_last, gb_last, scratch, st);
   if (e != hipSuccess) return fail_hip(e, "last-layer gradient kernel launch");
   (void)prof_mark(st, 0);
 
@@ -572,7 +573,8 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
     return fail(CTM_ERR_SHAPE, "ctm_create_mlp: n_layers = %d, need 2..64 (at least one hidden layer)", n_layers);
   for (int l = 0; l <= n_layers; ++l)
     if (dims[l] < 1 || dims[l] > (1 << 20)) return fail(CTM_ERR_SHAPE, "ctm_create_mlp: dims[%d] = %d out of range", l, dims[l]);
-  if (dims[n_layers] != 1) return fail(CTM_ERR_UNSUPPORTED, "ctm_create_mlp: output width %d, only scalar outputs are built", dims[n_layers]);
+  if (dims[n_layers] > kMaxOutputs)
+    return fail(CTM_ERR_UNSUPPORTED, "ctm_create_mlp: %d outputs, at most %d are built", dims[n_layers], kMaxOutputs);
   const size_t es = elem_size(dtype);
   for (int l = 0; l < n_layers; ++l) {
     if (!W[l]) return fail(CTM_ERR_NULL, "ctm_create_mlp: W[%d] is NULL", l);
@@ -594,7 +596,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
     const bool lastl = (l == n_layers - 1);
     const int ct = lastl ? 0 : (dims[l + 1] + bn - 1) / bn;
     if (!lastl) m->col_tiles.push_back(ct);
-    const size_t rows_pad = lastl ? 1 : (size_t)ct * bn;
+    const size_t rows_pad = lastl ? (size_t)dims[n_layers] : (size_t)ct * bn;
     woff[l] = total;
     total += round256(rows_pad * m->ld[l] * es);
     boff[l] = total;

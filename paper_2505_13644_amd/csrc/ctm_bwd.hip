@@ -5,6 +5,7 @@
 // layer, Z = H_prev W^T (+ bias on the order-0 rows) followed by the rule (ctm_rule.h):
 //   cotangents at the last hidden layer:  hb_0 = gu w,  hb_{1,r} = 0,  hb_2 = scale gop w      -> bwd_last_kernel
 //   dL/dw = sum_n gu_n h_0(n) + scale gop_n h_2(n),  dL/db_last = sum_n gu_n                  -> last_grads
+//   (a network with C outputs has one (u, op) pair, one row of w and one bias per output; the cotangents sum over them)
 //   per hidden layer:  dL/db = sum_n Zbar[order-0 row of n]                                    -> bias_grad
 //                      dL/dW = Zbar^T H_prev   (a GEMM whose k index runs over all N*rho rows)  -> wgrad_kernel
 //                      Hbar_prev = Zbar W, then the reverse rule                                -> layer_kernel (bwd)
@@ -24,9 +25,12 @@ template <typename T> __global__ void bwd_last_kernel(const BwdLastArgs<T> a) {
     const long n = i / a.ld;
     const T *zs = a.Z + (n * rho) * step + j;
     T *o = a.Zbar + (n * rho) * step + j;
-    const T w = a.w[j];
-    const T hb0 = (a.gu ? a.gu[n] : T(0)) * w;
-    const T hb2 = (T)(a.scale * (double)(a.gop ? a.gop[n] : T(0))) * w;
+    T hb0 = T(0), hb2 = T(0);
+    for (int c = 0; c < a.C; ++c) {
+      const T w = a.w[(long)c * a.ld + j];
+      if (a.gu) hb0 += a.gu[n * a.C + c] * w;
+      if (a.gop) hb2 += (T)(a.scale * (double)a.gop[n * a.C + c]) * w;
+    }
     T t, d1;
     act_eval<T>(a.act, zs[0], t, d1);
     const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
@@ -55,10 +59,10 @@ constexpr int kSumChunks = 64;
 
 // stage 1: partial[c][j] = sum over the rows n of chunk c of
 //   weighted == 0:  X[n*row_stride + j]
-//   weighted == 1:  ca[n] * X[n*row_stride + j] + sb * cb[n] * X[n*row_stride + second + j]   (a NULL vector counts as zeros)
+//   weighted == 1:  ca[n*cs] * X[n*row_stride + j] + sb * cb[n*cs] * X[n*row_stride + second + j]   (a NULL vector counts as zeros)
 template <typename T>
-__global__ void colsum_stage1(const T *X, long row_stride, long second, int weighted, const T *ca, const T *cb, double sb, long N,
-                              int ld, T *partial) {
+__global__ void colsum_stage1(const T *X, long row_stride, long second, int weighted, const T *ca, const T *cb, long cs, double sb,
+                              long N, int ld, T *partial) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int c = blockIdx.y;
   if (j >= ld) return;
@@ -68,15 +72,15 @@ __global__ void colsum_stage1(const T *X, long row_stride, long second, int weig
   for (long n = n0; n < n1; ++n) {
     const T *row = X + n * row_stride + j;
     T v = row[0];
-    if (weighted) v = (ca ? ca[n] : T(0)) * row[0] + (T)(sb * (double)(cb ? cb[n] : T(0))) * row[second];
+    if (weighted) v = (ca ? ca[n * cs] : T(0)) * row[0] + (T)(sb * (double)(cb ? cb[n * cs] : T(0))) * row[second];
     acc += v;
   }
   partial[(long)c * ld + j] = acc;
 }
 
-// stage 2: out[j] = sum_c partial[c][j], j < d.  Block 0 / thread 0 also folds `extra` (sum of an N-vector) if asked.
+// stage 2: out[j] = sum_c partial[c][j], j < d.  Block 0 also sums vec[n*vs], n < N, into vec_sum[0] if asked.
 template <typename T>
-__global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *vec, long N, T *vec_sum) {
+__global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *vec, long vs, long N, T *vec_sum) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j < d) {
     T acc = T(0);
@@ -88,7 +92,7 @@ __global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *
     __shared__ T red[256];
     T acc = T(0);
     if (vec != nullptr)
-      for (long n = threadIdx.x; n < N; n += blockDim.x) acc += vec[n];
+      for (long n = threadIdx.x; n < N; n += blockDim.x) acc += vec[n * vs];
     red[threadIdx.x] = acc;
     __syncthreads();
     for (int off = 128; off >= 1; off >>= 1) {
@@ -100,28 +104,34 @@ __global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *
 }
 
 template <typename T>
-hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, T *gw, T *gbias,
+hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, int C, T *gw, T *gbias,
                              T *scratch, hipStream_t s) {
-  // the order-0 row weighted by gu plus the collapsed row weighted by scale * gop
-  hipLaunchKernelGGL(colsum_stage1<T>, dim3((ld + 255) / 256, kSumChunks), dim3(256), 0, s, pair, (long)2 * ld, (long)ld, 1, gu, gop,
-                     scale, N, ld, scratch);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gw, gu, N, gbias);
-  return hipGetLastError();
+  // per output: the order-0 row weighted by gu[:, c] plus the collapsed row weighted by scale * gop[:, c]
+  for (int c = 0; c < C; ++c) {
+    const T *guc = gu ? gu + c : nullptr, *gopc = gop ? gop + c : nullptr;
+    hipLaunchKernelGGL(colsum_stage1<T>, dim3((ld + 255) / 256, kSumChunks), dim3(256), 0, s, pair, (long)2 * ld, (long)ld, 1, guc,
+                       gopc, (long)C, scale, N, ld, scratch);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gw + (long)c * d, guc, (long)C, N,
+                       gbias + c);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
-template hipError_t launch_last_grads<float>(const float *, const float *, const float *, double, long, int, int, float *, float *,
-                                             float *, hipStream_t);
-template hipError_t launch_last_grads<double>(const double *, const double *, const double *, double, long, int, int, double *,
+template hipError_t launch_last_grads<float>(const float *, const float *, const float *, double, long, int, int, int, float *,
+                                             float *, float *, hipStream_t);
+template hipError_t launch_last_grads<double>(const double *, const double *, const double *, double, long, int, int, int, double *,
                                               double *, double *, hipStream_t);
 
 template <typename T>
 hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s) {
   hipLaunchKernelGGL(colsum_stage1<T>, dim3((ld + 255) / 256, kSumChunks), dim3(256), 0, s, Zbar, (long)rho * ld, (long)0, 0,
-                     (const T *)nullptr, (const T *)nullptr, 0.0, N, ld, scratch);
+                     (const T *)nullptr, (const T *)nullptr, (long)1, 0.0, N, ld, scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gb, (const T *)nullptr, (long)0,
+  hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gb, (const T *)nullptr, (long)1, (long)0,
                      (T *)nullptr);
   return hipGetLastError();
 }

@@ -89,6 +89,7 @@ template <typename T> struct FirstArgs {
   int standard;   // un-collapsed row layout
   int out_rows;   // rows per point in out
 };
+constexpr int kMaxOutputs = 1024;  // widest last layer (outputs are produced by a per-point dot-product kernel)
 bool first_layer_fast_path(int D, long v_point_stride);
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s);
 
@@ -101,19 +102,21 @@ hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp
 // ---- reverse pass (order 2, collapsed) -----------------------------------------------------
 template <typename T> struct BwdLastArgs {
   const T *Z;     // recorded pre-activations of the last hidden layer [N * rho][ld]
-  const T *w;     // last-layer weights [ld]
-  const T *gu;    // dL/du [N] or nullptr
-  const T *gop;   // dL/dop [N] or nullptr
+  const T *w;     // last-layer weights [C][ld]
+  const T *gu;    // dL/du [N][C] or nullptr
+  const T *gop;   // dL/dop [N][C] or nullptr
   T *Zbar;        // out: cotangents of those pre-activations [N * rho][ld]
   long N;
   int ld, rho, R, act;
+  int C;          // network outputs
   double scale;
 };
 template <typename T> hipError_t launch_bwd_last(const BwdLastArgs<T> &a, hipStream_t s);
 
-// gw[j] = sum_n gu[n] pair[n][0][j] + scale gop[n] pair[n][1][j] (j < d), gbias[0] = sum_n gu[n]; scratch >= 65 * ld elements
+// For every output c < C: gw[c][j] = sum_n gu[n][c] pair[n][0][j] + scale gop[n][c] pair[n][1][j] (j < d, gw row pitch d),
+// gbias[c] = sum_n gu[n][c]; scratch >= 65 * ld elements (reused output after output, in stream order)
 template <typename T>
-hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, T *gw, T *gbias,
+hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, int C, T *gw, T *gbias,
                              T *scratch, hipStream_t s);
 // gb[j] = sum_n Zbar[n * rho][j] (j < d); scratch >= 64 * ld elements
 template <typename T>
@@ -137,12 +140,13 @@ hipError_t launch_sigma_dirs(const T *sigma, long sig_stride, const T *V, long v
 template <typename T> struct FinalArgs {
   const T *pair;  // [N][1 + nk][ld] : h_0 and the nk highest-order rows of the last hidden layer
   int nk;         // 1 (collapsed) or R (un-collapsed: summed here)
-  const T *w;     // [ld] zero-padded last-layer weights
-  const T *b;     // [1]
-  T *u;           // may be nullptr
-  T *op;          // may be nullptr
+  const T *w;     // [C][ld] zero-padded last-layer weights
+  const T *b;     // [C]
+  T *u;           // [N][C], may be nullptr
+  T *op;          // [N][C], may be nullptr
   long N;
   int ld;
+  int C;          // network outputs
   double scale;
   int accumulate;  // 0: write u and op; 1: op += (later passes over a split direction set)
 };

@@ -138,34 +138,50 @@ template hipError_t launch_sigma_dirs<float>(const float *, long, const float *,
 template hipError_t launch_sigma_dirs<double>(const double *, long, const double *, long, double *, long, int, int, int, hipStream_t);
 
 // ---- last layer (App. H: g is linear, bias on the 0-th coefficient only) ------------------
-//   u_n = w . h_0(n) + b        op_n = scale * (w . h_K(n))
-// One wavefront per point; lanes stride the features and the 64 partial sums are folded
-// with a fixed butterfly, so the result does not depend on scheduling.
+//   u_{n,c} = w_c . h_0(n) + b_c        op_{n,c} = scale * (w_c . h_K(n))       (Sec. 3.2: one operator value per output)
+// One wavefront per point; lanes stride the features, outputs are taken four at a time, and the 64
+// partial sums are folded with a fixed butterfly, so the result does not depend on scheduling.
 template <typename T> __global__ __launch_bounds__(256) void final_kernel(const FinalArgs<T> a) {
   const int lane = threadIdx.x & 63;
   const long n = blockIdx.x * 4L + (threadIdx.x >> 6);
   if (n >= a.N) return;
   const T *h0 = a.pair + n * (1 + a.nk) * a.ld;
-  T s0 = T(0), sk = T(0);
-  for (int k = lane; k < a.ld; k += 64) {
-    const T w = a.w[k];
-    s0 += w * h0[k];
-    T hk = T(0);
-    for (int r = 1; r <= a.nk; ++r) hk += h0[(long)r * a.ld + k];  // nk > 1: the sum un-collapsed mode defers to the end
-    sk += w * hk;
-  }
+  for (int c0 = 0; c0 < a.C; c0 += 4) {
+    T s0[4] = {T(0), T(0), T(0), T(0)}, sk[4] = {T(0), T(0), T(0), T(0)};
+    for (int k = lane; k < a.ld; k += 64) {
+      const T v0 = h0[k];
+      T hk = T(0);
+      for (int r = 1; r <= a.nk; ++r) hk += h0[(long)r * a.ld + k];  // nk > 1: the sum un-collapsed mode defers to the end
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    s0 += __shfl_xor(s0, off, 64);
-    sk += __shfl_xor(sk, off, 64);
-  }
-  if (lane == 0) {
-    const T opv = (T)(a.scale * (double)sk);
-    if (a.accumulate) {
-      if (a.op) a.op[n] += opv;
-    } else {
-      if (a.u) a.u[n] = s0 + a.b[0];
-      if (a.op) a.op[n] = opv;
+      for (int i = 0; i < 4; ++i) {
+        const int c = (c0 + i < a.C) ? c0 + i : a.C - 1;  // clamped: surplus slots repeat the last output and are dropped
+        const T w = a.w[(long)c * a.ld + k];
+        s0[i] += w * v0;
+        sk[i] += w * hk;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        s0[i] += __shfl_xor(s0[i], off, 64);
+        sk[i] += __shfl_xor(sk[i], off, 64);
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = c0 + i;
+        if (c >= a.C) break;
+        const T opv = (T)(a.scale * (double)sk[i]);
+        const long o = n * a.C + c;
+        if (a.accumulate) {
+          if (a.op) a.op[o] += opv;
+        } else {
+          if (a.u) a.u[o] = s0[i] + a.b[c];
+          if (a.op) a.op[o] = opv;
+        }
+      }
     }
   }
 }

@@ -76,9 +76,9 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.ctm_create_mlp(1, dims, fake, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -2
     bad = (ctypes.c_int * 3)(5, 0, 1)
     assert L.ctm_create_mlp(2, bad, fake, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -2
-    wide = (ctypes.c_int * 3)(5, 16, 2)
+    wide = (ctypes.c_int * 3)(5, 16, 1025)  # more outputs than the last-layer kernel takes
     assert L.ctm_create_mlp(2, wide, fake, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -4
-    assert "scalar" in B.ctm_last_error()
+    assert "outputs" in B.ctm_last_error()
     holes = (ctypes.c_void_p * 2)(0x1000, None)
     assert L.ctm_create_mlp(2, dims, holes, None, B.CTM_F32, B.CTM_ACT_TANH, None, ctypes.byref(out)) == -1
     odd = (ctypes.c_void_p * 2)(0x1002, 0x2000)
