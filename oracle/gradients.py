@@ -52,3 +52,42 @@ def laplacian_loss_grads(Ws, bs, x, V, scale, gu, gop, act="tanh"):
     gW = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[:len(Ws_t)], Ws_t)]
     gb = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[len(Ws_t):], bs_t)]
     return float(L.detach()), gW, gb
+
+
+def biharmonic_loss_grads(Ws, bs, x, V, gu, gop, act="tanh"):
+    """Gradients of  L = sum_{n,c} gu_{n,c} u_c(x_n) + gop_{n,c} op_c(x_n)  for the randomized biharmonic
+    op_c(x_n) = 1/(3S) sum_s d^4/dt^4 f_c(x_n + t v_s) at t = 0  (Sec. 3.3, Eq. 9, stochastic case).
+
+    The fourth directional derivative is four nested first-order forward derivatives of the scalar path
+    t -> f(x + t v); one reverse sweep then goes to the parameters.  V: [S, D] or [N, S, D].
+    Returns (L, [dL/dW_l], [dL/db_l]) as fp64 numpy.
+    """
+    t = lambda a: torch.as_tensor(np.asarray(a, dtype=np.float64))
+    Ws_t = [t(W).requires_grad_(True) for W in Ws]
+    bs_t = [t(b).requires_grad_(True) for b in bs]
+    xt, Vt = t(x), t(V)
+    N, D = xt.shape
+    C = Ws_t[-1].shape[0]
+    if Vt.dim() == 2:
+        Vt = Vt.expand(N, *Vt.shape)
+    S = Vt.shape[1]
+    gut, gopt = t(gu).reshape(N, C), t(gop).reshape(N, C)
+    zero = torch.zeros((), dtype=torch.float64)
+
+    def loss(params):
+        def d4(p, v):  # [C]: fourth derivative along v at the point p
+            g = lambda s: _mlp(params, p + s * v, act)
+            for _ in range(4):
+                g = torch.func.jacfwd(g)
+            return g(zero)
+
+        per_dir = torch.func.vmap(torch.func.vmap(d4, in_dims=(None, 0)))(xt, Vt)  # [N, S, C]
+        u = _mlp(params, xt, act)
+        op = per_dir.sum(dim=1) / (3.0 * S)
+        return (gut * u + gopt * op).sum()
+
+    L = loss((Ws_t, bs_t))
+    grads = torch.autograd.grad(L, Ws_t + bs_t, allow_unused=True)
+    gW = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[:len(Ws_t)], Ws_t)]
+    gb = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[len(Ws_t):], bs_t)]
+    return float(L.detach()), gW, gb

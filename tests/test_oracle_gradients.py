@@ -60,3 +60,48 @@ def test_one_hidden_layer_closed_form_gradient():
     want_a = gu @ t + gop @ (d2 * (W1 ** 2).sum(1))
     np.testing.assert_allclose(gW[1][0], want_a, rtol=1e-11)
     np.testing.assert_allclose(gb[1][0], gu.sum(), rtol=1e-12)
+
+
+def numpy_biharmonic_loss(Ws, bs, x, V, gu, gop):
+    u, op = orc.biharmonic_rand(Ws, bs, x, V)
+    return float((gu * u + gop * op).sum())
+
+
+@pytest.mark.parametrize("dims,per_point", [((3, 5, 4, 1), True), ((2, 6, 1), False)])
+def test_biharmonic_gradients_against_finite_differences_of_the_numpy_oracle(dims, per_point):
+    Ws, bs = tiny(dims, 41)
+    rng = np.random.default_rng(42)
+    N, S, D = 3, 2, dims[0]
+    x = rng.random((N, D))
+    V = rng.standard_normal((N, S, D) if per_point else (S, D))
+    gu, gop = rng.standard_normal(N), rng.standard_normal(N)
+    L, gW, gb = og.biharmonic_loss_grads(Ws, bs, x, V, gu, gop)
+    assert L == pytest.approx(numpy_biharmonic_loss(Ws, bs, x, V, gu, gop), rel=1e-11)
+    h = 1e-5
+    for group, grads in ((Ws, gW), (bs, gb)):
+        for arr, g in zip(group, grads):
+            it = np.nditer(arr, flags=["multi_index"])
+            for _ in it:
+                i = it.multi_index
+                old = arr[i]
+                arr[i] = old + h
+                lp = numpy_biharmonic_loss(Ws, bs, x, V, gu, gop)
+                arr[i] = old - h
+                lm = numpy_biharmonic_loss(Ws, bs, x, V, gu, gop)
+                arr[i] = old
+                assert g[i] == pytest.approx((lp - lm) / (2 * h), rel=5e-6, abs=5e-8), (i, g[i])
+
+
+def test_biharmonic_closed_form_gradient_one_hidden_layer():
+    # <d^4 u, v^4> = sum_j a_j (w_j.v)^4 tanh''''(z_j):  d/da_j = (w_j.v)^4 tanh''''(z_j), d/dc = 0
+    rng = np.random.default_rng(6)
+    W1, b1 = rng.standard_normal((6, 3)) * 0.5, rng.standard_normal(6) * 0.2
+    a, c = rng.standard_normal((1, 6)), rng.standard_normal(1)
+    x, V = rng.random((4, 3)), rng.standard_normal((2, 3))
+    gu, gop = rng.standard_normal(4), rng.standard_normal(4)
+    _, gW, gb = og.biharmonic_loss_grads([W1, a], [b1, c], x, V, gu, gop)
+    t = np.tanh(x @ W1.T + b1)
+    d4 = 8 * t * (1 - t * t) * (2 - 3 * t * t)
+    proj4 = ((V @ W1.T) ** 4).sum(0) / (3.0 * 2)
+    np.testing.assert_allclose(gW[1][0], gu @ t + gop @ (d4 * proj4), rtol=1e-11)
+    np.testing.assert_allclose(gb[1][0], gu.sum(), rtol=1e-12)
