@@ -97,7 +97,7 @@ def main():
     ap.add_argument("--taylor", choices=["collapsed", "standard"], default="collapsed",
                     help="standard = the un-collapsed comparison path (1 + K*R rows per point); c1..c5 only")
     ap.add_argument("--backward", action="store_true",
-                    help="time forward-with-tape plus the reverse pass to all weights (laplacian workloads, collapsed, native MFMA)")
+                    help="time forward-with-tape plus the reverse pass to all weights (laplacian and biharmonic_rand workloads, collapsed, native MFMA)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -136,10 +136,14 @@ def main():
 
     bwd = args.backward
     if bwd:
-        if w.op != "laplacian" or std or args.mfma != "native":
-            sys.exit("bench.py: --backward covers the laplacian workloads with collapsed Taylor mode and native MFMA")
-        tape = torch.empty(ctm.ctm_tape_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
-        ws = torch.empty(ctm.ctm_backward_workspace_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
+        if w.op not in ("laplacian", "biharmonic_rand") or std or args.mfma != "native":
+            sys.exit("bench.py: --backward covers the laplacian and biharmonic_rand workloads with collapsed Taylor mode and native MFMA")
+        if K == 4:
+            tape = torch.empty(ctm.ctm_biharmonic_tape_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
+            ws = torch.empty(ctm.ctm_biharmonic_backward_workspace_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
+        else:
+            tape = torch.empty(ctm.ctm_tape_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
+            ws = torch.empty(ctm.ctm_backward_workspace_bytes(mlp, w.N, R), dtype=torch.uint8, device=dev)
         gu = torch.ones(w.N, dtype=x.dtype, device=dev)
         gop = torch.ones(w.N, dtype=x.dtype, device=dev)
         nl = len(w.dims) - 1
@@ -147,7 +151,10 @@ def main():
         gb = [torch.empty(w.dims[l + 1], dtype=x.dtype, device=dev) for l in range(nl)]
 
     def step():
-        if bwd:
+        if bwd and K == 4:
+            ctm.ctm_biharmonic_rand_fwd(mlp, x, V, u, op, tape)
+            ctm.ctm_biharmonic_rand_bwd(mlp, w.N, R, tape, gu, gop, gW, gb, ws)
+        elif bwd:
             ctm.ctm_laplacian_fwd(mlp, x, V, arrs.get("scale", 1.0), u, op, tape)
             ctm.ctm_laplacian_bwd(mlp, w.N, R, arrs.get("scale", 1.0), tape, gu, gop, gW, gb, ws)
         elif std:

@@ -185,6 +185,21 @@ int ctm_laplacian_bwd(const ctm_mlp *mlp, long N, int R, double scale, const voi
 int ctm_update_mlp(ctm_mlp *mlp, const void *const *W, const void *const *b, void *stream);
 
 /*
+ * The same pair of calls for the randomized biharmonic (Sec. 3.3, Eq. 9; "differentiable" evaluation, Sec. 4):
+ * ctm_biharmonic_rand_fwd computes the (u, op) of ctm_biharmonic_rand by collapsed order-4 Taylor mode and
+ * records the tape; ctm_biharmonic_rand_bwd runs the reverse of the order-4 rule (it needs the fifth derivative
+ * of the activation) and writes dL/dW_l, dL/db_l.  One pass only: S <= 84.  Arguments as in the Laplacian pair;
+ * the scale 1/(3S) is implied.  V must not be NULL.
+ */
+size_t ctm_biharmonic_tape_bytes(const ctm_mlp *mlp, long N, int S);
+size_t ctm_biharmonic_backward_workspace_bytes(const ctm_mlp *mlp, long N, int S);
+int ctm_biharmonic_rand_fwd(const ctm_mlp *mlp, const void *x, long N, const void *V, int S, long v_point_stride,
+                            void *u, void *op, void *tape, size_t tape_bytes, void *stream);
+int ctm_biharmonic_rand_bwd(const ctm_mlp *mlp, long N, int S, const void *tape, size_t tape_bytes, const void *gu,
+                            const void *gop, void *const *gW, void *const *gb, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
+/*
  * The same sums computed by STANDARD (un-collapsed) Taylor mode, for comparison only: every direction
  * carries its own order-K coefficient through the network (1 + K*R rows per point, Sec. 3.1) and the sum
  * over directions is taken after the last layer.  K = 2 or 4; other arguments as in ctm_laplacian

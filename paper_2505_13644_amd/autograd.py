@@ -1,8 +1,9 @@
 """torch.autograd glue around the recording forward and the reverse pass of libctm.so.
 
     u, op = laplacian(mlp, Ws, bs, x, V=None, scale=1.0)
+    u, op = biharmonic_rand(mlp, Ws, bs, x, V)
 
-returns tensors that are differentiable with respect to the weight tensors Ws / bs (not x or V).  Every number is
+return tensors that are differentiable with respect to the weight tensors Ws / bs (not x or V).  Every number is
 produced by the library's kernels; this module only re-packs the current weights into the handle
 (ctm_update_mlp), keeps the tape alive between forward and backward, and hands the gradients to autograd.
 """
@@ -30,6 +31,28 @@ class _Laplacian(torch.autograd.Function):
         gop = None if gop is None else gop.contiguous()
         gW, gb = B.ctm_laplacian_bwd(ctx.mlp, ctx.N, ctx.R, ctx.scale, ctx.tape, gu, gop)
         return (None, None, None, None, None, *gW, *gb)
+
+
+class _BiharmonicRand(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, mlp, x, V, n_layers, *params):
+        Ws, bs = list(params[:n_layers]), list(params[n_layers:])
+        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        u, op, tape = B.ctm_biharmonic_rand_fwd(mlp, x, V)
+        ctx.mlp, ctx.tape, ctx.N, ctx.S = mlp, tape, x.shape[0], V.shape[-2]
+        return u, op
+
+    @staticmethod
+    def backward(ctx, gu, gop):
+        gu = None if gu is None else gu.contiguous()
+        gop = None if gop is None else gop.contiguous()
+        gW, gb = B.ctm_biharmonic_rand_bwd(ctx.mlp, ctx.N, ctx.S, ctx.tape, gu, gop)
+        return (None, None, None, None, *gW, *gb)
+
+
+def biharmonic_rand(mlp, Ws, bs, x, V):
+    """(u, op) of ctm_biharmonic_rand, differentiable with respect to the tensors in Ws and bs."""
+    return _BiharmonicRand.apply(mlp, x, V, len(Ws), *Ws, *bs)
 
 
 def laplacian(mlp, Ws, bs, x, V=None, scale=1.0):

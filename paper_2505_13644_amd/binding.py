@@ -44,6 +44,12 @@ SIGNATURES = {
     "ctm_laplacian_bwd": (c_int, [c_void_p, c_long, c_int, c_double, c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_void_p),
                                   POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
     "ctm_update_mlp": (c_int, [c_void_p, POINTER(c_void_p), POINTER(c_void_p), c_void_p]),
+    "ctm_biharmonic_tape_bytes": (c_size_t, [c_void_p, c_long, c_int]),
+    "ctm_biharmonic_backward_workspace_bytes": (c_size_t, [c_void_p, c_long, c_int]),
+    "ctm_biharmonic_rand_fwd": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_void_p, c_void_p,
+                                        c_size_t, c_void_p]),
+    "ctm_biharmonic_rand_bwd": (c_int, [c_void_p, c_long, c_int, c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_void_p),
+                                        POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
     "ctm_workspace_bytes_standard": (c_size_t, [c_void_p, c_int, c_long, c_int]),
     "ctm_taylor_standard": (c_int, [c_void_p, c_int, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]),
@@ -409,9 +415,7 @@ def ctm_laplacian_fwd(mlp: Mlp, x, V=None, scale=1.0, u=None, op=None, tape=None
     return u, op, tape
 
 
-def ctm_laplacian_bwd(mlp: Mlp, N, R, scale, tape, gu, gop, gW=None, gb=None, workspace=None):
-    """dL/dW_l, dL/db_l from dL/du (gu) and dL/dop (gop).  gW / gb: lists of preallocated tensors or None entries;
-    omitted lists are allocated.  Returns (gW, gb)."""
+def _grad_buffers(mlp, N, tape, gu, gop, gW, gb):
     torch = _torch()
     L = len(mlp.dims) - 1
     dev = tape.device
@@ -427,13 +431,62 @@ def ctm_laplacian_bwd(mlp: Mlp, N, R, scale, tape, gu, gop, gW=None, gb=None, wo
     for name, t in (("gu", gu), ("gop", gop)):
         if t is not None and tuple(t.shape) != _out_shape(mlp, N):
             raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {list(_out_shape(mlp, N))}")
-    if workspace is None:
-        workspace = torch.empty(ctm_backward_workspace_bytes(mlp, N, R), dtype=torch.uint8, device=dev)
     c_gW = (c_void_p * L)(*[_dev_ptr(g, mlp.dtype, f"gW[{l}]") for l, g in enumerate(gW)])
     c_gb = (c_void_p * L)(*[_dev_ptr(g, mlp.dtype, f"gb[{l}]") for l, g in enumerate(gb)])
+    return gW, gb, c_gW, c_gb
+
+
+def ctm_laplacian_bwd(mlp: Mlp, N, R, scale, tape, gu, gop, gW=None, gb=None, workspace=None):
+    """dL/dW_l, dL/db_l from dL/du (gu) and dL/dop (gop).  gW / gb: lists of preallocated tensors or None entries;
+    omitted lists are allocated.  Returns (gW, gb)."""
+    torch = _torch()
+    gW, gb, c_gW, c_gb = _grad_buffers(mlp, N, tape, gu, gop, gW, gb)
+    if workspace is None:
+        workspace = torch.empty(ctm_backward_workspace_bytes(mlp, N, R), dtype=torch.uint8, device=tape.device)
     _check(lib().ctm_laplacian_bwd(mlp.handle, N, R, float(scale), c_void_p(tape.data_ptr()), tape.numel(),
                                    _dev_ptr(gu, mlp.dtype, "gu"), _dev_ptr(gop, mlp.dtype, "gop"), c_gW, c_gb,
                                    c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr()))
+    return gW, gb
+
+
+def ctm_biharmonic_tape_bytes(mlp: Mlp, N: int, S: int) -> int:
+    n = lib().ctm_biharmonic_tape_bytes(mlp.handle, N, S)
+    if n == 0:
+        raise CtmError(-4, ctm_last_error())
+    return n
+
+
+def ctm_biharmonic_backward_workspace_bytes(mlp: Mlp, N: int, S: int) -> int:
+    n = lib().ctm_biharmonic_backward_workspace_bytes(mlp.handle, N, S)
+    if n == 0:
+        raise CtmError(-4, ctm_last_error())
+    return n
+
+
+def ctm_biharmonic_rand_fwd(mlp: Mlp, x, V, u=None, op=None, tape=None):
+    """Randomized biharmonic that records a tape for ctm_biharmonic_rand_bwd.  Returns (u, op, tape)."""
+    torch = _torch()
+    _check_shapes(mlp, x, V)
+    N = x.shape[0]
+    S, stride = _dirs_of(x, V)
+    u, op = _out_pair(mlp, x, u, op)
+    if tape is None:
+        tape = torch.empty(ctm_biharmonic_tape_bytes(mlp, N, S), dtype=torch.uint8, device=x.device)
+    _check(lib().ctm_biharmonic_rand_fwd(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(V, mlp.dtype, "V"), S, stride,
+                                         _dev_ptr(u, mlp.dtype, "u"), _dev_ptr(op, mlp.dtype, "op"), c_void_p(tape.data_ptr()),
+                                         tape.numel(), _stream_ptr()))
+    return u, op, tape
+
+
+def ctm_biharmonic_rand_bwd(mlp: Mlp, N, S, tape, gu, gop, gW=None, gb=None, workspace=None):
+    """dL/dW_l, dL/db_l of the randomized biharmonic from dL/du (gu) and dL/dop (gop).  Returns (gW, gb)."""
+    torch = _torch()
+    gW, gb, c_gW, c_gb = _grad_buffers(mlp, N, tape, gu, gop, gW, gb)
+    if workspace is None:
+        workspace = torch.empty(ctm_biharmonic_backward_workspace_bytes(mlp, N, S), dtype=torch.uint8, device=tape.device)
+    _check(lib().ctm_biharmonic_rand_bwd(mlp.handle, N, S, c_void_p(tape.data_ptr()), tape.numel(),
+                                         _dev_ptr(gu, mlp.dtype, "gu"), _dev_ptr(gop, mlp.dtype, "gop"), c_gW, c_gb,
+                                         c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr()))
     return gW, gb
 
 

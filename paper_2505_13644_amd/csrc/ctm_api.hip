@@ -345,15 +345,15 @@ hipError_t pack_everything(ctm_mlp *m, const void *const *W, const void *const *
   return e;
 }
 
-// ---- tape of a recording forward pass (order 2, collapsed, one pass) ---------------------------------
+// ---- tape of a recording forward pass (collapsed, order K, one pass) ---------------------------------
 struct TapeLayout {
   size_t h0;                  // seed block [M][ld0]
   std::vector<size_t> z, h;   // per hidden layer i (width dims[i+1]): pre-activations; outputs (all but the last hidden layer)
   size_t pair, total;
 };
-TapeLayout tape_layout(const ctm_mlp *m, long N, int R) {
+TapeLayout tape_layout(const ctm_mlp *m, int K, long N, int R) {
   const size_t es = elem_size(m->dtype);
-  const size_t M = (size_t)N * (size_t)rows_per_point(2, R);
+  const size_t M = (size_t)N * (size_t)rows_per_point(K, R);
   TapeLayout t;
   size_t off = 0;
   t.h0 = off;
@@ -373,9 +373,9 @@ TapeLayout tape_layout(const ctm_mlp *m, long N, int R) {
 struct BwdLayout {
   size_t block_bytes, scratch, partials, total;
 };
-BwdLayout bwd_layout(const ctm_mlp *m, long N, int R) {
+BwdLayout bwd_layout(const ctm_mlp *m, int K, long N, int R) {
   const size_t es = elem_size(m->dtype);
-  const long M = N * rows_per_point(2, R);
+  const long M = N * rows_per_point(K, R);
   int maxld = 0;
   size_t maxpart = 0;
   for (int i = 0; i + 1 < m->L; ++i) {
@@ -391,30 +391,30 @@ BwdLayout bwd_layout(const ctm_mlp *m, long N, int R) {
   return b;
 }
 
-int check_tape_call(const ctm_mlp *m, long N, int R, const char *who) {
+int check_tape_call(const ctm_mlp *m, int K, long N, int R, const char *who) {
   if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
   if (m->dtype != CTM_F64 && m->dtype != CTM_F32)
     return fail(CTM_ERR_UNSUPPORTED, "%s: the recording forward and the reverse pass are built for CTM_F32 and CTM_F64", who);
   if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
   if (R < 1) return fail(CTM_ERR_SHAPE, "%s: %d directions, need at least 1", who, R);
-  if (R > max_dirs_per_pass(2))
+  if (R > max_dirs_per_pass(K))
     return fail(CTM_ERR_UNSUPPORTED, "%s: %d directions; the recording forward keeps one pass and takes at most %d", who, R,
-                max_dirs_per_pass(2));
-  if (N > (1L << 40) / rows_per_point(2, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
+                max_dirs_per_pass(K));
+  if (N > (1L << 40) / rows_per_point(K, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
   return CTM_OK;
 }
 
 template <typename T>
-int run_fwd_tape(const ctm_mlp *m, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
+int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
                  hipStream_t st) {
-  const TapeLayout tl = tape_layout(m, N, R);
-  const PassPlan pl = plan_pass(2, R, false, N, m->min_col_tiles, m->slots);
+  const TapeLayout tl = tape_layout(m, K, N, R);
+  const PassPlan pl = plan_pass(K, R, false, N, m->min_col_tiles, m->slots);
   const int L = m->L;
   char *tp = (char *)tape;
   SeedArgs<T> sa;
   sa.x = x; sa.V = V; sa.out = (T *)(tp + tl.h0); sa.N = N;
   sa.v_sn = sn; sa.v_sr = m->dims[0]; sa.v_sd = 1;
-  sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = 2; sa.r0 = 0; sa.standard = 0; sa.R = R;
+  sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = 0; sa.standard = 0; sa.R = R;
   if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
   hipError_t e = launch_seed<T>(sa, st);
   if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
@@ -428,7 +428,7 @@ int run_fwd_tape(const ctm_mlp *m, const T *x, long N, const T *V, int R, long s
     la.Hout = last ? pair : (T *)(tp + tl.h[i]);
     la.n_points = N; la.n_row_tiles = (N + pl.P - 1) / pl.P; la.n_col_tiles = m->col_tiles[i];
     la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[i]; la.ldout = m->ld[i + 1];
-    la.order = 2; la.R = R; la.last = last ? 1 : 0; la.act = (int)m->act; la.standard = 0;
+    la.order = K; la.R = R; la.last = last ? 1 : 0; la.act = (int)m->act; la.standard = 0;
     la.out_rows = last ? 2 : pl.rho;
     la.Zout = (T *)(tp + tl.z[i]); la.Zsaved = nullptr; la.bwd = 0;
     e = launch_layer<T>(la, pl.MB, st);
@@ -446,11 +446,11 @@ int run_fwd_tape(const ctm_mlp *m, const T *x, long N, const T *V, int R, long s
 }
 
 template <typename T>
-int run_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, const T *gu, const T *gop, void *const *gW,
+int run_bwd(const ctm_mlp *m, int K, long N, int R, double scale, const void *tape, const T *gu, const T *gop, void *const *gW,
             void *const *gb, void *ws, hipStream_t st) {
-  const TapeLayout tl = tape_layout(m, N, R);
-  const BwdLayout bl = bwd_layout(m, N, R);
-  const PassPlan pl = plan_pass(2, R, false, N, m->min_col_tiles, m->slots);
+  const TapeLayout tl = tape_layout(m, K, N, R);
+  const BwdLayout bl = bwd_layout(m, K, N, R);
+  const PassPlan pl = plan_pass(K, R, false, N, m->min_col_tiles, m->slots);
   const int L = m->L;
   const long M = N * pl.rho;
   const char *tp = (const char *)tape;
@@ -466,7 +466,7 @@ int run_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, con
   int cur = 0;
   BwdLastArgs<T> ba;
   ba.Z = (const T *)(tp + tl.z[L - 2]); ba.w = (const T *)m->Wp[L - 1]; ba.gu = gu; ba.gop = gop; ba.Zbar = zb[cur];
-  ba.N = N; ba.ld = m->ld[L - 1]; ba.rho = pl.rho; ba.R = R; ba.act = (int)m->act; ba.scale = scale; ba.C = m->dims[L];
+  ba.N = N; ba.ld = m->ld[L - 1]; ba.rho = pl.rho; ba.R = R; ba.act = (int)m->act; ba.scale = scale; ba.C = m->dims[L]; ba.order = K;
   hipError_t e = launch_bwd_last<T>(ba, st);
   if (e != hipSuccess) return fail_hip(e, "reverse last-layer kernel launch");
   T *gw_last = (gW && gW[L - 1]) ? (T *)gW[L - 1] : dummy;
@@ -493,7 +493,7 @@ int run_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, con
       la.Hout = zb[cur ^ 1];
       la.n_points = N; la.n_row_tiles = (N + pl.P - 1) / pl.P; la.n_col_tiles = m->col_tiles[i - 1];
       la.rho = pl.rho; la.P = pl.P; la.ldin = m->ld[i + 1]; la.ldout = m->ld[i];
-      la.order = 2; la.R = R; la.last = 0; la.act = (int)m->act; la.standard = 0; la.out_rows = pl.rho;
+      la.order = K; la.R = R; la.last = 0; la.act = (int)m->act; la.standard = 0; la.out_rows = pl.rho;
       la.Zout = nullptr; la.Zsaved = (const T *)(tp + tl.z[i - 1]); la.bwd = 1;
       e = launch_layer<T>(la, pl.MB, st);
       if (e != hipSuccess) return fail_hip(e, "reverse layer kernel launch");
@@ -781,25 +781,39 @@ int ctm_update_mlp(ctm_mlp *m, const void *const *W, const void *const *b, void 
 }
 
 size_t ctm_tape_bytes(const ctm_mlp *m, long N, int R) {
-  if (check_tape_call(m, N, R, "ctm_tape_bytes") != CTM_OK) return 0;
-  return tape_layout(m, N, R).total;
+  if (check_tape_call(m, 2, N, R, "ctm_tape_bytes") != CTM_OK) return 0;
+  return tape_layout(m, 2, N, R).total;
 }
 
 size_t ctm_backward_workspace_bytes(const ctm_mlp *m, long N, int R) {
-  if (check_tape_call(m, N, R, "ctm_backward_workspace_bytes") != CTM_OK) return 0;
-  return bwd_layout(m, N, R).total;
+  if (check_tape_call(m, 2, N, R, "ctm_backward_workspace_bytes") != CTM_OK) return 0;
+  return bwd_layout(m, 2, N, R).total;
 }
 
-int ctm_laplacian_fwd(const ctm_mlp *m, const void *x, long N, const void *V, int R, long v_point_stride, double scale, void *u,
-                      void *op, void *tape, size_t tape_bytes, void *stream) {
-  const char *who = "ctm_laplacian_fwd";
-  int rc = check_tape_call(m, N, R, who);
+size_t ctm_biharmonic_tape_bytes(const ctm_mlp *m, long N, int S) {
+  if (check_tape_call(m, 4, N, S, "ctm_biharmonic_tape_bytes") != CTM_OK) return 0;
+  return tape_layout(m, 4, N, S).total;
+}
+
+size_t ctm_biharmonic_backward_workspace_bytes(const ctm_mlp *m, long N, int S) {
+  if (check_tape_call(m, 4, N, S, "ctm_biharmonic_backward_workspace_bytes") != CTM_OK) return 0;
+  return bwd_layout(m, 4, N, S).total;
+}
+
+}  // extern "C"
+
+namespace {
+
+int recording_forward(const char *who, const ctm_mlp *m, int K, const void *x, long N, const void *V, int R, long v_point_stride,
+                      double scale, void *u, void *op, void *tape, size_t tape_bytes, void *stream) {
+  int rc = check_tape_call(m, K, N, R, who);
   if (rc != CTM_OK) return rc;
   if (!x || !tape) return fail(CTM_ERR_NULL, "%s: x or tape is NULL", who);
+  if (K == 4 && !V) return fail(CTM_ERR_NULL, "%s: V is NULL", who);
   if (!V && R != m->dims[0]) return fail(CTM_ERR_SHAPE, "%s: V = NULL selects the standard basis, so R must be D = %d (got %d)", who, m->dims[0], R);
   if (v_point_stride != 0 && v_point_stride != (long)R * m->dims[0])
     return fail(CTM_ERR_SHAPE, "%s: v_point_stride = %ld, must be 0 (shared) or R*D = %ld", who, v_point_stride, (long)R * m->dims[0]);
-  const size_t need = tape_layout(m, N, R).total;
+  const size_t need = tape_layout(m, K, N, R).total;
   if (tape_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: tape has %zu bytes, need %zu", who, tape_bytes, need);
   const size_t es = elem_size(m->dtype);
   if (misaligned(tape, 256)) return fail(CTM_ERR_ALIGN, "%s: tape must be 256-byte aligned", who);
@@ -807,18 +821,17 @@ int ctm_laplacian_fwd(const ctm_mlp *m, const void *x, long N, const void *V, in
     return fail(CTM_ERR_ALIGN, "%s: x, directions, u and op must be aligned to the element size", who);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
-    return run_fwd_tape<double>(m, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st);
-  return run_fwd_tape<float>(m, (const float *)x, N, (const float *)V, R, v_point_stride, scale, (float *)u, (float *)op, tape, st);
+    return run_fwd_tape<double>(m, K, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st);
+  return run_fwd_tape<float>(m, K, (const float *)x, N, (const float *)V, R, v_point_stride, scale, (float *)u, (float *)op, tape, st);
 }
 
-int ctm_laplacian_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, size_t tape_bytes, const void *gu,
-                      const void *gop, void *const *gW, void *const *gb, void *ws, size_t ws_bytes, void *stream) {
-  const char *who = "ctm_laplacian_bwd";
-  int rc = check_tape_call(m, N, R, who);
+int reverse_pass(const char *who, const ctm_mlp *m, int K, long N, int R, double scale, const void *tape, size_t tape_bytes,
+                 const void *gu, const void *gop, void *const *gW, void *const *gb, void *ws, size_t ws_bytes, void *stream) {
+  int rc = check_tape_call(m, K, N, R, who);
   if (rc != CTM_OK) return rc;
   if (!tape || !ws) return fail(CTM_ERR_NULL, "%s: tape or workspace is NULL", who);
-  if (tape_bytes < tape_layout(m, N, R).total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than ctm_tape_bytes() says", who);
-  const size_t need = bwd_layout(m, N, R).total;
+  if (tape_bytes < tape_layout(m, K, N, R).total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than the tape size query says", who);
+  const size_t need = bwd_layout(m, K, N, R).total;
   if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
   const size_t es = elem_size(m->dtype);
   if (misaligned(tape, 256) || misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: tape and workspace must be 256-byte aligned", who);
@@ -828,8 +841,34 @@ int ctm_laplacian_bwd(const ctm_mlp *m, long N, int R, double scale, const void 
       return fail(CTM_ERR_ALIGN, "%s: gW[%d] / gb[%d] not aligned to the element size", who, l, l);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
-    return run_bwd<double>(m, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st);
-  return run_bwd<float>(m, N, R, scale, tape, (const float *)gu, (const float *)gop, gW, gb, ws, st);
+    return run_bwd<double>(m, K, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st);
+  return run_bwd<float>(m, K, N, R, scale, tape, (const float *)gu, (const float *)gop, gW, gb, ws, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ctm_laplacian_fwd(const ctm_mlp *m, const void *x, long N, const void *V, int R, long v_point_stride, double scale, void *u,
+                      void *op, void *tape, size_t tape_bytes, void *stream) {
+  return recording_forward("ctm_laplacian_fwd", m, 2, x, N, V, R, v_point_stride, scale, u, op, tape, tape_bytes, stream);
+}
+
+int ctm_laplacian_bwd(const ctm_mlp *m, long N, int R, double scale, const void *tape, size_t tape_bytes, const void *gu,
+                      const void *gop, void *const *gW, void *const *gb, void *ws, size_t ws_bytes, void *stream) {
+  return reverse_pass("ctm_laplacian_bwd", m, 2, N, R, scale, tape, tape_bytes, gu, gop, gW, gb, ws, ws_bytes, stream);
+}
+
+int ctm_biharmonic_rand_fwd(const ctm_mlp *m, const void *x, long N, const void *V, int S, long v_point_stride, void *u, void *op,
+                            void *tape, size_t tape_bytes, void *stream) {
+  const double scale = S >= 1 ? 1.0 / (3.0 * S) : 0.0;
+  return recording_forward("ctm_biharmonic_rand_fwd", m, 4, x, N, V, S, v_point_stride, scale, u, op, tape, tape_bytes, stream);
+}
+
+int ctm_biharmonic_rand_bwd(const ctm_mlp *m, long N, int S, const void *tape, size_t tape_bytes, const void *gu, const void *gop,
+                            void *const *gW, void *const *gb, void *ws, size_t ws_bytes, void *stream) {
+  const double scale = S >= 1 ? 1.0 / (3.0 * S) : 0.0;
+  return reverse_pass("ctm_biharmonic_rand_bwd", m, 4, N, S, scale, tape, tape_bytes, gu, gop, gW, gb, ws, ws_bytes, stream);
 }
 
 int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, long long *den) {

@@ -1,10 +1,10 @@
-// Reverse pass of the order-2 collapsed propagation (gradients with respect to the weights):
+// Reverse pass of the collapsed propagation, orders 2 and 4 (gradients with respect to the weights):
 // everything except the cotangent GEMM, which reuses layer_kernel with its reverse-rule epilogue.
 //
 // With L = sum_n gu_n u_n + gop_n op_n, u = w.h_0 + b, op = scale * w.h_2 at the last layer and, per hidden
 // layer, Z = H_prev W^T (+ bias on the order-0 rows) followed by the rule (ctm_rule.h):
-//   cotangents at the last hidden layer:  hb_0 = gu w,  hb_{1,r} = 0,  hb_2 = scale gop w      -> bwd_last_kernel
-//   dL/dw = sum_n gu_n h_0(n) + scale gop_n h_2(n),  dL/db_last = sum_n gu_n                  -> last_grads
+//   cotangents at the last hidden layer:  hb_0 = gu w,  hb_K = scale gop w, all other rows 0   -> bwd_last_kernel
+//   dL/dw = sum_n gu_n h_0(n) + scale gop_n h_K(n),  dL/db_last = sum_n gu_n                  -> last_grads
 //   (a network with C outputs has one (u, op) pair, one row of w and one bias per output; the cotangents sum over them)
 //   per hidden layer:  dL/db = sum_n Zbar[order-0 row of n]                                    -> bias_grad
 //                      dL/dW = Zbar^T H_prev   (a GEMM whose k index runs over all N*rho rows)  -> wgrad_kernel
@@ -25,23 +25,40 @@ template <typename T> __global__ void bwd_last_kernel(const BwdLastArgs<T> a) {
     const long n = i / a.ld;
     const T *zs = a.Z + (n * rho) * step + j;
     T *o = a.Zbar + (n * rho) * step + j;
-    T hb0 = T(0), hb2 = T(0);
+    T hb0 = T(0), hbK = T(0);  // cotangents of h_0 and of the collapsed highest-order row; all others are zero
     for (int c = 0; c < a.C; ++c) {
       const T w = a.w[(long)c * a.ld + j];
       if (a.gu) hb0 += a.gu[n * a.C + c] * w;
-      if (a.gop) hb2 += (T)(a.scale * (double)a.gop[n * a.C + c]) * w;
+      if (a.gop) hbK += (T)(a.scale * (double)a.gop[n * a.C + c]) * w;
     }
     T t, d1;
     act_eval<T>(a.act, zs[0], t, d1);
     const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
-    T s = T(0);
-    for (int r = 1; r <= R; ++r) {
-      const T z1 = zs[r * step];
-      s += z1 * z1;
-      o[r * step] = T(2) * d2 * z1 * hb2;
+    if (a.order == 2) {
+      T s = T(0);
+      for (int r = 1; r <= R; ++r) {
+        const T z1 = zs[r * step];
+        s += z1 * z1;
+        o[r * step] = T(2) * d2 * z1 * hbK;
+      }
+      o[(R + 1) * step] = d1 * hbK;
+      o[0] = d1 * hb0 + d2 * hbK * zs[(R + 1) * step] + d3 * s * hbK;
+    } else {  // the order-4 reverse rule (ctm_rule.h) with hb_1 = hb_2 = hb_3 = 0
+      const T d4 = act_d4<T>(a.act, t, d1), d5 = act_d5<T>(a.act, t, d1);
+      T s4 = T(0);
+      for (int r = 0; r < R; ++r) {
+        const T *zr = zs + (long)(1 + 3 * r) * step;
+        T *orow = o + (long)(1 + 3 * r) * step;
+        const T z1 = zr[0], z2 = zr[step], z3 = zr[2 * step];
+        const T z1s = z1 * z1;
+        orow[0] = T(4) * (d4 * z1s * z1 + T(3) * d3 * z1 * z2 + d2 * z3) * hbK;
+        orow[step] = T(6) * (d3 * z1s + d2 * z2) * hbK;
+        orow[2 * step] = T(4) * d2 * z1 * hbK;
+        s4 += d5 * z1s * z1s + T(6) * d4 * z1s * z2 + T(4) * d3 * z1 * z3 + T(3) * d3 * z2 * z2;
+      }
+      o[(long)(3 * R + 1) * step] = d1 * hbK;
+      o[0] = d1 * hb0 + hbK * (d2 * zs[(long)(3 * R + 1) * step] + s4);
     }
-    o[(R + 1) * step] = d1 * hb2;
-    o[0] = d1 * hb0 + d2 * hb2 * zs[(R + 1) * step] + d3 * s * hb2;
   }
 }
 
@@ -161,7 +178,7 @@ template <> struct WVec<double> {
 constexpr int kWgTile = 128;
 constexpr int kWgK = 16;               // rows per stage
 constexpr int kWgPitch = kWgTile + 16; // LDS row pitch in elements: the four k rows a wave reads land in distinct banks
-constexpr int kWgTargetBlocks = 2048;
+constexpr int kWgTargetBlocks = 1024;  // about two rounds of resident workgroups
 
 struct WgradPlan {
   int ti, tj, ksplit;
@@ -172,7 +189,7 @@ static WgradPlan wgrad_plan(long M, int d_out, int d_in) {
   p.ti = (d_out + kWgTile - 1) / kWgTile;
   p.tj = (d_in + kWgTile - 1) / kWgTile;
   long ks = kWgTargetBlocks / ((long)p.ti * p.tj);
-  const long max_ks = (M + 4 * kWgK - 1) / (4 * kWgK);  // at least four stages per block
+  const long max_ks = (M + 8 * kWgK - 1) / (8 * kWgK);  // at least eight stages per block
   if (ks > max_ks) ks = max_ks;
   if (ks > 1024) ks = 1024;
   if (ks < 1) ks = 1;
@@ -280,15 +297,36 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T *Zb, int ld_out, con
       }
 }
 
+// gW[i][j] = sum_k partials[k][i][j] in a fixed order: a block takes 64 outputs, its four wavefronts a quarter of
+// the k range each (four running sums per thread keep several loads in flight), then the quarters are added.
 template <typename T>
-__global__ void wgrad_reduce_kernel(const T *partials, int ksplit, long pi, long pj, int d_out, int d_in, T *gW) {
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const T *partials, int ksplit, long pi, long pj, int d_out, int d_in,
+                                                           T *gW) {
+  __shared__ T red[4][64];
+  const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
   const long total = (long)d_out * d_in;
-  for (long idx = blockIdx.x * (long)blockDim.x + threadIdx.x; idx < total; idx += (long)gridDim.x * blockDim.x) {
+  const long idx = blockIdx.x * 64L + o;
+  T acc = T(0);
+  if (idx < total) {
     const long i = idx / d_in, j = idx % d_in;
-    T acc = T(0);
-    for (int k = 0; k < ksplit; ++k) acc += partials[((long)k * pi + i) * pj + j];
-    gW[idx] = acc;
+    const int per = (ksplit + 3) / 4;
+    const int k0 = g * per, k1 = (k0 + per < ksplit) ? k0 + per : ksplit;
+    const long stride = pi * pj;
+    const T *p = partials + i * pj + j;
+    T a0 = T(0), a1 = T(0), a2 = T(0), a3 = T(0);
+    int k = k0;
+    for (; k + 3 < k1; k += 4) {
+      a0 += p[(long)k * stride];
+      a1 += p[(long)(k + 1) * stride];
+      a2 += p[(long)(k + 2) * stride];
+      a3 += p[(long)(k + 3) * stride];
+    }
+    for (; k < k1; ++k) a0 += p[(long)k * stride];
+    acc = (a0 + a1) + (a2 + a3);
   }
+  red[g][o] = acc;
+  __syncthreads();
+  if (g == 0 && idx < total) gW[idx] = (red[0][o] + red[1][o]) + (red[2][o] + red[3][o]);
 }
 
 template <typename T>
@@ -307,8 +345,8 @@ hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M
                      p.rows_per, p.tj, partials);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  long blocks = ((long)d_out * d_in + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
+  const long blocks = ((long)d_out * d_in + 63) / 64;
+  if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(wgrad_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, partials, p.ksplit, (long)p.ti * kWgTile,
                      (long)p.tj * kWgTile, d_out, d_in, gW);
   return hipGetLastError();

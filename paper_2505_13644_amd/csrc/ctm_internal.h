@@ -99,7 +99,7 @@ template <typename T>
 hipError_t launch_pack(const T *W, const T *b, int d_out, int d_in, T *Wp, T *bp, int rows_pad,
                        int ld, hipStream_t s, int transpose = 0);
 
-// ---- reverse pass (order 2, collapsed) -----------------------------------------------------
+// ---- reverse pass (collapsed, orders 2 and 4) -----------------------------------------------------
 template <typename T> struct BwdLastArgs {
   const T *Z;     // recorded pre-activations of the last hidden layer [N * rho][ld]
   const T *w;     // last-layer weights [C][ld]
@@ -109,6 +109,7 @@ template <typename T> struct BwdLastArgs {
   long N;
   int ld, rho, R, act;
   int C;          // network outputs
+  int order;      // 2 or 4
   double scale;
 };
 template <typename T> hipError_t launch_bwd_last(const BwdLastArgs<T> &a, hipStream_t s);

@@ -18,9 +18,10 @@ __device__ __forceinline__ void act_sincos(float z, float &s, float &c) { s = si
 __device__ __forceinline__ void act_sincos(double z, double &s, double &c) { s = sin(z); c = cos(z); }
 
 // Activation value t = phi(z) and first derivative d1; the higher derivatives follow from (t, d1):
-//   act 0, tanh:     d1 = 1 - t^2, d2 = -2 t d1, d3 = d1 (6 t^2 - 2), d4 = 8 t d1 (2 - 3 t^2)
-//   act 1, identity: d1 = 1, d2 = d3 = d4 = 0
-//   act 2, sin:      t = sin z, d1 = cos z, d2 = -t, d3 = -d1, d4 = t
+//   act 0, tanh:     d1 = 1 - t^2, d2 = -2 t d1, d3 = d1 (6 t^2 - 2), d4 = 8 t d1 (2 - 3 t^2),
+//                    d5 = d1 (16 - 120 t^2 + 120 t^4)   (only the reverse of the order-4 rule needs it)
+//   act 1, identity: d1 = 1, d2 = d3 = d4 = d5 = 0
+//   act 2, sin:      t = sin z, d1 = cos z, d2 = -t, d3 = -d1, d4 = t, d5 = d1
 template <typename T> __device__ __forceinline__ void act_eval(int act, T z, T &t, T &d1) {
   if (act == 0) {
     t = act_tanh(z);
@@ -40,6 +41,11 @@ template <typename T> __device__ __forceinline__ T act_d3(int act, T t, T d1) {
 }
 template <typename T> __device__ __forceinline__ T act_d4(int act, T t, T d1) {
   return act == 0 ? T(8) * t * d1 * (T(2) - T(3) * t * t) : (act == 2 ? t : T(0));
+}
+
+template <typename T> __device__ __forceinline__ T act_d5(int act, T t, T d1) {
+  const T t2 = t * t;
+  return act == 0 ? d1 * (T(16) + T(120) * t2 * (t2 - T(1))) : (act == 2 ? d1 : T(0));
 }
 
 // c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows);
@@ -132,13 +138,20 @@ __device__ __forceinline__ void save_preactivations(const T *c, int CROW, T bias
   for (int r = 1; r < rho; ++r) zo[r * zstep] = c[(long)r * CROW];
 }
 
-// Reverse of the order-2 collapsed rule for one (point, feature) pair.  With z the recorded pre-activations,
-// hb the cotangents of (h_0, h_{1,r}, h_2) and d3 the third derivative of tanh, d1 (6 t^2 - 2):
+// Reverse of the collapsed rule for one (point, feature) pair.  z are the recorded pre-activations, hb the
+// cotangents of the rule's outputs; d1 .. d5 depend on z_0 with d(d_k)/dz_0 = d_{k+1}.
+// Order 2 (h_0 = t, h_{1,r} = d1 z_{1,r}, h_2 = d1 z_2 + d2 sum_r z_{1,r}^2):
 //   zb_2     = d1 hb_2
 //   zb_{1,r} = d1 hb_{1,r} + 2 d2 z_{1,r} hb_2
 //   zb_0     = d1 hb_0 + d2 (sum_r hb_{1,r} z_{1,r} + hb_2 z_2) + d3 hb_2 sum_r z_{1,r}^2
-// (differentiate h_0 = t, h_{1,r} = d1 z_{1,r}, h_2 = d1 z_2 + d2 sum_r z_{1,r}^2; d1 and d2 depend on z_0 with
-// derivatives d2 and d3).  c: cotangent column in the staged C tile; zs: recorded column; o: output column.
+// Order 4 (h_{1..3,r} and the collapsed h_4 as in jet_rule; z1, z2, z3 stand for z_{1,r}, z_{2,r}, z_{3,r}):
+//   zb_4     = d1 hb_4
+//   zb_{3,r} = d1 hb_3 + 4 d2 z1 hb_4
+//   zb_{2,r} = d1 hb_2 + 3 d2 z1 hb_3 + 6 (d3 z1^2 + d2 z2) hb_4
+//   zb_{1,r} = d1 hb_1 + 2 d2 z1 hb_2 + 3 (d3 z1^2 + d2 z2) hb_3 + 4 (d4 z1^3 + 3 d3 z1 z2 + d2 z3) hb_4
+//   zb_0     = d1 hb_0 + sum_r [ d2 z1 hb_1 + (d3 z1^2 + d2 z2) hb_2 + (d4 z1^3 + 3 d3 z1 z2 + d2 z3) hb_3 ]
+//              + hb_4 [ d2 z_4 + sum_r (d5 z1^4 + 6 d4 z1^2 z2 + 4 d3 z1 z3 + 3 d3 z2^2) ]
+// c: cotangent column in the staged C tile; zs: recorded column; o: output column.
 template <typename T>
 __device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, long zstep, T *o, long ostep, const LayerArgs<T> &a) {
   const int R = a.R;
@@ -146,17 +159,41 @@ __device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, 
   T t, d1;
   act_eval<T>(a.act, z0, t, d1);
   const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
-  const T hb0 = c[0], hb2 = c[(long)(R + 1) * CROW];
-  const T z2 = zs[(long)(R + 1) * zstep];
-  T s = T(0), dot = T(0);
-  for (int r = 1; r <= R; ++r) {
-    const T z1 = zs[(long)r * zstep], hb1 = c[(long)r * CROW];
-    s += z1 * z1;
-    dot += hb1 * z1;
-    o[r * ostep] = d1 * hb1 + T(2) * d2 * z1 * hb2;
+  if (a.order == 2) {
+    const T hb0 = c[0], hb2 = c[(long)(R + 1) * CROW];
+    const T z2 = zs[(long)(R + 1) * zstep];
+    T s = T(0), dot = T(0);
+    for (int r = 1; r <= R; ++r) {
+      const T z1 = zs[(long)r * zstep], hb1 = c[(long)r * CROW];
+      s += z1 * z1;
+      dot += hb1 * z1;
+      o[r * ostep] = d1 * hb1 + T(2) * d2 * z1 * hb2;
+    }
+    o[(R + 1) * ostep] = d1 * hb2;
+    o[0] = d1 * hb0 + d2 * (dot + hb2 * z2) + d3 * s * hb2;
+  } else {
+    const T d4 = act_d4<T>(a.act, t, d1), d5 = act_d5<T>(a.act, t, d1);
+    const T hb0 = c[0], hb4 = c[(long)(3 * R + 1) * CROW];
+    const T z4 = zs[(long)(3 * R + 1) * zstep];
+    T acc = T(0), s4 = T(0);
+    for (int r = 0; r < R; ++r) {
+      const T *zr = zs + (long)(1 + 3 * r) * zstep;
+      const T *cr = c + (long)(1 + 3 * r) * CROW;
+      T *orow = o + (long)(1 + 3 * r) * ostep;
+      const T z1 = zr[0], z2 = zr[zstep], z3 = zr[2 * zstep];
+      const T hb1 = cr[0], hb2 = cr[CROW], hb3 = cr[2 * CROW];
+      const T z1s = z1 * z1;
+      const T p2 = d3 * z1s + d2 * z2;                              // d h_2 / d z_0
+      const T p3 = d4 * z1s * z1 + T(3) * d3 * z1 * z2 + d2 * z3;   // d h_3 / d z_0
+      orow[0] = d1 * hb1 + T(2) * d2 * z1 * hb2 + T(3) * p2 * hb3 + T(4) * p3 * hb4;
+      orow[ostep] = d1 * hb2 + T(3) * d2 * z1 * hb3 + T(6) * p2 * hb4;
+      orow[2 * ostep] = d1 * hb3 + T(4) * d2 * z1 * hb4;
+      acc += d2 * z1 * hb1 + p2 * hb2 + p3 * hb3;
+      s4 += d5 * z1s * z1s + T(6) * d4 * z1s * z2 + T(4) * d3 * z1 * z3 + T(3) * d3 * z2 * z2;
+    }
+    o[(long)(3 * R + 1) * ostep] = d1 * hb4;
+    o[0] = d1 * hb0 + acc + hb4 * (d2 * z4 + s4);
   }
-  o[(R + 1) * ostep] = d1 * hb2;
-  o[0] = d1 * hb0 + d2 * (dot + hb2 * z2) + d3 * s * hb2;
 }
 
 }  // namespace ctm

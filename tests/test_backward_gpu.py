@@ -183,3 +183,113 @@ def test_weight_gradients_sin_activation(dtype):
     for l in range(3):
         assert rel(gW[l].double().cpu().numpy(), rW[l]) <= tol and rel(gb[l].double().cpu().numpy(), rb[l]) <= tol
     mlp.close()
+
+
+# ---- randomized biharmonic: reverse of the order-4 rule (Sec. 3.3, Eq. 9; "differentiable" evaluation, Sec. 4) ----
+
+def run_gpu_biharmonic(arrs, gu, gop, dtype, act=None):
+    import torch
+    import paper_2505_13644_amd as ctm
+    dev = torch.device("cuda:0")
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]], ctm.CTM_ACT_TANH if act is None else act)
+    x, V = t(arrs["x"]), t(arrs["V"])
+    N, S = x.shape[0], V.shape[-2]
+    u, op, tape = ctm.ctm_biharmonic_rand_fwd(mlp, x, V)
+    u2, op2 = ctm.ctm_biharmonic_rand(mlp, x, V)
+    gW, gb = ctm.ctm_biharmonic_rand_bwd(mlp, N, S, tape, t(gu.astype(dtype)), t(gop.astype(dtype)))
+    torch.cuda.synchronize()
+    tol = 1e-12 if dtype == np.float64 else 2e-5
+    same = (u - u2).abs().max().item() <= tol * u2.abs().max().item() and (op - op2).abs().max().item() <= tol * op2.abs().max().item()
+    out = ([g.double().cpu().numpy() for g in gW], [g.double().cpu().numpy() for g in gb], same)
+    mlp.close()
+    return out
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,S,per_point", [
+    ((5, 16, 16, 1), 8, 3, True),            # c1's network
+    ((3, 40, 24, 1), 37, 5, False),          # shared directions, ragged tiles
+    ((4, 48, 48, 48, 2), 21, 4, True),       # three hidden layers, two outputs
+    ((2, 100, 1), 70, 2, False),             # one hidden layer
+    ((10, 160, 144, 1), 60, 6, True),        # widths over one 128-column tile
+])
+def test_biharmonic_weight_gradients_against_the_autograd_oracle(dtype, dims, N, S, per_point):
+    from oracle import gradients as og
+    arrs = case(dims, N, dtype, seed=N + len(dims), R=S, per_point=per_point)
+    C = dims[-1]
+    rng = np.random.default_rng(N)
+    shape = (N,) if C == 1 else (N, C)
+    gu, gop = rng.standard_normal(shape), rng.standard_normal(shape)
+    print(f"case biharmonic backward dims={dims} N={N} S={S} {dtype.__name__}", flush=True)
+    gW, gb, same = run_gpu_biharmonic(arrs, gu, gop, dtype)
+    assert same, "the recording forward must agree with ctm_biharmonic_rand"
+    _, rW, rb = og.biharmonic_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], arrs["V"],
+                                         gu.astype(dtype).astype(np.float64), gop.astype(dtype).astype(np.float64))
+    tol = 1e-9 if dtype == np.float64 else 2e-4
+    for l in range(len(dims) - 1):
+        eW, eb = rel(gW[l], rW[l]), rel(gb[l], rb[l])
+        print(f"  layer {l}: dW err {eW:.2e}  db err {eb:.2e}", flush=True)
+        assert eW <= tol and eb <= tol, (l, eW, eb)
+
+
+def test_biharmonic_backward_on_its_benchmark_network_sin_activation_and_limits():
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import gradients as og
+    # the order-4 workload's network and direction count at a reduced batch
+    w = synth.WORKLOADS["c5"]
+    N = 12
+    arrs = w.build(N)
+    rng = np.random.default_rng(8)
+    gu, gop = rng.standard_normal(N), rng.standard_normal(N)
+    gW, gb, same = run_gpu_biharmonic(arrs, gu, gop, np.float32)
+    gW2, gb2, _ = run_gpu_biharmonic(arrs, gu, gop, np.float32)
+    assert same
+    for a, b in zip(gW + gb, gW2 + gb2):
+        assert np.array_equal(a, b)  # fixed partitions and orders: bitwise reproducible
+    _, rW, rb = og.biharmonic_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], arrs["V"], gu.astype(np.float32).astype(np.float64),
+                                         gop.astype(np.float32).astype(np.float64))
+    for l in range(len(rW)):
+        eW, eb = rel(gW[l], rW[l]), rel(gb[l], rb[l])
+        print(f"  c5 net layer {l}: dW err {eW:.2e}  db err {eb:.2e}", flush=True)
+        assert eW <= 2e-4 and eb <= 2e-4
+    # sin activation: its fifth derivative is cos
+    arrs = case((4, 24, 16, 1), 15, np.float64, 3, 3, True)
+    gu, gop = rng.standard_normal(15), rng.standard_normal(15)
+    gW, gb, _ = run_gpu_biharmonic(arrs, gu, gop, np.float64, act=ctm.CTM_ACT_SIN)
+    _, rW, rb = og.biharmonic_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"], arrs["V"], gu, gop, act="sin")
+    for l in range(3):
+        assert rel(gW[l], rW[l]) <= 1e-9 and rel(gb[l], rb[l]) <= 1e-9
+    # one pass only: more than 84 directions are refused on the host
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    with pytest.raises(ctm.CtmError) as ei:
+        ctm.ctm_biharmonic_tape_bytes(mlp, 10, 85)
+    assert "at most 84" in str(ei.value)
+    assert ctm.ctm_biharmonic_tape_bytes(mlp, 10, 84) > 0
+    mlp.close()
+
+
+def test_autograd_wrapper_biharmonic():
+    import torch
+    import paper_2505_13644_amd as ctm
+    from paper_2505_13644_amd.autograd import biharmonic_rand
+    from oracle import gradients as og
+    dev = torch.device("cuda:0")
+    dims, N, S = (3, 24, 24, 1), 40, 4
+    Wn, bn = synth.make_mlp(dims, 13, 0.05, np.float64)
+    Ws = [torch.tensor(W, device=dev, requires_grad=True) for W in Wn]
+    bs = [torch.tensor(b, device=dev, requires_grad=True) for b in bn]
+    xn = synth.make_points(N, 3, 13, np.float64)
+    Vn = synth.make_directions("gaussian", (N, S, 3), 13, np.float64)
+    mlp = ctm.ctm_create_mlp([W.detach() for W in Ws], [b.detach() for b in bs])
+    u, op = biharmonic_rand(mlp, Ws, bs, torch.tensor(xn, device=dev), torch.tensor(Vn, device=dev))
+    loss = (op ** 2).mean() + (u ** 2).mean()
+    loss.backward()
+    gu, gop = (2 * u / N).detach().cpu().numpy(), (2 * op / N).detach().cpu().numpy()
+    _, rW, rb = og.biharmonic_loss_grads(Wn, bn, xn, Vn, gu, gop)
+    for l in range(3):
+        assert rel(Ws[l].grad.cpu().numpy(), rW[l]) <= 1e-8 and rel(bs[l].grad.cpu().numpy(), rb[l]) <= 1e-8
+    mlp.close()
