@@ -37,7 +37,8 @@
  *     aborts.  Arguments are validated on the host before any GPU work is issued, and
  *     ctm_last_error() gives a readable message for the calling thread's last failure.
  *   - A handle is immutable: concurrent operator calls on one handle are fine as long
- *     as they use distinct workspaces.
+ *     as they use distinct workspaces.  It belongs to the device that was current at
+ *     ctm_create_mlp; calls with another device current return CTM_ERR_UNSUPPORTED.
  */
 #ifndef CTM_H
 #define CTM_H

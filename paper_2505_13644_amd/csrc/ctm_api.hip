@@ -292,6 +292,16 @@ extern "C" size_t ctm_workspace_bytes_standard(const ctm_mlp *m, int K, long N, 
 namespace {
 bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
+// The handle's weights live on the device that was current at ctm_create_mlp; calls must be made with it current.
+int check_device(const ctm_mlp *m, const char *who) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev != m->device)
+    return fail(CTM_ERR_UNSUPPORTED, "%s: the handle belongs to device %d but device %d is current", who, m->device, dev);
+  return CTM_OK;
+}
+
 int run_operator(const ctm_mlp *m, int K, const void *x, long N, const void *V, int R, long sn, long sr,
                  long sd, double scale, void *u, void *op, void *ws, size_t ws_bytes, void *stream,
                  const char *who, bool standard = false) {
@@ -308,6 +318,7 @@ int run_operator(const ctm_mlp *m, int K, const void *x, long N, const void *V, 
   if (misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: workspace must be 256-byte aligned", who);
   if (misaligned(x, es) || misaligned(V, es) || misaligned(u, es) || misaligned(op, es))
     return fail(CTM_ERR_ALIGN, "%s: x, directions, u and op must be aligned to the element size", who);
+  if (int rc = check_device(m, who)) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
     return run_passes<double>(m, K, (const double *)x, N, (const double *)V, R, sn, sr, sd, scale, (double *)u,
@@ -756,6 +767,7 @@ int ctm_weighted_laplacian_rand(const ctm_mlp *m, const void *x, long N, const v
   const bool per_point = sigma_point_stride != 0 || v_point_stride != 0;
   const long Nd = per_point ? N : 1;
   const size_t dbytes = round256((size_t)Nd * S * D * es);
+  if (int rc = check_device(m, who)) return rc;
   void *dirs = (char *)ws + (need - dbytes);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   hipError_t e = (m->dtype == CTM_F64)
@@ -775,6 +787,7 @@ int ctm_update_mlp(ctm_mlp *m, const void *const *W, const void *const *b, void 
     if (misaligned(W[l], es) || (b && misaligned(b[l], es)))
       return fail(CTM_ERR_ALIGN, "ctm_update_mlp: W[%d] / b[%d] not aligned to the element size", l, l);
   }
+  if (int rc = check_device(m, "ctm_update_mlp")) return rc;
   hipError_t e = pack_everything(m, W, b, reinterpret_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "ctm_update_mlp: weight packing");
   return CTM_OK;
@@ -819,6 +832,7 @@ int recording_forward(const char *who, const ctm_mlp *m, int K, const void *x, l
   if (misaligned(tape, 256)) return fail(CTM_ERR_ALIGN, "%s: tape must be 256-byte aligned", who);
   if (misaligned(x, es) || misaligned(V, es) || misaligned(u, es) || misaligned(op, es))
     return fail(CTM_ERR_ALIGN, "%s: x, directions, u and op must be aligned to the element size", who);
+  if (int rc2 = check_device(m, who)) return rc2;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
     return run_fwd_tape<double>(m, K, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st);
@@ -839,6 +853,7 @@ int reverse_pass(const char *who, const ctm_mlp *m, int K, long N, int R, double
   for (int l = 0; l < m->L; ++l)
     if ((gW && misaligned(gW[l], es)) || (gb && misaligned(gb[l], es)))
       return fail(CTM_ERR_ALIGN, "%s: gW[%d] / gb[%d] not aligned to the element size", who, l, l);
+  if (int rc2 = check_device(m, who)) return rc2;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
     return run_bwd<double>(m, K, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st);
@@ -910,6 +925,7 @@ int ctm_biharmonic_exact(const ctm_mlp *m, const void *x, long N, void *u, void 
   if (misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: workspace must be 256-byte aligned", who);
   if (misaligned(x, es) || misaligned(u, es) || misaligned(op, es))
     return fail(CTM_ERR_ALIGN, "%s: x, u and op must be aligned to the element size", who);
+  if (int rc = check_device(m, who)) return rc;
   const int D = m->dims[0];
   // weights of the three direction families (final form of the interpolation formula, App. E.1)
   const int i22[2] = {2, 2}, j40[2] = {4, 0}, j31[2] = {3, 1}, j22[2] = {2, 2};

@@ -334,13 +334,9 @@ hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M
                         hipStream_t s) {
   const WgradPlan p = wgrad_plan(M, d_out, d_in);
   constexpr size_t lds = 4 * (size_t)kWgK * kWgPitch * sizeof(T);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void *>(&wgrad_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)lds);
-    if (ea != hipSuccess) return ea;
-    attr_set = true;
-  }
+  static LdsLimitOnce lds_limit;
+  hipError_t ea = lds_limit.ensure(reinterpret_cast<const void *>(&wgrad_kernel<T>), lds);
+  if (ea != hipSuccess) return ea;
   hipLaunchKernelGGL(wgrad_kernel<T>, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
                      p.rows_per, p.tj, partials);
   hipError_t e = hipGetLastError();

@@ -3,9 +3,26 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstddef>
 
 namespace ctm {
+
+// Raises a kernel's dynamic-LDS limit the first time it is launched on each device (the attribute belongs to
+// the device's copy of the kernel); safe to call from several threads.
+struct LdsLimitOnce {
+  std::atomic<unsigned long long> done{0};
+  hipError_t ensure(const void *kernel, size_t bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && tracked) done.fetch_or(1ull << dev, std::memory_order_release);
+    return e;
+  }
+};
 
 // Shape constants of the stacked-GEMM kernel, per storage type.
 //   KV  elements per 16-byte LDS/global vector

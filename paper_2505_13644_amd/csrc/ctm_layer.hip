@@ -267,13 +267,9 @@ void layer_kernel(const LayerArgs<T> a) {
 
 template <typename T, int MB> static hipError_t launch_one(const LayerArgs<T> &a, hipStream_t s) {
   using TL = Tile<T, MB>;
-  static bool attr_set = false;  // benign race: every thread sets the same value
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&layer_kernel<T, MB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)TL::kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce lds_limit;
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB>), TL::kLdsBytes);
+  if (e != hipSuccess) return e;
   const long n_tiles = a.n_row_tiles * a.n_col_tiles;
   const long grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
   if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;

@@ -239,13 +239,9 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
 
 template <int MB, int NSPLIT> static hipError_t launch_one_b(const LayerArgs<float> &a, hipStream_t s) {
   using TL = TileB<MB, NSPLIT>;
-  static bool attr_set = false;  // benign race: every thread sets the same value
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&layer_kernel_bf16<MB, NSPLIT>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)TL::kLdsBytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsLimitOnce lds_limit;
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel_bf16<MB, NSPLIT>), TL::kLdsBytes);
+  if (e != hipSuccess) return e;
   const long n_tiles = a.n_row_tiles * a.n_col_tiles;
   const long grid = (n_tiles + kXcdsB - 1) / kXcdsB * kXcdsB;
   if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;

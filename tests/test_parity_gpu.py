@@ -464,3 +464,40 @@ def test_sin_network_closed_form():
     np.testing.assert_allclose(gl, -(np.sin(z) * n2) @ a[0], rtol=1e-10, atol=1e-13)
     _, gb = gpu_run(arrs, "biharmonic_exact", act=ctm.CTM_ACT_SIN)
     np.testing.assert_allclose(gb, (np.sin(z) * n2 ** 2) @ a[0], rtol=1e-9, atol=1e-12)
+
+
+def test_coefficient_blocks_beyond_two_to_the_31_elements():
+    # Maximum sizes: N * rho * ld exceeds 2^31 elements, so every kernel's indexing must be 64-bit.  A small network
+    # keeps the arithmetic negligible; inputs are drawn on the device from a seeded generator, a sample of points
+    # (first, last and spread) is checked against the oracle, and a sub-batch must reproduce its points bit for bit.
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import operators as orc
+    dev = torch.device("cuda:0")
+    dims = (5, 16, 16, 1)
+    Ws, bs = synth.make_mlp(dims, 3, 0.1, np.float32)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in Ws], [t(b) for b in bs])
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    for R, N in ((None, 9_700_000), (2, 16_900_000)):
+        rho = 2 + (5 if R is None else R)
+        assert N * rho * 32 > 2 ** 31
+        print(f"case huge batch N={N} rho={rho}", flush=True)
+        x = torch.rand(N, 5, generator=g, device=dev)
+        V = None if R is None else torch.randn(N, R, 5, generator=g, device=dev)
+        u, op = ctm.ctm_laplacian(mlp, x, V, 0.5)
+        idx = np.unique(np.concatenate([np.arange(4), np.arange(N - 4, N), np.linspace(0, N - 1, 40).astype(np.int64)]))
+        ti = torch.from_numpy(idx).to(dev)
+        xs = x[ti].cpu().numpy()
+        Vs = None if V is None else V[ti].cpu().numpy()
+        ru, rop = orc.laplacian(Ws, bs, xs, Vs, 0.5)
+        eu, eo = orc.scaled_max_err(u[ti].cpu().numpy(), ru), orc.scaled_max_err(op[ti].cpu().numpy(), rop)
+        print(f"  sampled errors: u {eu:.2e} op {eo:.2e}", flush=True)
+        assert eu <= 2e-4 and eo <= 2e-4
+        tail = slice(N - 1000, N)
+        u2, op2 = ctm.ctm_laplacian(mlp, x[tail].contiguous(), None if V is None else V[tail].contiguous(), 0.5)
+        assert torch.equal(u2, u[tail]) and torch.equal(op2, op[tail])
+        del x, V, u, op
+        torch.cuda.empty_cache()
+    mlp.close()
