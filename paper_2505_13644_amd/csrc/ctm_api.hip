@@ -225,6 +225,8 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
     const PassPlan pl = plan_pass(K, Rp, standard, N, m->min_col_tiles, m->slots);
     const int last_rows = standard ? 1 + Rp : 2;
     const bool fast_first = first_layer_fast_path(m->dims[0], sn);
+    // plain-bf16 handles keep the blocks between layers as one bf16 plane; see ctm_layer_bf16.hip
+    const int bf16_blocks = m->dtype == CTM_F32_BF16 ? 1 : 0;
     const T *in = buf[1];
     int l_begin = 0;
     hipError_t e;
@@ -239,6 +241,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       fa.D = m->dims[0]; fa.ld0 = m->ld[0]; fa.ld1 = m->ld[1]; fa.rho = pl.rho; fa.order = K; fa.R = Rp;
       fa.r0 = pass * sp.first; fa.last = last ? 1 : 0; fa.act = (int)m->act;
       fa.standard = standard ? 1 : 0; fa.out_rows = last ? last_rows : pl.rho;
+      fa.out_bf16 = last ? 0 : bf16_blocks;
       e = launch_first<T>(fa, st);
       if (e != hipSuccess) return fail_hip(e, "first-layer kernel launch");
       (void)prof_mark(st, 0);
@@ -249,7 +252,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       sa.x = x; sa.V = V; sa.out = buf[1]; sa.N = N;
       sa.v_sn = sn; sa.v_sr = sr; sa.v_sd = sd;
       sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = pass * sp.first;
-      sa.standard = standard ? 1 : 0; sa.R = Rp;
+      sa.standard = standard ? 1 : 0; sa.R = Rp; sa.out_bf16 = bf16_blocks;
       e = launch_seed<T>(sa, st);
       if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
       (void)prof_mark(st, 0);
@@ -268,6 +271,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       if constexpr (std::is_same<T, float>::value) {
         if (is_bf16(m->dtype)) {
           la.Whi = m->Whi[l]; la.Wlo = m->Wlo[l];
+          la.out_bf16 = last ? 0 : bf16_blocks;
           e = launch_layer_bf16(la, pl.MB, m->dtype == CTM_F32_BF16X3 ? 3 : 1, st);
           done = true;
         }

@@ -13,6 +13,8 @@
 #include "ctm_internal.h"
 #include "ctm_rule.h"
 
+#include <type_traits>
+
 namespace ctm {
 
 // z1[r][j] = sum_k W[j][k] v_r[k].  One thread per (direction, feature).
@@ -34,7 +36,8 @@ template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
 constexpr int kFirstPoints = 16;  // points per workgroup
 constexpr int kFirstDmax = 64;    // input widths up to this are held in registers
 
-template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
+// BF = 0: out holds rows of T; BF = 1: out is written as bf16 (input of the plain-bf16 GEMM kernel).
+template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
   __shared__ T xs[kFirstPoints][kFirstDmax];
   const int tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
@@ -63,11 +66,18 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
 
   const long ld = a.ld1;
   const int rho = a.rho;
-  T *o = a.out + (n0 * a.out_rows) * ld + j;
+  const long obase = ((a.out_point0 + n0) * a.out_rows) * ld + j;
   const long pstep = (long)a.out_rows * ld;
+  auto put = [&](long off, T v) {  // off: element offset from this thread's first output element
+    if constexpr (BF == 0) {
+      a.out[obase + off] = v;
+    } else {
+      reinterpret_cast<__bf16 *>(a.out)[obase + off] = (__bf16)(float)v;
+    }
+  };
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
-    if (p < np) o[p * pstep] = t[p];
+    if (p < np) put(p * pstep, t[p]);
   T mom = T(0);  // sum_r z1_r^order, the only term of the collapsed row at the first layer
   for (int r = 0; r < a.R; ++r) {
     const T z1 = a.Z1[(long)r * ld + j];
@@ -84,13 +94,13 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
         if (p < np) {
           const T d2 = act_d2<T>(a.act, t[p], d1[p]);
           const T dK = (K == 2) ? d2 : act_d4<T>(a.act, t[p], d1[p]);
-          o[p * pstep + rowK * ld] = dK * zK;
+          put(p * pstep + rowK * ld, dK * zK);
           if (!a.last) {
-            o[p * pstep + row1 * ld] = d1[p] * z1;
+            put(p * pstep + row1 * ld, d1[p] * z1);
             if (K == 4) {
               const T d3 = act_d3<T>(a.act, t[p], d1[p]);
-              o[p * pstep + (row1 + 1) * ld] = d2 * z1s;
-              o[p * pstep + (row1 + 2) * ld] = d3 * z1s * z1;
+              put(p * pstep + (row1 + 1) * ld, d2 * z1s);
+              put(p * pstep + (row1 + 2) * ld, d3 * z1s * z1);
             }
           }
         }
@@ -98,30 +108,30 @@ template <typename T> __global__ __launch_bounds__(256) void first_layer_kernel(
     }
     if (a.last) continue;
     if (a.order == 2) {
-      T *orow = o + (long)(1 + r) * ld;
+      const long orow = (long)(1 + r) * ld;
 #pragma unroll
       for (int p = 0; p < kFirstPoints; ++p)
-        if (p < np) orow[p * pstep] = d1[p] * z1;
+        if (p < np) put(orow + p * pstep, d1[p] * z1);
     } else {
-      T *orow = o + (long)(1 + 3 * r) * ld;
+      const long orow = (long)(1 + 3 * r) * ld;
       const T z1c = z1s * z1;
 #pragma unroll
       for (int p = 0; p < kFirstPoints; ++p)
         if (p < np) {
           const T d2 = act_d2<T>(a.act, t[p], d1[p]), d3 = act_d3<T>(a.act, t[p], d1[p]);
-          orow[p * pstep] = d1[p] * z1;
-          orow[p * pstep + ld] = d2 * z1s;
-          orow[p * pstep + 2 * ld] = d3 * z1c;
+          put(orow + p * pstep, d1[p] * z1);
+          put(orow + p * pstep + ld, d2 * z1s);
+          put(orow + p * pstep + 2 * ld, d3 * z1c);
         }
     }
   }
   if (a.standard) return;  // no collapsed row
-  T *olast = o + (long)(a.last ? 1 : rho - 1) * ld;
+  const long olast = (long)(a.last ? 1 : rho - 1) * ld;
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p)
     if (p < np) {
       const T dk = (a.order == 2) ? act_d2<T>(a.act, t[p], d1[p]) : act_d4<T>(a.act, t[p], d1[p]);
-      olast[p * pstep] = dk * mom;
+      put(olast + p * pstep, dk * mom);
     }
 }
 
@@ -138,10 +148,18 @@ template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t
     const long nc = (chunks - c0) < 65535 ? (chunks - c0) : 65535;
     FirstArgs<T> b = a;
     b.x = a.x + c0 * kFirstPoints * a.D;
-    b.out = a.out + c0 * kFirstPoints * (long)a.out_rows * a.ld1;
+    b.out_point0 = c0 * kFirstPoints;
     b.N = a.N - c0 * kFirstPoints;
     if (b.N > nc * kFirstPoints) b.N = nc * kFirstPoints;
-    hipLaunchKernelGGL(first_layer_kernel<T>, dim3((a.ld1 + 255) / 256, (unsigned)nc), dim3(256), 0, s, b);
+    const dim3 grid((a.ld1 + 255) / 256, (unsigned)nc);
+    bool launched = false;
+    if constexpr (std::is_same<T, float>::value) {
+      if (a.out_bf16) { hipLaunchKernelGGL((first_layer_kernel<T, 1>), grid, dim3(256), 0, s, b); launched = true; }
+    }
+    if (!launched) {
+      if (a.out_bf16) return hipErrorInvalidValue;
+      hipLaunchKernelGGL((first_layer_kernel<T, 0>), grid, dim3(256), 0, s, b);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

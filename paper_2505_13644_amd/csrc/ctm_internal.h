@@ -68,6 +68,9 @@ template <typename T> struct LayerArgs {
   const T *Zsaved;   // bwd == 1: recorded pre-activations of the layer whose rule is reversed, [n_points * rho][ldout]
   int bwd;           // 1: Hin holds cotangents, W the transposed weights, and the epilogue is the reverse of the
                      //    order-2 collapsed rule (writes the cotangents of the pre-activations)
+  // plain-bf16 kernel only: Hin is a bf16 plane [rows][ldin]; out_bf16 != 0: Hout is one too (0: rows of T, the
+  // last hidden layer's output for the final kernel)
+  int out_bf16 = 0;
 };
 
 // Launch the stacked GEMM + fused jet rule for one layer.  MB in {4, 8, 9, 12, 13, 16}.
@@ -89,6 +92,7 @@ template <typename T> struct SeedArgs {
   int r0;       // index of this pass's first direction
   int standard; // row layout of un-collapsed Taylor mode
   int R;        // directions in this pass
+  int out_bf16 = 0;  // 0: rows of T; 1: the block is written as bf16 (same [rows][ld] indexing)
 };
 template <typename T> hipError_t launch_seed(const SeedArgs<T> &a, hipStream_t s);
 
@@ -105,6 +109,8 @@ template <typename T> struct FirstArgs {
   int D, ld0, ld1, rho, order, R, r0, last, act;
   int standard;   // un-collapsed row layout
   int out_rows;   // rows per point in out
+  int out_bf16 = 0;      // 0: rows of T; 1: out is written as bf16 (same indexing)
+  long out_point0 = 0;   // index of this launch's first point in out (x and N are already offset)
 };
 constexpr int kMaxOutputs = 1024;  // widest last layer (outputs are produced by a per-point dot-product kernel)
 bool first_layer_fast_path(int D, long v_point_stride);

@@ -6,8 +6,13 @@
 //               term, relative size 2^-16, is dropped) -- three v_mfma_f32_16x16x32_bf16 per block pair.
 //   NSPLIT = 1  plain bf16 inputs: a_hi*b_hi only.
 //
-// The coefficient block stays fp32 in HBM; the A tile is split while it is copied to LDS, the
-// weights are split once at handle creation (Whi / Wlo, [rows_pad][ld] bf16).
+// Split variant: the coefficient block stays fp32 in HBM and the A tile is split while it is copied to LDS
+// (measured faster than storing hi / lo planes, whose 2-byte stores double the epilogue's store count).
+// Plain variant: between the layers the block lives in HBM as ONE bf16 plane [rows][ld] (half the traffic):
+// every producer (the first-layer / seed kernels and this kernel's epilogue) rounds a value once, when it is
+// written, and the GEMM copies its A tile to LDS as it is.  The last hidden layer's output rows are fp32 in
+// both variants (they feed the final kernel).  The weights are split once at handle creation
+// (Whi / Wlo, [rows_pad][ld] bf16).
 //
 // MFMA use: v_mfma_f32_16x16x32_bf16.  Lane l supplies 8 consecutive k values of A row l%16 and of
 // B column l%16 (k = 8*(l/16) .. +7, the same assignment for both) and receives D rows
@@ -88,14 +93,15 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   const long p0 = row_tile * a.P;
   const int p_valid = (int)((a.n_points - p0) < a.P ? (a.n_points - p0) : a.P);
   const int rows_valid = p_valid * a.rho;
-  const float *Ag = a.Hin + p0 * a.rho * (long)a.ldin;
+  const float *Af_g = a.Hin + p0 * a.rho * (long)a.ldin;                                            // split: fp32 rows
+  const __bf16 *Ah_g = reinterpret_cast<const __bf16 *>(a.Hin) + p0 * a.rho * (long)a.ldin;        // plain: bf16 plane
   const __bf16 *Bhi = reinterpret_cast<const __bf16 *>(a.Whi) + (long)col_tile * BN * a.ldin;
   const __bf16 *Blo = reinterpret_cast<const __bf16 *>(a.Wlo) + (long)col_tile * BN * a.ldin;
 
-  // global -> LDS copy slots: 8 consecutive k values each (32 B of fp32 for A, 16 B of bf16 per weight plane);
-  // unconditional, clamped as in layer_kernel
+  // global -> LDS copy slots: 8 consecutive k values each (split: 32 B of fp32; plain: 16 B of bf16; weights: 16 B per
+  // plane); unconditional, clamped as in layer_kernel
   int a_off[TL::A_LD];
-  const float *a_src[TL::A_LD];
+  long a_src[TL::A_LD];
 #pragma unroll
   for (int i = 0; i < TL::A_LD; ++i) {
     int u = tid + i * kThreadsB;
@@ -103,7 +109,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     const int row = u / UPR, q = u % UPR;
     a_off[i] = row * PITCH + q * 8;
     const int grow = row < rows_valid ? row : rows_valid - 1;
-    a_src[i] = Ag + (long)grow * a.ldin + q * 8;
+    a_src[i] = (long)grow * a.ldin + q * 8;
   }
   int b_off[TL::B_LD];
   long b_src[TL::B_LD];
@@ -115,13 +121,18 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     b_src[i] = (long)row * a.ldin + q * 8;
   }
 
-  f32x4 ga[TL::A_LD][2];
+  f32x4 ga[SPLIT ? TL::A_LD : 1][2];
+  bf16x8 gah[SPLIT ? 1 : TL::A_LD];
   bf16x8 gbh[TL::B_LD], gbl[TL::B_LD];
   auto load_global = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < TL::A_LD; ++i) {
-      ga[i][0] = *reinterpret_cast<const f32x4 *>(a_src[i] + k0);
-      ga[i][1] = *reinterpret_cast<const f32x4 *>(a_src[i] + k0 + 4);
+      if constexpr (SPLIT) {
+        ga[i][0] = *reinterpret_cast<const f32x4 *>(Af_g + a_src[i] + k0);
+        ga[i][1] = *reinterpret_cast<const f32x4 *>(Af_g + a_src[i] + k0 + 4);
+      } else {
+        gah[i] = *reinterpret_cast<const bf16x8 *>(Ah_g + a_src[i] + k0);
+      }
     }
 #pragma unroll
     for (int i = 0; i < TL::B_LD; ++i) {
@@ -136,10 +147,14 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     __bf16 *Bh = S + TL::PLANES * TL::A_PLANE, *Bl = Bh + TL::B_PLANE;
 #pragma unroll
     for (int i = 0; i < TL::A_LD; ++i) {
-      bf16x8 hi, lo;
-      split8(ga[i][0], ga[i][1], hi, lo);
-      *reinterpret_cast<bf16x8 *>(Ah + a_off[i]) = hi;
-      if (SPLIT) *reinterpret_cast<bf16x8 *>(Al + a_off[i]) = lo;
+      if constexpr (SPLIT) {
+        bf16x8 hi, lo;
+        split8(ga[i][0], ga[i][1], hi, lo);
+        *reinterpret_cast<bf16x8 *>(Ah + a_off[i]) = hi;
+        *reinterpret_cast<bf16x8 *>(Al + a_off[i]) = lo;
+      } else {
+        *reinterpret_cast<bf16x8 *>(Ah + a_off[i]) = gah[i];
+      }
     }
 #pragma unroll
     for (int i = 0; i < TL::B_LD; ++i) {
@@ -230,9 +245,11 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     for (int p = wave; p < p_valid; p += kThreadsB / 64) {
       const float *c = Cs + (long)p * rho * CROW + j;
       const long n = p0 + p;
-      float *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
-      if (a.Zout) save_preactivations<float>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
-      jet_rule<float>(c, CROW, bias, o, a.ldout, a);
+      const long o_off = (n * a.out_rows) * a.ldout + jg;
+      if (a.out_bf16)
+        jet_rule<float, Bf16Rows>(c, CROW, bias, Bf16Rows{reinterpret_cast<__bf16 *>(a.Hout) + o_off, a.ldout}, a);
+      else
+        jet_rule<float>(c, CROW, bias, a.Hout + o_off, a.ldout, a);
     }
   }
 }

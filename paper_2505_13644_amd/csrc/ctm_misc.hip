@@ -2,6 +2,8 @@
 // block, re-packing weights at handle creation, and the last (width-1) linear layer.
 #include "ctm_internal.h"
 
+#include <type_traits>
+
 namespace ctm {
 
 // ---- input jets (Sec. 3.1: x_{0,r} = x_0, x_{1,r} = v_r, x_{k>=2,r} = 0) ---------------
@@ -30,6 +32,12 @@ template <typename T> __global__ void seed_kernel(const SeedArgs<T> a) {
           r += a.r0;
           v = a.V ? a.V[n * a.v_sn + r * a.v_sr + k * a.v_sd] : (k == r ? T(1) : T(0));
         }
+      }
+    }
+    if constexpr (std::is_same<T, float>::value) {
+      if (a.out_bf16) {
+        reinterpret_cast<__bf16 *>(a.out)[i] = (__bf16)v;
+        continue;
       }
     }
     a.out[i] = v;

@@ -48,16 +48,27 @@ template <typename T> __device__ __forceinline__ T act_d5(int act, T t, T d1) {
   return act == 0 ? d1 * (T(16) + T(120) * t2 * (t2 - T(1))) : (act == 2 ? d1 : T(0));
 }
 
-// c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows);
-// o: the pair's column in the output block (row pitch ostep elements).
-template <typename T>
-__device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, long ostep, const LayerArgs<T> &a) {
+// Where the rule's output rows go: `put(row, v)` stores the value of coefficient row `row` of the pair's column.
+template <typename T> struct PlainRows {  // rows of T, `step` elements apart
+  T *o;
+  long step;
+  __device__ __forceinline__ void put(long row, T v) const { o[row * step] = v; }
+};
+struct Bf16Rows {  // rows of bf16 (the block between the layers of a plain-bf16 handle)
+  __bf16 *o;
+  long step;
+  __device__ __forceinline__ void put(long row, float v) const { o[row * step] = (__bf16)v; }
+};
+
+// c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows).
+template <typename T, typename Out>
+__device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out &out, const LayerArgs<T> &a) {
   const int R = a.R;
   const T z0 = c[0] + bias;
   T t, d1;
   act_eval<T>(a.act, z0, t, d1);
   const T d2 = act_d2<T>(a.act, t, d1);
-  o[0] = t;
+  out.put(0, t);
   if (a.standard) {
     // un-collapsed ("standard") Taylor mode, kept for comparison: every direction carries its own
     // highest-order row (1 + K*R rows per point) and the sum over directions is taken after the last layer
@@ -66,10 +77,10 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
         const T z1 = c[(long)(1 + r) * CROW], z2 = c[(long)(1 + R + r) * CROW];
         const T h2 = d1 * z2 + d2 * z1 * z1;
         if (a.last) {
-          o[(1 + r) * ostep] = h2;
+          out.put(1 + r, h2);
         } else {
-          o[(1 + r) * ostep] = d1 * z1;
-          o[(1 + R + r) * ostep] = h2;
+          out.put(1 + r, d1 * z1);
+          out.put(1 + R + r, h2);
         }
       }
     } else {  // rows 1+4r .. 4+4r: orders 1..4 of direction r
@@ -80,13 +91,13 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
         const T z1s = z1 * z1;
         const T h4 = d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2 + d1 * z4;
         if (a.last) {
-          o[(1 + r) * ostep] = h4;
+          out.put(1 + r, h4);
         } else {
-          T *orow = o + (long)(1 + 4 * r) * ostep;
-          orow[0] = d1 * z1;
-          orow[ostep] = d2 * z1s + d1 * z2;
-          orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
-          orow[3 * ostep] = h4;
+          const long row = 1 + 4 * r;
+          out.put(row, d1 * z1);
+          out.put(row + 1, d2 * z1s + d1 * z2);
+          out.put(row + 2, d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3);
+          out.put(row + 3, h4);
         }
       }
     }
@@ -100,17 +111,17 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         s += z1[i] * z1[i];
-        if (!a.last) o[(r + i) * ostep] = d1 * z1[i];
+        if (!a.last) out.put(r + i, d1 * z1[i]);
       }
     }
     for (; r <= R; ++r) {
       const T z1 = c[(long)r * CROW];
       s += z1 * z1;
-      if (!a.last) o[r * ostep] = d1 * z1;
+      if (!a.last) out.put(r, d1 * z1);
     }
     const T z2 = c[(long)(R + 1) * CROW];
     const T h2 = d1 * z2 + d2 * s;
-    o[(a.last ? 1 : R + 1) * ostep] = h2;
+    out.put(a.last ? 1 : R + 1, h2);
   } else {
     const T d3 = act_d3<T>(a.act, t, d1), d4 = act_d4<T>(a.act, t, d1);
     T s = T(0);
@@ -120,15 +131,21 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
       const T z1s = z1 * z1;
       s += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
       if (!a.last) {
-        T *orow = o + (long)(1 + 3 * r) * ostep;
-        orow[0] = d1 * z1;
-        orow[ostep] = d2 * z1s + d1 * z2;
-        orow[2 * ostep] = d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3;
+        const long row = 1 + 3 * r;
+        out.put(row, d1 * z1);
+        out.put(row + 1, d2 * z1s + d1 * z2);
+        out.put(row + 2, d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3);
       }
     }
     const T z4 = c[(long)(3 * R + 1) * CROW];
-    o[(a.last ? 1 : 3 * R + 1) * ostep] = d1 * z4 + s;
+    out.put(a.last ? 1 : 3 * R + 1, d1 * z4 + s);
   }
+}
+
+// o: the pair's column in an output block of plain rows (row pitch ostep elements).
+template <typename T>
+__device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, long ostep, const LayerArgs<T> &a) {
+  jet_rule<T, PlainRows<T>>(c, CROW, bias, PlainRows<T>{o, ostep}, a);
 }
 
 // Record the pre-activation rows of one (point, feature) pair (bias on the order-0 row only).
