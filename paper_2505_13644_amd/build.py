@@ -21,6 +21,8 @@ FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # loop heads on 32-byte boundaries: the stacked-GEMM k loop loses ~0.7 % when it straddles fetch windows
+    "-falign-loops=32",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

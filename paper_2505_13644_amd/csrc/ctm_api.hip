@@ -267,6 +267,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       la.order = K; la.R = Rp; la.last = last ? 1 : 0; la.act = (int)m->act;
       la.standard = standard ? 1 : 0; la.out_rows = last ? last_rows : pl.rho;
       la.Whi = nullptr; la.Wlo = nullptr; la.Zout = nullptr; la.Zsaved = nullptr; la.bwd = 0;
+      la.wpp = (standard || pl.P > 2) ? 1 : 4 / pl.P;
       bool done = false;
       if constexpr (std::is_same<T, float>::value) {
         if (is_bf16(m->dtype)) {
@@ -446,6 +447,7 @@ int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R,
     la.order = K; la.R = R; la.last = last ? 1 : 0; la.act = (int)m->act; la.standard = 0;
     la.out_rows = last ? 2 : pl.rho;
     la.Zout = (T *)(tp + tl.z[i]); la.Zsaved = nullptr; la.bwd = 0;
+    la.wpp = pl.P > 2 ? 1 : 4 / pl.P;
     e = launch_layer<T>(la, pl.MB, st);
     if (e != hipSuccess) return fail_hip(e, "layer kernel launch");
     (void)prof_mark(st, 1);

@@ -68,6 +68,7 @@ template <typename T> struct LayerArgs {
   const T *Zsaved;   // bwd == 1: recorded pre-activations of the layer whose rule is reversed, [n_points * rho][ldout]
   int bwd;           // 1: Hin holds cotangents, W the transposed weights, and the epilogue is the reverse of the
                      //    order-2 collapsed rule (writes the cotangents of the pre-activations)
+  int wpp = 1;  // wavefronts sharing one point in the rule: 4 / P for tiles of 1 or 2 points (forward, collapsed), else 1
   // plain-bf16 kernel only: Hin is a bf16 plane [rows][ldin]; out_bf16 != 0: Hout is one too (0: rows of T, the
   // last hidden layer's output for the final kernel)
   int out_bf16 = 0;

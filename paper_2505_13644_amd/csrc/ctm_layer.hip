@@ -70,7 +70,10 @@ template <typename T, int MB> struct Tile {
   static constexpr int CROW = CCOLS + PADE;       // LDS row pitch of the staged C chunk
   static constexpr size_t kStageBytes = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(T);
   static constexpr size_t kCBytes = (size_t)BM * CROW * sizeof(T);
-  static constexpr size_t kLdsBytes = kStageBytes > kCBytes ? kStageBytes : kCBytes;
+  // behind them: the group sums that wavefronts sharing a point exchange (2 point slots x 4 groups x 64 columns)
+  static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
+  static constexpr size_t kRedBytes = 2 * 4 * 64 * sizeof(T);   // only allocated by the kernels that share points (WPP > 1)
+  static constexpr size_t kLdsBytes = kRedOffset + kRedBytes;
   static_assert((BN * UPR) % kThreads == 0, "B tile must split evenly over the threads");
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
 };
@@ -79,7 +82,7 @@ template <typename T, int MB> struct Tile {
 // keeps the accumulators in ordinary VGPRs and issues MFMAs on them directly; without it (512
 // registers allowed) it parks them in AGPRs and copies each block back and forth around every
 // MFMA group, which left the matrix pipe idle almost half of the time.
-template <typename T, int MB>
+template <typename T, int MB, int WPP>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void layer_kernel(const LayerArgs<T> a) {
   using TL = Tile<T, MB>;
@@ -248,33 +251,56 @@ void layer_kernel(const LayerArgs<T> a) {
     __syncthreads();
 
     const long jg = (long)col_tile * BN + nb * 64 + j;
-    if (jg >= a.ldout) continue;  // uniform per wave; barriers are outside this branch
-    const T bias = a.bias[jg];
-    for (int p = wave; p < p_valid; p += kThreads / 64) {
+    const bool col_ok = jg < a.ldout;
+    const T bias = col_ok ? a.bias[jg] : T(0);
+    const long ostep = a.ldout;
+    if constexpr (WPP == 1) {  // a wavefront per point
+      if (col_ok) {
+        for (int p = wave; p < p_valid; p += kThreads / 64) {
+          const T *c = Cs + (long)p * rho * CROW + j;
+          const long n = p0 + p;
+          T *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
+          if (a.bwd) {
+            jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg, a.ldout, o, ostep, a);
+          } else {
+            if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
+            jet_rule<T>(c, CROW, bias, o, ostep, a);
+          }
+        }
+      }
+    } else {
+      // tiles of one or two points: the point's directions are shared out over 4 or 2 wavefronts (every thread
+      // takes part: the rule holds a barrier)
+      const int p = WPP == 2 ? (wave >> 1) : 0;
+      const int sub = WPP == 2 ? (wave & 1) : wave;
+      const bool active = col_ok && p < p_valid;
       const T *c = Cs + (long)p * rho * CROW + j;
       const long n = p0 + p;
-      T *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
-      const long ostep = a.ldout;
-      if (a.bwd) {
-        jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg, a.ldout, o, ostep, a);
-      } else {
-        if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
-        jet_rule<T>(c, CROW, bias, o, ostep, a);
-      }
+      const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg, ostep};
+      T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 4 * 64 + j;
+      if (a.Zout && active && sub == 0) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
+      jet_rule<T, PlainRows<T>, WPP>(c, CROW, bias, out, a, active, sub, red);
     }
   }
 }
 
-template <typename T, int MB> static hipError_t launch_one(const LayerArgs<T> &a, hipStream_t s) {
+template <typename T, int MB, int WPP> static hipError_t launch_wpp(const LayerArgs<T> &a, hipStream_t s) {
   using TL = Tile<T, MB>;
   static LdsLimitOnce lds_limit;
-  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB>), TL::kLdsBytes);
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB, WPP>), TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0));
   if (e != hipSuccess) return e;
   const long n_tiles = a.n_row_tiles * a.n_col_tiles;
   const long grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
   if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((layer_kernel<T, MB>), dim3((unsigned)grid), dim3(kThreads), TL::kLdsBytes, s, a);
+  hipLaunchKernelGGL((layer_kernel<T, MB, WPP>), dim3((unsigned)grid), dim3(kThreads), TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0), s, a);
   return hipGetLastError();
+}
+
+// wpp wavefronts share a point in the rule (tiles of 1 or 2 points; forward, collapsed mode only)
+template <typename T, int MB> static hipError_t launch_one(const LayerArgs<T> &a, hipStream_t s) {
+  if (a.wpp == 1) return launch_wpp<T, MB, 1>(a, s);
+  if (a.bwd || a.standard || a.P * a.wpp != 4) return hipErrorInvalidValue;
+  return a.wpp == 2 ? launch_wpp<T, MB, 2>(a, s) : launch_wpp<T, MB, 4>(a, s);
 }
 
 bool row_blocks_supported(int MB) {

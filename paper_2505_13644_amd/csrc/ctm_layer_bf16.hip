@@ -49,7 +49,10 @@ template <int MB, int NSPLIT> struct TileB {
   static constexpr int NSTAGE = NSPLIT == 3 ? 1 : 2;
   static constexpr size_t kStageBytes = NSTAGE * (size_t)STAGE * 2;
   static constexpr size_t kCBytes = (size_t)BM * CROW * 4;
-  static constexpr size_t kLdsBytes = kStageBytes > kCBytes ? kStageBytes : kCBytes;
+  // behind them: the group sums that wavefronts sharing a point exchange (2 point slots x 4 groups x 64 columns)
+  static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
+  static constexpr size_t kRedBytes = 2 * 4 * 64 * sizeof(float);   // only allocated by the kernels that share points (WPP > 1)
+  static constexpr size_t kLdsBytes = kRedOffset + kRedBytes;
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
 };
 
@@ -64,7 +67,7 @@ __device__ __forceinline__ void split8(const f32x4 &x0, const f32x4 &x1, bf16x8 
   }
 }
 
-template <int MB, int NSPLIT>
+template <int MB, int NSPLIT, int WPP>
 __global__ __launch_bounds__(kThreadsB) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void layer_kernel_bf16(const LayerArgs<float> a) {
   using TL = TileB<MB, NSPLIT>;
@@ -223,7 +226,6 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   // ---- epilogue: 64 output columns at a time.  Chunk c holds the columns of the waves with wc == c.
   const int rho = a.rho;
   const int j = tid & 63;
-#pragma unroll
   for (int chunk = 0; chunk < 2; ++chunk) {
     if (chunk > 0) __syncthreads();
     if (wc == chunk) {
@@ -240,30 +242,45 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     }
     __syncthreads();
     const long jg = (long)col_tile * BN + chunk * 64 + j;
-    if (jg >= a.ldout) continue;
-    const float bias = a.bias[jg];
-    for (int p = wave; p < p_valid; p += kThreadsB / 64) {
-      const float *c = Cs + (long)p * rho * CROW + j;
-      const long n = p0 + p;
+    const bool col_ok = jg < a.ldout;
+    const float bias = col_ok ? a.bias[jg] : 0.f;
+    auto rule = [&](const float *c, long n, bool active, int sub, float *red) {
       const long o_off = (n * a.out_rows) * a.ldout + jg;
       if (a.out_bf16)
-        jet_rule<float, Bf16Rows>(c, CROW, bias, Bf16Rows{reinterpret_cast<__bf16 *>(a.Hout) + o_off, a.ldout}, a);
+        jet_rule<float, Bf16Rows, WPP>(c, CROW, bias, Bf16Rows{reinterpret_cast<__bf16 *>(a.Hout) + o_off, a.ldout}, a, active, sub, red);
       else
-        jet_rule<float>(c, CROW, bias, a.Hout + o_off, a.ldout, a);
+        jet_rule<float, PlainRows<float>, WPP>(c, CROW, bias, PlainRows<float>{a.Hout + o_off, a.ldout}, a, active, sub, red);
+    };
+    if constexpr (WPP == 1) {  // a wavefront per point
+      if (col_ok)
+        for (int p = wave; p < p_valid; p += kThreadsB / 64)
+          rule(Cs + (long)p * rho * CROW + j, p0 + p, true, 0, nullptr);
+    } else {  // one or two points per tile: 4 or 2 wavefronts share a point's directions (see jet_rule)
+      const int p = WPP == 2 ? (wave >> 1) : 0;
+      const int sub = WPP == 2 ? (wave & 1) : wave;
+      const bool active = col_ok && p < p_valid;
+      float *red = reinterpret_cast<float *>(lds_raw + TL::kRedOffset) + p * 4 * 64 + j;
+      rule(Cs + (long)p * rho * CROW + j, p0 + p, active, sub, red);
     }
   }
 }
 
-template <int MB, int NSPLIT> static hipError_t launch_one_b(const LayerArgs<float> &a, hipStream_t s) {
+template <int MB, int NSPLIT, int WPP> static hipError_t launch_wpp_b(const LayerArgs<float> &a, hipStream_t s) {
   using TL = TileB<MB, NSPLIT>;
   static LdsLimitOnce lds_limit;
-  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel_bf16<MB, NSPLIT>), TL::kLdsBytes);
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel_bf16<MB, NSPLIT, WPP>), TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0));
   if (e != hipSuccess) return e;
   const long n_tiles = a.n_row_tiles * a.n_col_tiles;
   const long grid = (n_tiles + kXcdsB - 1) / kXcdsB * kXcdsB;
   if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((layer_kernel_bf16<MB, NSPLIT>), dim3((unsigned)grid), dim3(kThreadsB), TL::kLdsBytes, s, a);
+  hipLaunchKernelGGL((layer_kernel_bf16<MB, NSPLIT, WPP>), dim3((unsigned)grid), dim3(kThreadsB), TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0), s, a);
   return hipGetLastError();
+}
+
+template <int MB, int NSPLIT> static hipError_t launch_one_b(const LayerArgs<float> &a, hipStream_t s) {
+  if (a.wpp == 1) return launch_wpp_b<MB, NSPLIT, 1>(a, s);
+  if (a.bwd || a.standard || a.P * a.wpp != 4) return hipErrorInvalidValue;
+  return a.wpp == 2 ? launch_wpp_b<MB, NSPLIT, 2>(a, s) : launch_wpp_b<MB, NSPLIT, 4>(a, s);
 }
 
 template <int NSPLIT> static hipError_t dispatch_b(const LayerArgs<float> &a, int MB, hipStream_t s) {

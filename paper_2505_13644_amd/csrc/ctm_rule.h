@@ -61,17 +61,30 @@ struct Bf16Rows {  // rows of bf16 (the block between the layers of a plain-bf16
 };
 
 // c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows).
-template <typename T, typename Out>
-__device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out &out, const LayerArgs<T> &a) {
+//
+// The sum over directions is always taken the same way: direction i (counted from 0) belongs to group i % 4, each
+// group is summed in order of i, and the four group sums are combined as (g0 + g1) + (g2 + g3).  WPP wavefronts
+// (1, 2 or 4) share a point: wavefront `sub` takes the groups sub, sub + WPP, ... and writes their per-direction rows;
+// for WPP > 1 the group sums meet in LDS (`red`: this pair's first slot, group stride 64 elements) and wavefront 0
+// writes the collapsed row.  The result is therefore bit-identical for every WPP, i.e. for every tile shape.
+// With WPP > 1 every thread of the workgroup must make the call (it holds a barrier); threads without a valid
+// pair pass active = false.  Un-collapsed (standard) mode has no sum and is only built for WPP = 1.
+template <typename T, typename Out, int WPP = 1>
+__device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out &out, const LayerArgs<T> &a, bool active = true,
+                                         int sub = 0, T *red = nullptr) {
+  constexpr int NG = 4 / WPP;  // groups per wavefront
   const int R = a.R;
-  const T z0 = c[0] + bias;
-  T t, d1;
-  act_eval<T>(a.act, z0, t, d1);
-  const T d2 = act_d2<T>(a.act, t, d1);
-  out.put(0, t);
+  T t = T(0), d1 = T(0), d2 = T(0);
+  if (active) {
+    const T z0 = c[0] + bias;
+    act_eval<T>(a.act, z0, t, d1);
+    d2 = act_d2<T>(a.act, t, d1);
+    if (sub == 0) out.put(0, t);
+  }
   if (a.standard) {
     // un-collapsed ("standard") Taylor mode, kept for comparison: every direction carries its own
     // highest-order row (1 + K*R rows per point) and the sum over directions is taken after the last layer
+    if (!active) return;
     if (a.order == 2) {  // rows 1..R first order, R+1..2R second order
       for (int r = 0; r < R; ++r) {
         const T z1 = c[(long)(1 + r) * CROW], z2 = c[(long)(1 + R + r) * CROW];
@@ -101,42 +114,72 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
         }
       }
     }
-  } else if (a.order == 2) {
-    T s = T(0);
-    int r = 1;
-    for (; r + 3 <= R; r += 4) {  // four independent LDS reads in flight per trip
-      T z1[4];
+    return;
+  }
+  T sg[NG];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) z1[i] = c[(long)(r + i) * CROW];
+  for (int k = 0; k < NG; ++k) sg[k] = T(0);
+  T d3 = T(0), d4 = T(0);
+  if (a.order == 2) {
+    if (active) {
+      int i0 = 0;
+      for (; i0 + 3 < R; i0 += 4) {  // NG independent LDS reads in flight per trip
+        T z1[NG];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        s += z1[i] * z1[i];
-        if (!a.last) out.put(r + i, d1 * z1[i]);
+        for (int k = 0; k < NG; ++k) z1[k] = c[(long)(1 + i0 + sub + k * WPP) * CROW];
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+          sg[k] += z1[k] * z1[k];
+          if (!a.last) out.put(1 + i0 + sub + k * WPP, d1 * z1[k]);
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < NG; ++k) {
+        const int i = i0 + sub + k * WPP;
+        if (i < R) {
+          const T z1 = c[(long)(1 + i) * CROW];
+          sg[k] += z1 * z1;
+          if (!a.last) out.put(1 + i, d1 * z1);
+        }
       }
     }
-    for (; r <= R; ++r) {
-      const T z1 = c[(long)r * CROW];
-      s += z1 * z1;
-      if (!a.last) out.put(r, d1 * z1);
+  } else if (active) {
+    d3 = act_d3<T>(a.act, t, d1);
+    d4 = act_d4<T>(a.act, t, d1);
+    for (int i0 = 0; i0 < R; i0 += 4) {
+#pragma unroll
+      for (int k = 0; k < NG; ++k) {
+        const int i = i0 + sub + k * WPP;
+        if (i < R) {
+          const T *cr = c + (long)(1 + 3 * i) * CROW;
+          const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW];
+          const T z1s = z1 * z1;
+          sg[k] += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
+          if (!a.last) {
+            const long row = 1 + 3 * i;
+            out.put(row, d1 * z1);
+            out.put(row + 1, d2 * z1s + d1 * z2);
+            out.put(row + 2, d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3);
+          }
+        }
+      }
     }
-    const T z2 = c[(long)(R + 1) * CROW];
-    const T h2 = d1 * z2 + d2 * s;
-    out.put(a.last ? 1 : R + 1, h2);
+  }
+  T s;
+  if constexpr (WPP == 1) {
+    if (!active) return;
+    s = (sg[0] + sg[1]) + (sg[2] + sg[3]);
   } else {
-    const T d3 = act_d3<T>(a.act, t, d1), d4 = act_d4<T>(a.act, t, d1);
-    T s = T(0);
-    for (int r = 0; r < R; ++r) {
-      const T *cr = c + (long)(1 + 3 * r) * CROW;
-      const T z1 = cr[0], z2 = cr[CROW], z3 = cr[2 * CROW];
-      const T z1s = z1 * z1;
-      s += d4 * z1s * z1s + T(6) * d3 * z1s * z2 + T(4) * d2 * z1 * z3 + T(3) * d2 * z2 * z2;
-      if (!a.last) {
-        const long row = 1 + 3 * r;
-        out.put(row, d1 * z1);
-        out.put(row + 1, d2 * z1s + d1 * z2);
-        out.put(row + 2, d3 * z1s * z1 + T(3) * d2 * z1 * z2 + d1 * z3);
-      }
-    }
+#pragma unroll
+    for (int k = 0; k < NG; ++k) red[(sub + k * WPP) * 64] = sg[k];
+    __syncthreads();
+    if (!active || sub != 0) return;
+    s = (red[0] + red[64]) + (red[128] + red[192]);
+  }
+  if (a.order == 2) {
+    const T z2 = c[(long)(R + 1) * CROW];
+    out.put(a.last ? 1 : R + 1, d1 * z2 + d2 * s);
+  } else {
     const T z4 = c[(long)(3 * R + 1) * CROW];
     out.put(a.last ? 1 : 3 * R + 1, d1 * z4 + s);
   }
@@ -145,7 +188,7 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
 // o: the pair's column in an output block of plain rows (row pitch ostep elements).
 template <typename T>
 __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, long ostep, const LayerArgs<T> &a) {
-  jet_rule<T, PlainRows<T>>(c, CROW, bias, PlainRows<T>{o, ostep}, a);
+  jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{o, ostep}, a);
 }
 
 // Record the pre-activation rows of one (point, feature) pair (bias on the order-0 row only).

@@ -501,3 +501,40 @@ def test_coefficient_blocks_beyond_two_to_the_31_elements():
         del x, V, u, op
         torch.cuda.empty_cache()
     mlp.close()
+
+
+@pytest.mark.parametrize("op_name", ["laplacian", "biharmonic_rand"])
+def test_results_do_not_depend_on_the_tile_shape(op_name):
+    # rho = 62 rows per point: a large batch runs tiles of 4 points (a wavefront per point in the rule), a small one
+    # tiles of 1 point whose directions are shared out over 4 wavefronts.  The direction sum is grouped the same
+    # way in both, so a point's result is the same bit pattern in either batch.
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import operators as orc
+    dev = torch.device("cuda:0")
+    D = 60 if op_name == "laplacian" else 6
+    dims = (D, 128, 128, 1)
+    Ws, bs = synth.make_mlp(dims, 4, 0.1, np.float32)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in Ws], [t(b) for b in bs])
+    N = 4096
+    x = synth.make_points(N, D, 4, np.float32)
+    if op_name == "laplacian":
+        V = None
+        call = lambda xs, Vs: ctm.ctm_laplacian(mlp, xs, None)
+    else:
+        V = synth.make_directions("gaussian", (N, 20, D), 4, np.float32)   # 2 + 3 * 20 = 62 rows
+        call = lambda xs, Vs: ctm.ctm_biharmonic_rand(mlp, xs, Vs)
+    xt, Vt = t(x), None if V is None else t(V)
+    u, op = call(xt, Vt)
+    for n_small in (1, 64, 700):
+        u2, op2 = call(xt[:n_small].contiguous(), None if Vt is None else Vt[:n_small].contiguous())
+        assert torch.equal(u2, u[:n_small]) and torch.equal(op2, op[:n_small]), n_small
+    idx = np.arange(0, N, 173)
+    if op_name == "laplacian":
+        ru, rop = orc.laplacian(Ws, bs, x[idx], None, 1.0, mode="directional")
+    else:
+        ru, rop = orc.biharmonic_rand(Ws, bs, x[idx], V[idx])
+    assert orc.scaled_max_err(u.cpu().numpy()[idx], ru) <= 2e-4
+    assert orc.scaled_max_err(op.cpu().numpy()[idx], rop) <= 2e-4
+    mlp.close()
