@@ -91,6 +91,21 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.ctm_biharmonic_rand(None, None, 4, None, 5, 0, None, None, None, 0, None) == -1
     assert L.ctm_workspace_bytes(None, 2, 4, 5) == 0
     assert L.ctm_destroy_mlp(None) == 0
+    # every other entry point that takes a handle: NULL is an error reported on the host, never a crash
+    assert L.ctm_weighted_laplacian_rand(None, None, 4, None, 5, 0, None, 0, 0, None, None, None, 0, None) == -1
+    assert L.ctm_biharmonic_exact(None, None, 4, None, None, None, 0, None) == -1
+    assert L.ctm_taylor_standard(None, 2, None, 4, None, 5, 0, 1.0, None, None, None, 0, None) == -1
+    assert L.ctm_taylor_standard(None, 3, None, 4, None, 5, 0, 1.0, None, None, None, 0, None) == -4
+    assert L.ctm_laplacian_fwd(None, None, 4, None, 5, 0, 1.0, None, None, None, 0, None) == -1
+    assert L.ctm_laplacian_bwd(None, 4, 5, 1.0, None, 0, None, None, None, None, None, 0, None) == -1
+    assert L.ctm_biharmonic_rand_fwd(None, None, 4, None, 5, 0, None, None, None, 0, None) == -1
+    assert L.ctm_biharmonic_rand_bwd(None, 4, 5, None, 0, None, None, None, None, None, 0, None) == -1
+    assert L.ctm_update_mlp(None, None, None, None) == -1
+    for fn in (L.ctm_tape_bytes, L.ctm_backward_workspace_bytes, L.ctm_biharmonic_tape_bytes, L.ctm_biharmonic_backward_workspace_bytes):
+        assert fn(None, 4, 5) == 0
+    assert L.ctm_biharmonic_exact_workspace_bytes(None, 4) == 0
+    assert L.ctm_workspace_bytes_standard(None, 2, 4, 5) == 0
+    assert L.ctm_weighted_laplacian_rand_workspace_bytes(None, 4, 5, 3, 0, 0) == 0
     with pytest.raises(B.CtmError):
         B.ctm_tile_plan(B.CTM_F32, 3, 5)
     with pytest.raises(B.CtmError):
