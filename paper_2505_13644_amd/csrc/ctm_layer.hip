@@ -15,7 +15,8 @@
 // the accumulators are staged through LDS (64 columns at a time) and each thread then walks
 // the rows of one (point, feature) pair, keeping the running sums in registers.
 // LDS per workgroup stays below 80 KiB for fp32 so that two workgroups share a CU and one's
-// epilogue, barriers and first loads overlap with the other's MFMAs.
+// epilogue, barriers and first loads overlap with the other's MFMAs.  The A and B tiles of a k-block
+// reach LDS by LDS-direct loads (no register staging), double-buffered one k-block ahead.
 //
 // MFMA use: v_mfma_{f32,f64}_16x16x4.  Lane l supplies A[row l%16][k l/16] and
 // B[k l/16][col l%16]; it receives four elements of column l%16 of D, in rows
@@ -59,13 +60,10 @@ template <typename T, int MB> struct Tile {
   static constexpr int NB = Shape<T>::NB;
   static constexpr int BM = 16 * MB;
   static constexpr int BN = 64 * NB;
-  static constexpr int PADE = 16 / sizeof(T);     // 16 bytes of padding per LDS row
-  static constexpr int LROW = BK + PADE;          // LDS row pitch of a stage, elements
-  static constexpr int UPR = BK / KV;             // 16-byte units per stage row (= 4)
+  static constexpr int PADE = 16 / sizeof(T);     // 16 bytes of padding per row of the staged C chunk
+  static constexpr int LROW = BK;                 // LDS row pitch of a stage, elements: 64 bytes, no padding (LDS-direct loads)
   static constexpr int A_STAGE = BM * LROW;
   static constexpr int B_STAGE = BN * LROW;
-  static constexpr int A_LD = (BM * UPR + kThreads - 1) / kThreads;
-  static constexpr int B_LD = (BN * UPR) / kThreads;
   static constexpr int CCOLS = 64;                // the C tile is staged 64 columns at a time
   static constexpr int CROW = CCOLS + PADE;       // LDS row pitch of the staged C chunk
   static constexpr size_t kStageBytes = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(T);
@@ -74,7 +72,7 @@ template <typename T, int MB> struct Tile {
   static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
   static constexpr size_t kRedBytes = 2 * 4 * 64 * sizeof(T);   // only allocated by the kernels that share points (WPP > 1)
   static constexpr size_t kLdsBytes = kRedOffset + kRedBytes;
-  static_assert((BN * UPR) % kThreads == 0, "B tile must split evenly over the threads");
+  static_assert(BK * sizeof(T) == 64 && BN % 16 == 0, "a 16-row chunk of a stage is one 1 KiB LDS-direct load");
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
 };
 
@@ -89,7 +87,7 @@ void layer_kernel(const LayerArgs<T> a) {
   using vld = typename Vec<T>::ld;
   using vacc = typename Vec<T>::acc;
   constexpr int KV = TL::KV, BK = TL::BK, NB = TL::NB, BN = TL::BN;
-  constexpr int LROW = TL::LROW, UPR = TL::UPR, CROW = TL::CROW;
+  constexpr int LROW = TL::LROW, CROW = TL::CROW;
 
   extern __shared__ __align__(16) unsigned char lds_raw[];
   T *lds = reinterpret_cast<T *>(lds_raw);
@@ -120,49 +118,49 @@ void layer_kernel(const LayerArgs<T> a) {
   const T *Ag = a.Hin + p0 * a.rho * (long)a.ldin;
   const T *Bg = a.W + (long)col_tile * BN * a.ldin;
 
-  // ---- per-thread global->LDS copy slots (16 bytes each).  Every slot is loaded and stored
-  // unconditionally, so the k loop has no branches and the loads stay in flight across the
-  // MFMAs: a slot past the end of the tile repeats the tile's last slot (same value to the same
-  // LDS address), and a row past the tile's last valid row re-reads that last valid row.  Such
-  // rows only feed accumulator rows the epilogue never looks at (MFMA rows do not mix).
-  int a_off[TL::A_LD];
-  const T *a_src[TL::A_LD];
+  // ---- global -> LDS by LDS-direct loads (global_load_lds_dwordx4): every lane names its own 16 global bytes and
+  // the wave's 1 KiB lands at LDS address M0 + 16 * lane, without passing through registers.  A stage row is 64 bytes
+  // (BK elements, unpadded), so one instruction moves a chunk of 16 rows: lane l brings row l/4 of the chunk, and the
+  // row's four 16-byte units are stored XOR-swizzled with bits 2..3 of the row, which makes the fragment reads below
+  // (16 lanes = 16 rows of one unit) hit 16 different bank groups.  Chunks 0..MB-1 are the A tile, MB..MB+BN/16-1 the
+  // B tile; wave w takes chunks w, w+4, ...  Rows past the tile's last valid row re-read that row: they only feed
+  // accumulator rows the epilogue never looks at (MFMA rows do not mix).  The loads are unconditional per wave, so
+  // the k loop stays branch-free apart from the uniform chunk-count test.
+  constexpr int kChunks = MB + BN / 16;
+  constexpr int NCH = (kChunks + 3) / 4;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const T *c_src[NCH];
+  unsigned c_off[NCH];   // byte offset inside buffer 0; buffer 1 adds the stage size of the operand
+  unsigned c_step[NCH];  // bytes from buffer 0 to buffer 1 for this chunk's operand
 #pragma unroll
-  for (int i = 0; i < TL::A_LD; ++i) {
-    int u = tid + i * kThreads;
-    u = u < TL::BM * UPR ? u : TL::BM * UPR - 1;
-    const int row = u / UPR, kq = u % UPR;
-    a_off[i] = row * LROW + kq * KV;
-    const int grow = row < rows_valid ? row : rows_valid - 1;
-    a_src[i] = Ag + (long)grow * a.ldin + kq * KV;
+  for (int i = 0; i < NCH; ++i) {
+    const int c = wave_u + 4 * i;
+    const int rr = lane >> 2;                       // row inside the chunk
+    const int uu = (lane & 3) ^ ((rr >> 2) & 3);    // the unit this lane's LDS slot holds
+    if (c < MB) {
+      const int row = c * 16 + rr;
+      const int grow = row < rows_valid ? row : rows_valid - 1;
+      c_src[i] = Ag + (long)grow * a.ldin + uu * KV;
+      c_off[i] = (unsigned)(c * 16 * BK * sizeof(T));
+      c_step[i] = (unsigned)(TL::A_STAGE * sizeof(T));
+    } else {
+      const int cb = c < kChunks ? c - MB : 0;
+      c_src[i] = Bg + (long)(cb * 16 + rr) * a.ldin + uu * KV;
+      c_off[i] = (unsigned)((2 * TL::A_STAGE + cb * 16 * BK) * sizeof(T));
+      c_step[i] = (unsigned)(TL::B_STAGE * sizeof(T));
+    }
   }
-  int b_off[TL::B_LD];
-  const T *b_src[TL::B_LD];
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
+  auto issue = [&](int buf, int k0) {
 #pragma unroll
-  for (int i = 0; i < TL::B_LD; ++i) {
-    const int u = tid + i * kThreads;
-    const int row = u / UPR, kq = u % UPR;
-    b_off[i] = row * LROW + kq * KV;
-    b_src[i] = Bg + (long)row * a.ldin + kq * KV;
-  }
-
-  // Two register sets for the global->LDS copies: while k-block kt is being multiplied, k-block
-  // kt+1 sits in one set (fetched a whole stage earlier) and k-block kt+2 is being fetched into
-  // the other.
-  vld ga[2][TL::A_LD], gb[2][TL::B_LD];
-  auto load_global = [&](int set, int k0) {
-#pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) ga[set][i] = *reinterpret_cast<const vld *>(a_src[i] + k0);
-#pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) gb[set][i] = *reinterpret_cast<const vld *>(b_src[i] + k0);
-  };
-  auto store_lds = [&](int stage, int set) {
-    T *Ad = As + stage * TL::A_STAGE;
-    T *Bd = Bs + stage * TL::B_STAGE;
-#pragma unroll
-    for (int i = 0; i < TL::A_LD; ++i) *reinterpret_cast<vld *>(Ad + a_off[i]) = ga[set][i];
-#pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) *reinterpret_cast<vld *>(Bd + b_off[i]) = gb[set][i];
+    for (int i = 0; i < NCH; ++i) {
+      if (wave_u + 4 * i < kChunks) {
+        const unsigned off = lds_base + c_off[i] + buf * c_step[i];
+        const T *g = c_src[i] + k0;
+        // M0 carries the LDS byte address; the compiler does not model this load, so the waits below are explicit
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(off) : "memory");
+      }
+    }
   };
 
   vacc acc[MB][NB];
@@ -173,50 +171,45 @@ void layer_kernel(const LayerArgs<T> a) {
 
   // ---- k loop.  A stage is one k-block of BK = 4*KV values, i.e. MB steps of NB*KV MFMAs (one A
   // fragment against the NB B fragments).  The loop body covers two stages so that every LDS
-  // buffer, register set and fragment slot is a compile-time choice.  Within a stage:
-  //   * the global loads for the k-block two stages ahead are issued first;
-  //   * at step kWriteStep the k-block one stage ahead (already in registers) goes to the other
-  //     LDS buffer -- every wave finished reading that buffer before the previous barrier;
+  // buffer and fragment slot is a compile-time choice.  Within a stage:
+  //   * the LDS-direct loads of the next k-block are issued first, into the other buffer -- every wave
+  //     finished reading that buffer before the previous barrier;
   //   * every step fetches the next step's A fragment before issuing its own MFMAs;
-  //   * the last step waits for this wave's LDS traffic, passes the barrier (after which the other
+  //   * the last step waits for this wave's loads (vmcnt), passes the barrier (after which the other
   //     buffer is complete) and fetches the first fragments of the next stage, so they arrive
   //     while the last MFMAs of this stage execute.
   static_assert(BK == 4 * KV, "one k-group per stage");
-  constexpr int kWriteStep = 2;
-  static_assert(kWriteStep < MB - 1, "the LDS write must precede the stage's barrier step");
   const int npairs = a.ldin / (2 * BK);  // ldin is a multiple of 32, so the stage count is even
-  const T *Ar = As + lr * LROW + lg * KV;
-  const T *Br = Bs + (wave * 16 + lr) * LROW + lg * KV;  // + nb * 64 rows
+  const int lgs = lg ^ ((lr >> 2) & 3);  // 16-byte units of a row are stored XOR-swizzled: conflict-free fragment reads
+  const T *Ar = As + lr * LROW + lgs * KV;
+  const T *Br = Bs + (wave * 16 + lr) * LROW + lgs * KV;  // + nb * 64 rows
   vld bf[2][NB], af[2];
 
-  load_global(0, 0);
-  load_global(1, BK);
-  store_lds(0, 0);
+  issue(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Br + nb * 64 * LROW);
   af[0] = *reinterpret_cast<const vld *>(Ar);
 
-  // The body is branch-free: the last pair fetches and stores its own k-blocks once more (unused)
-  // rather than skipping, because a conditional load would make the compiler wait for *all*
-  // outstanding loads at the LDS write.
-  const int k_last = a.ldin - 2 * BK;
+  const int k_last = a.ldin - BK;
   for (int kp = 0; kp < npairs; ++kp) {
-    const int k_next = (2 * kp + 2) * BK < k_last ? (2 * kp + 2) * BK : k_last;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      // stage `half` reads LDS buffer `half`; set 1-half holds the next k-block; set half is free
-      load_global(half, k_next + half * BK);
+      // stage `half` reads LDS buffer `half`; the next k-block goes straight to the other buffer, which every wave
+      // finished reading before the previous barrier (the very last stage re-fetches its own block, unused)
+      const int k_next = (2 * kp + half + 1) * BK < k_last ? (2 * kp + half + 1) * BK : k_last;
+      issue(half ^ 1, k_next);
       const T *Ac = Ar + half * TL::A_STAGE;
       const T *An = Ar + (half ^ 1) * TL::A_STAGE;
       const T *Bn = Br + (half ^ 1) * TL::B_STAGE;
 #pragma unroll
       for (int st = 0; st < MB; ++st) {
         const int s = half * MB + st;  // fragment slot parity runs across both stages
-        if (st == kWriteStep) store_lds(half ^ 1, half ^ 1);
         if (st + 1 < MB) {
           af[(s + 1) & 1] = *reinterpret_cast<const vld *>(Ac + (st + 1) * 16 * LROW);
         } else {
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of the next stage has landed
           __syncthreads();
           af[(s + 1) & 1] = *reinterpret_cast<const vld *>(An);
 #pragma unroll
@@ -231,8 +224,8 @@ void layer_kernel(const LayerArgs<T> a) {
       }
     }
   }
-  // Each wave's last real fragment read completed before it entered the final barrier above, so the
-  // stages can be reused for the C tile right away (the fragments fetched after that barrier are unused).
+  // Each wave's last real fragment read and its last (surplus) loads completed before it entered the final barrier
+  // above, so the stages can be reused for the C tile right away (the fragments fetched after that barrier are unused).
 
   // ---- epilogue, 64 output columns at a time (wave w holds columns nb*64 + w*16 .. +15 of the
   // tile in acc[.][nb]): stage that chunk of the accumulators through LDS, then apply the
