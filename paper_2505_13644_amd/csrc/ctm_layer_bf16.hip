@@ -34,7 +34,9 @@ template <int MB, int NSPLIT> struct TileB {
   static constexpr int AROWS = 2 * MBH * 16;      // LDS rows of the A planes; rows >= 16*MB are never written
   static constexpr int BM = 16 * MB;
   static constexpr int BN = 128, BK = 32;
-  static constexpr int PITCH = BK + 8;            // bf16 elements per LDS row: 64 B of k + 16 B pad
+  // bf16 elements per LDS row.  Split: 64 B of k + 16 B pad (rows are written from registers).  Plain: 64 B,
+  // unpadded and XOR-swizzled, because the rows arrive by LDS-direct loads (16 rows = 1 KiB per wave instruction).
+  static constexpr int PITCH = NSPLIT == 3 ? BK + 8 : BK;
   static constexpr int PLANES = NSPLIT == 3 ? 2 : 1;
   static constexpr int A_PLANE = AROWS * PITCH;
   static constexpr int B_PLANE = BN * PITCH;
@@ -166,6 +168,43 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     }
   };
 
+  // Plain variant: both operands are bf16 in HBM, so a k-block goes straight to LDS by LDS-direct loads
+  // (global_load_lds_dwordx4: lane l of a wave brings row l/4, 16-byte unit (l%4) ^ ((l/4 >> 2) & 3) of a 16-row chunk to
+  // LDS address M0 + 16*l).  Chunks 0..MB-1 are the A tile, MB..MB+7 the B tile; wave w takes chunks w, w+4, ...
+  constexpr int kChunks = MB + BN / 16;
+  constexpr int NCH = (kChunks + 3) / 4;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const __bf16 *c_src[NCH];
+  unsigned c_off[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = wave_u + 4 * i;
+    const int rr = lane >> 2;
+    const int uu = (lane & 3) ^ ((rr >> 2) & 3);
+    if (c < MB) {
+      const int row = c * 16 + rr;
+      const int grow = row < rows_valid ? row : rows_valid - 1;
+      c_src[i] = Ah_g + (long)grow * a.ldin + uu * 8;
+      c_off[i] = (unsigned)(c * 16 * PITCH * 2);
+    } else {
+      const int cb = c < kChunks ? c - MB : 0;
+      c_src[i] = Bhi + (long)(cb * 16 + rr) * a.ldin + uu * 8;
+      c_off[i] = (unsigned)((TL::A_PLANE + cb * 16 * PITCH) * 2);
+    }
+  }
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
+  auto issue = [&](int stage, int k0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      if (wave_u + 4 * i < kChunks) {
+        const unsigned off = lds_base + c_off[i] + (unsigned)(stage * TL::STAGE * 2);
+        const __bf16 *g = c_src[i] + k0;
+        // M0 carries the LDS byte address; the compiler does not model this load, so the waits are explicit
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(off) : "memory");
+      }
+    }
+  };
+
   f32x4 acc[MBH][4];
 #pragma unroll
   for (int m = 0; m < MBH; ++m)
@@ -173,19 +212,26 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     for (int nb = 0; nb < 4; ++nb) acc[m][nb] = f32x4{0, 0, 0, 0};
 
   const int nk = a.ldin / BK;
-  load_global(0);
-  store_lds(0);
+  if constexpr (SPLIT) {
+    load_global(0);
+    store_lds(0);
+  } else {
+    issue(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
   __syncthreads();
+  const int lgs = SPLIT ? lg : (lg ^ ((lr >> 2) & 3));  // plain: swizzled unit (rows lr and 16*m + lr share bits 2..3)
 
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = TL::NSTAGE == 2 ? (kt & 1) : 0;
     const int k_next = (kt + 1 < nk) ? (kt + 1) * BK : kt * BK;   // last stage re-fetches itself (unused)
-    load_global(k_next);
+    if constexpr (SPLIT) load_global(k_next);
+    else issue(stage ^ 1, k_next);   // every wave finished reading that stage before the previous barrier
 
     const __bf16 *S = lds + stage * TL::STAGE;
-    const __bf16 *Ah = S + (wr * MBH * 16 + lr) * PITCH + lg * 8;
+    const __bf16 *Ah = S + (wr * MBH * 16 + lr) * PITCH + lgs * 8;
     const __bf16 *Al = Ah + TL::A_PLANE;
-    const __bf16 *Bh = S + TL::PLANES * TL::A_PLANE + (wc * 64 + lr) * PITCH + lg * 8;
+    const __bf16 *Bh = S + TL::PLANES * TL::A_PLANE + (wc * 64 + lr) * PITCH + lgs * 8;
     const __bf16 *Bl = Bh + TL::B_PLANE;
     bf16x8 bh[4], bl[4];
 #pragma unroll
@@ -214,11 +260,11 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    if (TL::NSTAGE == 2) {
-      store_lds(stage ^ 1);   // every wave finished reading that stage before the previous barrier
-    } else {
+    if constexpr (SPLIT) {
       __syncthreads();        // every wave finished reading the only stage
       store_lds(0);
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of the next stage has landed
     }
     __syncthreads();
   }
