@@ -121,8 +121,9 @@ void layer_kernel(const LayerArgs<T> a) {
   // ---- global -> LDS by LDS-direct loads (global_load_lds_dwordx4): every lane names its own 16 global bytes and
   // the wave's 1 KiB lands at LDS address M0 + 16 * lane, without passing through registers.  A stage row is 64 bytes
   // (BK elements, unpadded), so one instruction moves a chunk of 16 rows: lane l brings row l/4 of the chunk, and the
-  // row's four 16-byte units are stored XOR-swizzled with bits 2..3 of the row, which makes the fragment reads below
-  // (16 lanes = 16 rows of one unit) hit 16 different bank groups.  Chunks 0..MB-1 are the A tile, MB..MB+BN/16-1 the
+  // row's four 16-byte units are stored XOR-swizzled with bits 2..3 of the row, so that the 16 rows x one unit that 16
+  // lanes of a fragment read touch fall into 16 different 16-byte bank groups (measured neutral: LDS conflicts are
+  // not on this kernel's critical path).  Chunks 0..MB-1 are the A tile, MB..MB+BN/16-1 the
   // B tile; wave w takes chunks w, w+4, ...  Rows past the tile's last valid row re-read that row: they only feed
   // accumulator rows the epilogue never looks at (MFMA rows do not mix).  The loads are unconditional per wave, so
   // the k loop stays branch-free apart from the uniform chunk-count test.
