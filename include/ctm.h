@@ -56,7 +56,8 @@ typedef enum {
   CTM_F32 = 1,        /* fp32 storage, fp32 MFMA (the benchmarked path)                     */
   CTM_F32_BF16X3 = 2, /* fp32 storage; GEMMs on the bf16 matrix cores with every operand split
                          into hi + lo bf16 parts (3 MFMAs per product, fp32 accumulate)      */
-  CTM_F32_BF16 = 3    /* fp32 storage; GEMM inputs rounded to bf16 (1 MFMA, fp32 accumulate) */
+  CTM_F32_BF16 = 3    /* fp32 tensors at the boundary; GEMM inputs rounded to bf16 (1 MFMA, fp32 accumulate;
+                         the workspace blocks between layers are kept in bf16)                */
 } ctm_dtype;
 
 typedef enum {
