@@ -130,7 +130,11 @@ void layer_kernel(const LayerArgs<T> a) {
   constexpr int kChunks = MB + BN / 16;
   constexpr int NCH = (kChunks + 3) / 4;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  const T *c_src[NCH];
+  // Address = uniform tile base (SGPR pair, advanced along k by scalar adds) + per-lane 32-bit byte offset: the k loop
+  // issues its loads without a single vector ALU instruction (VALU work there competes with the MFMAs for issue slots;
+  // per-lane 64-bit addresses cost 1 % more).
+  unsigned c_voff[NCH];  // per-lane byte offset from the operand's tile base (< 2^32: at most 256 rows of ldin elements)
+  const T *c_base[NCH];  // uniform: the operand's tile base
   unsigned c_off[NCH];   // byte offset inside buffer 0; buffer 1 adds the stage size of the operand
   unsigned c_step[NCH];  // bytes from buffer 0 to buffer 1 for this chunk's operand
 #pragma unroll
@@ -141,12 +145,14 @@ void layer_kernel(const LayerArgs<T> a) {
     if (c < MB) {
       const int row = c * 16 + rr;
       const int grow = row < rows_valid ? row : rows_valid - 1;
-      c_src[i] = Ag + (long)grow * a.ldin + uu * KV;
+      c_voff[i] = (unsigned)(((long)grow * a.ldin + uu * KV) * sizeof(T));
+      c_base[i] = Ag;
       c_off[i] = (unsigned)(c * 16 * BK * sizeof(T));
       c_step[i] = (unsigned)(TL::A_STAGE * sizeof(T));
     } else {
       const int cb = c < kChunks ? c - MB : 0;
-      c_src[i] = Bg + (long)(cb * 16 + rr) * a.ldin + uu * KV;
+      c_voff[i] = (unsigned)(((long)(cb * 16 + rr) * a.ldin + uu * KV) * sizeof(T));
+      c_base[i] = Bg;
       c_off[i] = (unsigned)((2 * TL::A_STAGE + cb * 16 * BK) * sizeof(T));
       c_step[i] = (unsigned)(TL::B_STAGE * sizeof(T));
     }
@@ -157,9 +163,9 @@ void layer_kernel(const LayerArgs<T> a) {
     for (int i = 0; i < NCH; ++i) {
       if (wave_u + 4 * i < kChunks) {
         const unsigned off = lds_base + c_off[i] + buf * c_step[i];
-        const T *g = c_src[i] + k0;
+        const T *g = c_base[i] + k0;   // uniform
         // M0 carries the LDS byte address; the compiler does not model this load, so the waits below are explicit
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(off) : "memory");
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(c_voff[i]), "s"(off), "s"(g) : "memory");
       }
     }
   };
