@@ -26,10 +26,11 @@ PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6, "bf16": 2500.0, "bf16x3": 2500.0}  # M
 def gemm_flops(dims, N, rho, R, per_point_dirs):
     """Algorithmic flops of the stacked-GEMM launches of one call.  Hidden layers 2..L-1 multiply all
     N*rho coefficient rows: 2 * N * rho * d_in * d_out (un-padded widths, collapsed row count).  The first
-    layer goes through the GEMM kernel only when directions differ per point, and then only its 1 + R
-    non-zero rows per point count.  The width-1 last layer is not a GEMM."""
+    layer goes through the GEMM kernel only when directions differ per point in more than 16 input dimensions
+    (or the input is wider than 64), and then only its 1 + R non-zero rows per point count.  The width-1 last
+    layer is not a GEMM."""
     f = sum(2.0 * N * rho * dims[l] * dims[l + 1] for l in range(1, len(dims) - 2))
-    if per_point_dirs or dims[0] > 64:
+    if (per_point_dirs and dims[0] > 16) or dims[0] > 64:
         f += 2.0 * N * (1 + R) * dims[0] * dims[1]
     return f
 

@@ -224,7 +224,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
     const int Rp = (pass == sp.n_passes - 1) ? sp.lastR : sp.first;
     const PassPlan pl = plan_pass(K, Rp, standard, N, m->min_col_tiles, m->slots);
     const int last_rows = standard ? 1 + Rp : 2;
-    const bool fast_first = first_layer_fast_path(m->dims[0], sn);
+    const int fast_first = first_layer_fast_path(m->dims[0], sn, Rp);
     // plain-bf16 handles keep the blocks between layers as one bf16 plane; see ctm_layer_bf16.hip
     const int bf16_blocks = m->dtype == CTM_F32_BF16 ? 1 : 0;
     const T *in = buf[1];
@@ -237,7 +237,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       fa.x = x; fa.V = V; fa.W = (const T *)m->Wp[0]; fa.bias = (const T *)m->bp[0];
       fa.Z1 = dirs;
       fa.out = last ? pair : buf[0];
-      fa.N = N; fa.v_sr = sr; fa.v_sd = sd;
+      fa.N = N; fa.v_sn = sn; fa.v_sr = sr; fa.v_sd = sd;
       fa.D = m->dims[0]; fa.ld0 = m->ld[0]; fa.ld1 = m->ld[1]; fa.rho = pl.rho; fa.order = K; fa.R = Rp;
       fa.r0 = pass * sp.first; fa.last = last ? 1 : 0; fa.act = (int)m->act;
       fa.standard = standard ? 1 : 0; fa.out_rows = last ? last_rows : pl.rho;

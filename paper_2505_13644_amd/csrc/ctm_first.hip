@@ -135,9 +135,123 @@ template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer
     }
 }
 
-bool first_layer_fast_path(int D, long v_point_stride) { return v_point_stride == 0 && D <= kFirstDmax; }
+// ---- per-point directions in a low-dimensional input space (D <= 16) ------------------------------------------
+// z_{1,r}(n) = W_1 v_{n,r} differs from point to point, but with so few inputs it is cheaper as D multiply-adds per
+// (row, feature) than as a stacked GEMM over a seeded block whose higher-order rows are all zero: the layer is then
+// bound by writing its output block, like the shared-direction kernel above.  A workgroup takes kPPPoints points;
+// their x and directions are staged in LDS (zero-padded to 16 inputs) and read back 4 inputs at a time.
+constexpr int kPPPoints = 2;  // measured on the order-4 benchmark workload: 1 -> 26 us, 2 -> 28 us, 4 -> 44 us (too few workgroups)
+constexpr int kPPDmax = 16;
+
+template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer_pp_kernel(const FirstArgs<T> a) {
+  extern __shared__ __align__(16) unsigned char pp_lds[];
+  T *xs = reinterpret_cast<T *>(pp_lds);                 // [kPPPoints][16]
+  T *vs = xs + kPPPoints * kPPDmax;                      // [kPPPoints][R][16]
+  const int tid = threadIdx.x;
+  const int j = blockIdx.y * 256 + tid;                  // blockIdx.x runs over the points (it has the larger range)
+  const long n0 = (long)blockIdx.x * kPPPoints;
+  const int np = (int)((a.N - n0) < kPPPoints ? (a.N - n0) : kPPPoints);
+  const int R = a.R;
+  for (int i = tid; i < kPPPoints * kPPDmax; i += 256) {
+    const int p = i / kPPDmax, k = i % kPPDmax;
+    xs[i] = (p < np && k < a.D) ? a.x[(n0 + p) * a.D + k] : T(0);
+  }
+  for (int i = tid; i < kPPPoints * R * kPPDmax; i += 256) {
+    const int k = i % kPPDmax;
+    const int r = (i / kPPDmax) % R;
+    const int p = i / (kPPDmax * R);
+    vs[i] = (p < np && k < a.D) ? a.V[(n0 + p) * a.v_sn + (long)(a.r0 + r) * a.v_sr + (long)k * a.v_sd] : T(0);
+  }
+  __syncthreads();
+  if (j >= a.ld1) return;
+
+  T w[kPPDmax];
+#pragma unroll
+  for (int k = 0; k < kPPDmax; ++k) w[k] = k < a.D ? a.W[(long)j * a.ld0 + k] : T(0);
+  const T bias = a.bias[j];
+  const long ld = a.ld1;
+  const int rho = a.rho, K = a.order;
+  auto dot16 = [&](const T *v) {   // v: 16 staged inputs, the same address for every lane (LDS broadcast reads)
+    T acc = T(0);
+#pragma unroll
+    for (int k = 0; k < kPPDmax; ++k) acc += w[k] * v[k];
+    return acc;
+  };
+  for (int p = 0; p < np; ++p) {
+    const long obase = ((a.out_point0 + n0 + p) * a.out_rows) * ld + j;
+    auto put = [&](long row, T v) {
+      if constexpr (BF == 0) a.out[obase + row * ld] = v;
+      else reinterpret_cast<__bf16 *>(a.out)[obase + row * ld] = (__bf16)(float)v;
+    };
+    T t, d1;
+    act_eval<T>(a.act, bias + dot16(xs + p * kPPDmax), t, d1);
+    const T d2 = act_d2<T>(a.act, t, d1);
+    const T d3 = K == 4 ? act_d3<T>(a.act, t, d1) : T(0);
+    const T dK = K == 2 ? d2 : act_d4<T>(a.act, t, d1);
+    put(0, t);
+    T mom = T(0);  // sum_r z1_r^K, the only term of the collapsed row at the first layer
+    for (int r = 0; r < R; ++r) {
+      const T z1 = dot16(vs + ((long)p * R + r) * kPPDmax);
+      const T z1s = z1 * z1;
+      const T zK = K == 2 ? z1s : z1s * z1s;
+      mom += zK;
+      if (a.standard) {  // un-collapsed layout: direction r keeps its own highest-order row, d_K z1^K at this layer
+        const long row1 = K == 2 ? 1 + r : 1 + 4 * r;
+        const long rowK = a.last ? 1 + r : (K == 2 ? 1 + R + r : 4 + 4 * r);
+        put(rowK, dK * zK);
+        if (!a.last) {
+          put(row1, d1 * z1);
+          if (K == 4) {
+            put(row1 + 1, d2 * z1s);
+            put(row1 + 2, d3 * z1s * z1);
+          }
+        }
+      } else if (!a.last) {
+        if (K == 2) {
+          put(1 + r, d1 * z1);
+        } else {
+          put(1 + 3 * r, d1 * z1);
+          put(2 + 3 * r, d2 * z1s);
+          put(3 + 3 * r, d3 * z1s * z1);
+        }
+      }
+    }
+    if (!a.standard) put(a.last ? 1 : rho - 1, dK * mom);
+  }
+}
+
+// 0: no fast path (seed block + stacked GEMM); 1: shared directions; 2: per-point directions, D <= 16
+int first_layer_fast_path(int D, long v_point_stride, int R) {
+  if (v_point_stride == 0) return D <= kFirstDmax ? 1 : 0;
+  const size_t lds = (size_t)kPPPoints * (1 + (size_t)R) * kPPDmax * sizeof(double);
+  return (D <= kPPDmax && lds <= 96 * 1024) ? 2 : 0;
+}
+
+template <typename T> static hipError_t launch_first_pp(const FirstArgs<T> &a, hipStream_t s) {
+  const size_t lds = (size_t)kPPPoints * (1 + (size_t)a.R) * kPPDmax * sizeof(T);
+  const long chunks = (a.N + kPPPoints - 1) / kPPPoints;
+  if (chunks > 0x7fffffffL || (a.ld1 + 255) / 256 > 65535) return hipErrorInvalidValue;
+  static LdsLimitOnce lim0, lim1;
+  hipError_t e = lim0.ensure(reinterpret_cast<const void *>(&first_layer_pp_kernel<T, 0>), 96 * 1024);
+  if (e != hipSuccess) return e;
+  if constexpr (std::is_same<T, float>::value) {
+    e = lim1.ensure(reinterpret_cast<const void *>(&first_layer_pp_kernel<T, 1>), 96 * 1024);
+    if (e != hipSuccess) return e;
+  }
+  const dim3 grid((unsigned)chunks, (a.ld1 + 255) / 256);
+  bool launched = false;
+  if constexpr (std::is_same<T, float>::value) {
+    if (a.out_bf16) { hipLaunchKernelGGL((first_layer_pp_kernel<T, 1>), grid, dim3(256), lds, s, a); launched = true; }
+  }
+  if (!launched) {
+    if (a.out_bf16) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((first_layer_pp_kernel<T, 0>), grid, dim3(256), lds, s, a);
+  }
+  return hipGetLastError();
+}
 
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s) {
+  if (a.v_sn != 0) return launch_first_pp<T>(a, s);
   hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256, a.R), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -100,13 +100,14 @@ template <typename T> hipError_t launch_seed(const SeedArgs<T> &a, hipStream_t s
 // First layer when every point shares the directions: no GEMM over the per-direction rows.
 template <typename T> struct FirstArgs {
   const T *x;     // [N][D]
-  const T *V;     // shared directions (element (r, k) at V[r*v_sr + k*v_sd]) or nullptr (basis)
+  const T *V;     // directions (element (n, r, k) at V[n*v_sn + r*v_sr + k*v_sd]) or nullptr (basis)
   const T *W;     // zero-padded first-layer weights [rows_pad][ld0]
   const T *bias;  // [rows_pad]
   T *Z1;          // scratch [R][ld1]: W_1 v_r
   T *out;         // last == 0: [N * rho][ld1]; last == 1: [N][2][ld1]
   long N;
   long v_sr, v_sd;
+  long v_sn = 0;  // point stride of V (0: shared by all points)
   int D, ld0, ld1, rho, order, R, r0, last, act;
   int standard;   // un-collapsed row layout
   int out_rows;   // rows per point in out
@@ -114,7 +115,8 @@ template <typename T> struct FirstArgs {
   long out_point0 = 0;   // index of this launch's first point in out (x and N are already offset)
 };
 constexpr int kMaxOutputs = 1024;  // widest last layer (outputs are produced by a per-point dot-product kernel)
-bool first_layer_fast_path(int D, long v_point_stride);
+// 0: none (seed block + stacked GEMM); 1: directions shared by all points; 2: per-point directions with D <= 16
+int first_layer_fast_path(int D, long v_point_stride, int R);
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s);
 
 // transpose == 0: Wp[j][k] = W[j][k] (W is [d_out][d_in]); transpose == 1: Wp[j][k] = W[k][j] (W is [d_in][d_out]).
