@@ -360,6 +360,25 @@ def test_errors_from_the_library_with_a_live_handle():
     assert err(op.double().cpu().numpy(), ref[1]) <= TOL32
     with pytest.raises(ValueError):
         ctm.ctm_laplacian(mlp, x[:, :4].contiguous())
+    # recording forward / reverse pass: tape and workspace sizes, direction limits, missing directions
+    V = torch.randn(8, 3, 5, device=dev)
+    tape = torch.empty(ctm.ctm_biharmonic_tape_bytes(mlp, 8, 3), dtype=torch.uint8, device=dev)
+    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 3, 15, p(u), p(op), p(tape), tape.numel() - 1, st) == -5
+    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, None, 3, 15, p(u), p(op), p(tape), tape.numel(), st) == -1
+    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 3, 14, p(u), p(op), p(tape), tape.numel(), st) == -2
+    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 85, 85 * 5, p(u), p(op), p(tape), tape.numel(), st) == -4
+    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 3, 15, p(u), p(op), p(tape), tape.numel(), st) == 0
+    bws = torch.empty(ctm.ctm_biharmonic_backward_workspace_bytes(mlp, 8, 3), dtype=torch.uint8, device=dev)
+    assert L.ctm_biharmonic_rand_bwd(mlp.handle, 8, 3, p(tape), tape.numel(), p(u), p(op), None, None, p(bws), bws.numel() - 1, st) == -5
+    assert L.ctm_biharmonic_rand_bwd(mlp.handle, 8, 3, p(tape), tape.numel() - 1, p(u), p(op), None, None, p(bws), bws.numel(), st) == -5
+    assert L.ctm_biharmonic_rand_bwd(mlp.handle, 8, 3, p(tape), tape.numel(), p(u), p(op), None, None, p(bws), bws.numel(), st) == 0  # no gradient wanted
+    assert L.ctm_laplacian_fwd(mlp.handle, p(x), 8, None, 5, 0, 1.0, p(u), p(op), p(tape), 16, st) == -5
+    assert L.ctm_laplacian_fwd(mlp.handle, p(x), 8, None, 300, 0, 1.0, p(u), p(op), p(tape), tape.numel(), st) == -4
+    torch.cuda.synchronize()
+    # the bf16 variants have no recording forward
+    m16 = ctm.ctm_create_mlp([torch.from_numpy(W).to(dev) for W in arrs["Ws"]], None, mfma=ctm.CTM_F32_BF16X3)
+    assert L.ctm_tape_bytes(m16.handle, 8, 5) == 0 and "CTM_F32 and CTM_F64" in ctm.ctm_last_error()
+    m16.close()
     mlp.close()
 
 
