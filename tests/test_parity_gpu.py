@@ -557,3 +557,41 @@ def test_results_do_not_depend_on_the_tile_shape(op_name):
     assert orc.scaled_max_err(u.cpu().numpy()[idx], ru) <= 2e-4
     assert orc.scaled_max_err(op.cpu().numpy()[idx], rop) <= 2e-4
     mlp.close()
+
+
+@pytest.mark.parametrize("gain", [4.0, 8.0])
+def test_saturating_activations_stay_inside_the_fp32_bar(gain):
+    # weights scaled up and points spread over [-2, 2): most tanh units saturate, so 1 - t^2 is a difference of nearly
+    # equal numbers and the operator values grow by orders of magnitude; the scaled max-norm error must still hold
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import operators as orc
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    dims = (10, 128, 128, 128, 1)
+    Ws, bs = synth.make_mlp(dims, 0, 0.1, np.float32)
+    Ws = [(W * gain).astype(np.float32) for W in Ws[:-1]] + [Ws[-1]]
+    x = (synth.make_points(120, 10, 0, np.float32) * 4 - 2).astype(np.float32)
+    V = synth.make_directions("gaussian", (120, 6, 10), 0, np.float32)
+    mlp = ctm.ctm_create_mlp([t(W) for W in Ws], [t(b) for b in bs])
+    u, op = ctm.ctm_laplacian(mlp, t(x))
+    u4, op4 = ctm.ctm_biharmonic_rand(mlp, t(x), t(V))
+    ru, rop = orc.laplacian(Ws, bs, x, None, 1.0, mode="directional")
+    _, rop4 = orc.biharmonic_rand(Ws, bs, x, V)
+    errs = (err(u.cpu().numpy(), ru), err(op.cpu().numpy(), rop), err(op4.cpu().numpy(), rop4))
+    print(f"case saturation gain={gain}: u {errs[0]:.2e} laplacian {errs[1]:.2e} biharmonic {errs[2]:.2e}", flush=True)
+    assert max(errs) <= TOL32
+    mlp.close()
+
+
+@pytest.mark.parametrize("dims,N", [((3, 4096, 2048, 1), 24), ((4,) + (32,) * 18 + (1,), 50), ((64, 96, 1), 40), ((65, 96, 80, 1), 33)])
+def test_very_wide_very_deep_and_wide_input_networks(dims, N):
+    # 32 column tiles in one layer; 19 linear layers; an input as wide as the register-resident first layer takes (64)
+    # and one just beyond it (65: seed block + stacked GEMM for the first layer even with shared directions)
+    arrs = small_case(dims, N, np.float32, 3)
+    print(f"case network shape dims={dims[:3]}..x{len(dims) - 1} N={N}", flush=True)
+    u, op = gpu_run(arrs, "laplacian")
+    ru, rop = oracle_run(arrs, "laplacian")
+    eu, eo = err(u, ru), err(op, rop)
+    print(f"  u {eu:.2e} op {eo:.2e}", flush=True)
+    assert eu <= TOL32 and eo <= TOL32
