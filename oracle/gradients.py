@@ -91,3 +91,35 @@ def biharmonic_loss_grads(Ws, bs, x, V, gu, gop, act="tanh"):
     gW = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[:len(Ws_t)], Ws_t)]
     gb = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[len(Ws_t):], bs_t)]
     return float(L.detach()), gW, gb
+
+
+def biharmonic_exact_loss_grads(Ws, bs, x, gu, gop, act="tanh"):
+    """Gradients of  L = sum_{n,c} gu_{n,c} u_c(x_n) + gop_{n,c} (Delta^2 u_c)(x_n)  with the exact biharmonic
+    Delta^2 u = Delta(Delta u) = sum_{i,j} d^4 u / dx_i^2 dx_j^2  (Sec. 3.3, Eq. 9, exact case).
+
+    Written as the Laplacian of the Laplacian with nested first-order automatic differentiation (trace of the
+    Hessian, twice), then one reverse sweep to the parameters.  Meant for tiny D and narrow networks.
+    Returns (L, [dL/dW_l], [dL/db_l]) as fp64 numpy.
+    """
+    t = lambda a: torch.as_tensor(np.asarray(a, dtype=np.float64))
+    Ws_t = [t(W).requires_grad_(True) for W in Ws]
+    bs_t = [t(b).requires_grad_(True) for b in bs]
+    xt = t(x)
+    N, D = xt.shape
+    C = Ws_t[-1].shape[0]
+    gut, gopt = t(gu).reshape(N, C), t(gop).reshape(N, C)
+
+    def loss(params):
+        def bih(p):  # [C]
+            f = lambda q: _mlp(params, q, act)                                             # [C]
+            lap = lambda q: torch.diagonal(torch.func.hessian(f)(q), dim1=-2, dim2=-1).sum(-1)   # [C]
+            return torch.diagonal(torch.func.hessian(lap)(p), dim1=-2, dim2=-1).sum(-1)
+        op = torch.func.vmap(bih)(xt)
+        u = _mlp(params, xt, act)
+        return (gut * u + gopt * op).sum()
+
+    L = loss((Ws_t, bs_t))
+    grads = torch.autograd.grad(L, Ws_t + bs_t, allow_unused=True)
+    gW = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[:len(Ws_t)], Ws_t)]
+    gb = [(g if g is not None else torch.zeros_like(p)).numpy() for g, p in zip(grads[len(Ws_t):], bs_t)]
+    return float(L.detach()), gW, gb

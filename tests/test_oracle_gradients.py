@@ -105,3 +105,40 @@ def test_biharmonic_closed_form_gradient_one_hidden_layer():
     proj4 = ((V @ W1.T) ** 4).sum(0) / (3.0 * 2)
     np.testing.assert_allclose(gW[1][0], gu @ t + gop @ (d4 * proj4), rtol=1e-11)
     np.testing.assert_allclose(gb[1][0], gu.sum(), rtol=1e-12)
+
+
+def test_exact_biharmonic_gradients_against_finite_differences_and_a_closed_form():
+    Ws, bs = tiny((3, 5, 4, 1), 51)
+    rng = np.random.default_rng(52)
+    N = 3
+    x = rng.random((N, 3))
+    gu, gop = rng.standard_normal(N), rng.standard_normal(N)
+
+    def loss():
+        return float((gu * orc.value(Ws, bs, x) + gop * orc.biharmonic_exact(Ws, bs, x)).sum())
+
+    L, gW, gb = og.biharmonic_exact_loss_grads(Ws, bs, x, gu, gop)
+    assert L == pytest.approx(loss(), rel=1e-11)
+    h = 1e-5
+    for group, grads in ((Ws, gW), (bs, gb)):
+        for arr, g in zip(group, grads):
+            it = np.nditer(arr, flags=["multi_index"])
+            for _ in it:
+                i = it.multi_index
+                old = arr[i]
+                arr[i] = old + h
+                lp = loss()
+                arr[i] = old - h
+                lm = loss()
+                arr[i] = old
+                assert g[i] == pytest.approx((lp - lm) / (2 * h), rel=5e-6, abs=5e-8), (i, g[i])
+    # one hidden layer: Delta^2 u = sum_j a_j |w_j|^4 tanh''''(z_j)  =>  d/da_j = |w_j|^4 tanh''''(z_j)
+    rng = np.random.default_rng(7)
+    W1, b1 = rng.standard_normal((6, 3)) * 0.5, rng.standard_normal(6) * 0.2
+    a, c = rng.standard_normal((1, 6)), rng.standard_normal(1)
+    x = rng.random((4, 3))
+    gu, gop = rng.standard_normal(4), rng.standard_normal(4)
+    _, gW, gb = og.biharmonic_exact_loss_grads([W1, a], [b1, c], x, gu, gop)
+    t = np.tanh(x @ W1.T + b1)
+    d4 = 8 * t * (1 - t * t) * (2 - 3 * t * t)
+    np.testing.assert_allclose(gW[1][0], gu @ t + gop @ (d4 * (W1 ** 2).sum(1) ** 2), rtol=1e-10)
