@@ -202,6 +202,20 @@ int ctm_biharmonic_rand_bwd(const ctm_mlp *mlp, long N, int S, const void *tape,
                             size_t workspace_bytes, void *stream);
 
 /*
+ * And for the exact biharmonic (Sec. 3.3, Eq. 12; "differentiable" evaluation, Sec. 4): the forward records one
+ * order-4 tape per direction family of the interpolation formula, the reverse pass runs once per family and adds
+ * the three contributions in a fixed order (u enters through the first).  Every family must fit one pass:
+ * D (D - 1) <= 84, i.e. D <= 9 (CTM_ERR_UNSUPPORTED beyond).  Arguments as in the pairs above.
+ */
+size_t ctm_biharmonic_exact_tape_bytes(const ctm_mlp *mlp, long N);
+size_t ctm_biharmonic_exact_backward_workspace_bytes(const ctm_mlp *mlp, long N);
+int ctm_biharmonic_exact_fwd(const ctm_mlp *mlp, const void *x, long N, void *u, void *op, void *tape,
+                             size_t tape_bytes, void *stream);
+int ctm_biharmonic_exact_bwd(const ctm_mlp *mlp, long N, const void *tape, size_t tape_bytes, const void *gu,
+                             const void *gop, void *const *gW, void *const *gb, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/*
  * The same sums computed by STANDARD (un-collapsed) Taylor mode, for comparison only: every direction
  * carries its own order-K coefficient through the network (1 + K*R rows per point, Sec. 3.1) and the sum
  * over directions is taken after the last layer.  K = 2 or 4; other arguments as in ctm_laplacian

@@ -2,6 +2,7 @@
 
     u, op = laplacian(mlp, Ws, bs, x, V=None, scale=1.0)
     u, op = biharmonic_rand(mlp, Ws, bs, x, V)
+    u, op = biharmonic_exact(mlp, Ws, bs, x)
 
 return tensors that are differentiable with respect to the weight tensors Ws / bs (not x or V).  Every number is
 produced by the library's kernels; this module only re-packs the current weights into the handle
@@ -48,6 +49,28 @@ class _BiharmonicRand(torch.autograd.Function):
         gop = None if gop is None else gop.contiguous()
         gW, gb = B.ctm_biharmonic_rand_bwd(ctx.mlp, ctx.N, ctx.S, ctx.tape, gu, gop)
         return (None, None, None, None, *gW, *gb)
+
+
+class _BiharmonicExact(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, mlp, x, n_layers, *params):
+        Ws, bs = list(params[:n_layers]), list(params[n_layers:])
+        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        u, op, tape = B.ctm_biharmonic_exact_fwd(mlp, x)
+        ctx.mlp, ctx.tape, ctx.N = mlp, tape, x.shape[0]
+        return u, op
+
+    @staticmethod
+    def backward(ctx, gu, gop):
+        gu = None if gu is None else gu.contiguous()
+        gop = None if gop is None else gop.contiguous()
+        gW, gb = B.ctm_biharmonic_exact_bwd(ctx.mlp, ctx.N, ctx.tape, gu, gop)
+        return (None, None, None, *gW, *gb)
+
+
+def biharmonic_exact(mlp, Ws, bs, x):
+    """(u, op) of ctm_biharmonic_exact, differentiable with respect to the tensors in Ws and bs (D <= 9)."""
+    return _BiharmonicExact.apply(mlp, x, len(Ws), *Ws, *bs)
 
 
 def biharmonic_rand(mlp, Ws, bs, x, V):

@@ -50,6 +50,11 @@ SIGNATURES = {
                                         c_size_t, c_void_p]),
     "ctm_biharmonic_rand_bwd": (c_int, [c_void_p, c_long, c_int, c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_void_p),
                                         POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
+    "ctm_biharmonic_exact_tape_bytes": (c_size_t, [c_void_p, c_long]),
+    "ctm_biharmonic_exact_backward_workspace_bytes": (c_size_t, [c_void_p, c_long]),
+    "ctm_biharmonic_exact_fwd": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "ctm_biharmonic_exact_bwd": (c_int, [c_void_p, c_long, c_void_p, c_size_t, c_void_p, c_void_p, POINTER(c_void_p),
+                                         POINTER(c_void_p), c_void_p, c_size_t, c_void_p]),
     "ctm_workspace_bytes_standard": (c_size_t, [c_void_p, c_int, c_long, c_int]),
     "ctm_taylor_standard": (c_int, [c_void_p, c_int, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p,
                                     c_void_p, c_size_t, c_void_p]),
@@ -487,6 +492,45 @@ def ctm_biharmonic_rand_bwd(mlp: Mlp, N, S, tape, gu, gop, gW=None, gb=None, wor
     _check(lib().ctm_biharmonic_rand_bwd(mlp.handle, N, S, c_void_p(tape.data_ptr()), tape.numel(),
                                          _dev_ptr(gu, mlp.dtype, "gu"), _dev_ptr(gop, mlp.dtype, "gop"), c_gW, c_gb,
                                          c_void_p(workspace.data_ptr()), workspace.numel(), _stream_ptr()))
+    return gW, gb
+
+
+def ctm_biharmonic_exact_tape_bytes(mlp: Mlp, N: int) -> int:
+    n = lib().ctm_biharmonic_exact_tape_bytes(mlp.handle, N)
+    if n == 0:
+        raise CtmError(-4, ctm_last_error())
+    return n
+
+
+def ctm_biharmonic_exact_backward_workspace_bytes(mlp: Mlp, N: int) -> int:
+    n = lib().ctm_biharmonic_exact_backward_workspace_bytes(mlp.handle, N)
+    if n == 0:
+        raise CtmError(-4, ctm_last_error())
+    return n
+
+
+def ctm_biharmonic_exact_fwd(mlp: Mlp, x, u=None, op=None, tape=None):
+    """Exact biharmonic that records a tape for ctm_biharmonic_exact_bwd.  Returns (u, op, tape)."""
+    torch = _torch()
+    _check_shapes(mlp, x, None)
+    N = x.shape[0]
+    u, op = _out_pair(mlp, x, u, op)
+    if tape is None:
+        tape = torch.empty(ctm_biharmonic_exact_tape_bytes(mlp, N), dtype=torch.uint8, device=x.device)
+    _check(lib().ctm_biharmonic_exact_fwd(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(u, mlp.dtype, "u"),
+                                          _dev_ptr(op, mlp.dtype, "op"), c_void_p(tape.data_ptr()), tape.numel(), _stream_ptr()))
+    return u, op, tape
+
+
+def ctm_biharmonic_exact_bwd(mlp: Mlp, N, tape, gu, gop, gW=None, gb=None, workspace=None):
+    """dL/dW_l, dL/db_l of the exact biharmonic from dL/du (gu) and dL/dop (gop).  Returns (gW, gb)."""
+    torch = _torch()
+    gW, gb, c_gW, c_gb = _grad_buffers(mlp, N, tape, gu, gop, gW, gb)
+    if workspace is None:
+        workspace = torch.empty(ctm_biharmonic_exact_backward_workspace_bytes(mlp, N), dtype=torch.uint8, device=tape.device)
+    _check(lib().ctm_biharmonic_exact_bwd(mlp.handle, N, c_void_p(tape.data_ptr()), tape.numel(), _dev_ptr(gu, mlp.dtype, "gu"),
+                                          _dev_ptr(gop, mlp.dtype, "gop"), c_gW, c_gb, c_void_p(workspace.data_ptr()),
+                                          workspace.numel(), _stream_ptr()))
     return gW, gb
 
 

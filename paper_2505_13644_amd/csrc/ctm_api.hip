@@ -422,7 +422,7 @@ int check_tape_call(const ctm_mlp *m, int K, long N, int R, const char *who) {
 
 template <typename T>
 int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
-                 hipStream_t st) {
+                 hipStream_t st, bool accumulate_op = false) {
   const TapeLayout tl = tape_layout(m, K, N, R);
   const PassPlan pl = plan_pass(K, R, false, N, m->min_col_tiles, m->slots);
   const int L = m->L;
@@ -455,7 +455,7 @@ int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R,
   }
   FinalArgs<T> fa;
   fa.pair = pair; fa.nk = 1; fa.w = (const T *)m->Wp[L - 1]; fa.b = (const T *)m->bp[L - 1];
-  fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.C = m->dims[L]; fa.scale = scale; fa.accumulate = 0;
+  fa.u = u; fa.op = op; fa.N = N; fa.ld = m->ld[L - 1]; fa.C = m->dims[L]; fa.scale = scale; fa.accumulate = accumulate_op ? 1 : 0;
   e = launch_final<T>(fa, st);
   if (e != hipSuccess) return fail_hip(e, "final kernel launch");
   (void)prof_mark(st, 2);
@@ -464,7 +464,7 @@ int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R,
 
 template <typename T>
 int run_bwd(const ctm_mlp *m, int K, long N, int R, double scale, const void *tape, const T *gu, const T *gop, void *const *gW,
-            void *const *gb, void *ws, hipStream_t st) {
+            void *const *gb, void *ws, hipStream_t st, int accumulate = 0) {
   const TapeLayout tl = tape_layout(m, K, N, R);
   const BwdLayout bl = bwd_layout(m, K, N, R);
   const PassPlan pl = plan_pass(K, R, false, N, m->min_col_tiles, m->slots);
@@ -488,19 +488,19 @@ int run_bwd(const ctm_mlp *m, int K, long N, int R, double scale, const void *ta
   if (e != hipSuccess) return fail_hip(e, "reverse last-layer kernel launch");
   T *gw_last = (gW && gW[L - 1]) ? (T *)gW[L - 1] : dummy;
   T *gb_last = (gb && gb[L - 1]) ? (T *)gb[L - 1] : dummy + (size_t)C * maxld;
-  e = launch_last_grads<T>((const T *)(tp + tl.pair), gu, gop, scale, N, m->ld[L - 1], m->dims[L - 1], C, gw_last, gb_last, scratch, st);
+  e = launch_last_grads<T>((const T *)(tp + tl.pair), gu, gop, scale, N, m->ld[L - 1], m->dims[L - 1], C, gw_last, gb_last, scratch, st, accumulate);
   if (e != hipSuccess) return fail_hip(e, "last-layer gradient kernel launch");
   (void)prof_mark(st, 0);
 
   for (int i = L - 2; i >= 0; --i) {
     const T *Zb = zb[cur];
     if (gb && gb[i]) {
-      e = launch_bias_grad<T>(Zb, N, pl.rho, m->ld[i + 1], m->dims[i + 1], (T *)gb[i], scratch, st);
+      e = launch_bias_grad<T>(Zb, N, pl.rho, m->ld[i + 1], m->dims[i + 1], (T *)gb[i], scratch, st, accumulate);
       if (e != hipSuccess) return fail_hip(e, "bias gradient kernel launch");
     }
     if (gW && gW[i]) {
       const T *Hprev = (const T *)(tp + (i == 0 ? tl.h0 : tl.h[i - 1]));
-      e = launch_wgrad<T>(Zb, m->ld[i + 1], Hprev, m->ld[i], M, m->dims[i + 1], m->dims[i], (T *)gW[i], partials, st);
+      e = launch_wgrad<T>(Zb, m->ld[i + 1], Hprev, m->ld[i], M, m->dims[i + 1], m->dims[i], (T *)gW[i], partials, st, accumulate);
       if (e != hipSuccess) return fail_hip(e, "weight gradient kernel launch");
     }
     (void)prof_mark(st, 2);
@@ -917,6 +917,139 @@ size_t ctm_biharmonic_exact_workspace_bytes(const ctm_mlp *m, long N) {
   return workspace_layout(m, 4, N, split_dirs(4, (int)rmax).first).total + round256((size_t)rmax * D * elem_size(m->dtype));
 }
 
+}  // extern "C"
+
+namespace {
+
+// The three direction families of the interpolation formula (Sec. 3.3, Eq. 12; App. E.1, last display) and their weights.
+struct BiharmFamilies {
+  double weight[3];
+  long count[3];
+  long rmax;
+};
+BiharmFamilies biharm_families(int D) {
+  const int i22[2] = {2, 2}, j40[2] = {4, 0}, j31[2] = {3, 1}, j22[2] = {2, 2};
+  const Frac g40 = interp_gamma(2, i22, j40), g31 = interp_gamma(2, i22, j31), g22 = interp_gamma(2, i22, j22);
+  const double G40 = (double)g40.n / g40.d, G31 = (double)g31.n / g31.d, G22 = (double)g22.n / g22.d;
+  BiharmFamilies f;
+  f.weight[0] = (2.0 * D * G40 + 2.0 * G31 + G22) / 24.0;
+  f.weight[1] = 2.0 * G31 / 24.0;
+  f.weight[2] = 2.0 * G22 / 24.0;
+  f.count[0] = D;
+  f.count[1] = (long)D * (D - 1);
+  f.count[2] = (long)D * (D - 1) / 2;
+  f.rmax = D > 1 ? (long)D * (D - 1) : D;
+  return f;
+}
+
+// Tape of the differentiable exact biharmonic: one order-4 tape per family, then the direction scratch.
+struct ExactTape {
+  size_t off[3], dirs, total;
+};
+int exact_tape_layout(const ctm_mlp *m, long N, const char *who, ExactTape *t) {
+  if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
+  const BiharmFamilies f = biharm_families(m->dims[0]);
+  size_t off = 0;
+  for (int fam = 0; fam < 3; ++fam) {
+    t->off[fam] = off;
+    if (f.count[fam] == 0) continue;
+    if (f.count[fam] > 0x7fffffffL) return fail(CTM_ERR_SHAPE, "%s: D too large", who);
+    const int rc = check_tape_call(m, 4, N, (int)f.count[fam], who);
+    if (rc != CTM_OK) return rc;
+    off += tape_layout(m, 4, N, (int)f.count[fam]).total;
+  }
+  t->dirs = off;
+  t->total = off + round256((size_t)f.rmax * m->dims[0] * elem_size(m->dtype));
+  return CTM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ctm_biharmonic_exact_tape_bytes(const ctm_mlp *m, long N) {
+  ExactTape t;
+  return exact_tape_layout(m, N, "ctm_biharmonic_exact_tape_bytes", &t) == CTM_OK ? t.total : 0;
+}
+
+size_t ctm_biharmonic_exact_backward_workspace_bytes(const ctm_mlp *m, long N) {
+  ExactTape t;
+  if (exact_tape_layout(m, N, "ctm_biharmonic_exact_backward_workspace_bytes", &t) != CTM_OK) return 0;
+  return bwd_layout(m, 4, N, (int)biharm_families(m->dims[0]).rmax).total;
+}
+
+int ctm_biharmonic_exact_fwd(const ctm_mlp *m, const void *x, long N, void *u, void *op, void *tape, size_t tape_bytes,
+                             void *stream) {
+  const char *who = "ctm_biharmonic_exact_fwd";
+  ExactTape t;
+  int rc = exact_tape_layout(m, N, who, &t);
+  if (rc != CTM_OK) return rc;
+  if (!x || !tape) return fail(CTM_ERR_NULL, "%s: x or tape is NULL", who);
+  if (tape_bytes < t.total) return fail(CTM_ERR_WORKSPACE, "%s: tape has %zu bytes, need %zu", who, tape_bytes, t.total);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(tape, 256)) return fail(CTM_ERR_ALIGN, "%s: tape must be 256-byte aligned", who);
+  if (misaligned(x, es) || misaligned(u, es) || misaligned(op, es))
+    return fail(CTM_ERR_ALIGN, "%s: x, u and op must be aligned to the element size", who);
+  if ((rc = check_device(m, who)) != CTM_OK) return rc;
+  const int D = m->dims[0];
+  const BiharmFamilies f = biharm_families(D);
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char *tp = (char *)tape;
+  bool first = true;
+  for (int fam = 0; fam < 3; ++fam) {
+    if (f.count[fam] == 0) continue;
+    if (m->dtype == CTM_F64) {
+      hipError_t e = launch_biharm_dirs<double>((double *)(tp + t.dirs), D, fam, st);
+      if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
+      rc = run_fwd_tape<double>(m, 4, (const double *)x, N, (const double *)(tp + t.dirs), (int)f.count[fam], 0, f.weight[fam],
+                                first ? (double *)u : nullptr, (double *)op, tp + t.off[fam], st, !first);
+    } else {
+      hipError_t e = launch_biharm_dirs<float>((float *)(tp + t.dirs), D, fam, st);
+      if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
+      rc = run_fwd_tape<float>(m, 4, (const float *)x, N, (const float *)(tp + t.dirs), (int)f.count[fam], 0, f.weight[fam],
+                               first ? (float *)u : nullptr, (float *)op, tp + t.off[fam], st, !first);
+    }
+    if (rc != CTM_OK) return rc;
+    first = false;
+  }
+  return CTM_OK;
+}
+
+int ctm_biharmonic_exact_bwd(const ctm_mlp *m, long N, const void *tape, size_t tape_bytes, const void *gu, const void *gop,
+                             void *const *gW, void *const *gb, void *ws, size_t ws_bytes, void *stream) {
+  const char *who = "ctm_biharmonic_exact_bwd";
+  ExactTape t;
+  int rc = exact_tape_layout(m, N, who, &t);
+  if (rc != CTM_OK) return rc;
+  if (!tape || !ws) return fail(CTM_ERR_NULL, "%s: tape or workspace is NULL", who);
+  if (tape_bytes < t.total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than ctm_biharmonic_exact_tape_bytes() says", who);
+  const BiharmFamilies f = biharm_families(m->dims[0]);
+  const size_t need = bwd_layout(m, 4, N, (int)f.rmax).total;
+  if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
+  const size_t es = elem_size(m->dtype);
+  if (misaligned(tape, 256) || misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: tape and workspace must be 256-byte aligned", who);
+  if (misaligned(gu, es) || misaligned(gop, es)) return fail(CTM_ERR_ALIGN, "%s: gu and gop must be aligned to the element size", who);
+  for (int l = 0; l < m->L; ++l)
+    if ((gW && misaligned(gW[l], es)) || (gb && misaligned(gb[l], es)))
+      return fail(CTM_ERR_ALIGN, "%s: gW[%d] / gb[%d] not aligned to the element size", who, l, l);
+  if ((rc = check_device(m, who)) != CTM_OK) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const char *tp = (const char *)tape;
+  bool first = true;
+  for (int fam = 0; fam < 3; ++fam) {  // the families' contributions add up in this order; u enters through the first only
+    if (f.count[fam] == 0) continue;
+    if (m->dtype == CTM_F64)
+      rc = run_bwd<double>(m, 4, N, (int)f.count[fam], f.weight[fam], tp + t.off[fam], first ? (const double *)gu : nullptr,
+                           (const double *)gop, gW, gb, ws, st, first ? 0 : 1);
+    else
+      rc = run_bwd<float>(m, 4, N, (int)f.count[fam], f.weight[fam], tp + t.off[fam], first ? (const float *)gu : nullptr,
+                          (const float *)gop, gW, gb, ws, st, first ? 0 : 1);
+    if (rc != CTM_OK) return rc;
+    first = false;
+  }
+  return CTM_OK;
+}
+
 int ctm_biharmonic_exact(const ctm_mlp *m, const void *x, long N, void *u, void *op, void *ws, size_t ws_bytes,
                          void *stream) {
   const char *who = "ctm_biharmonic_exact";
@@ -934,12 +1067,10 @@ int ctm_biharmonic_exact(const ctm_mlp *m, const void *x, long N, void *u, void 
   if (int rc = check_device(m, who)) return rc;
   const int D = m->dims[0];
   // weights of the three direction families (final form of the interpolation formula, App. E.1)
-  const int i22[2] = {2, 2}, j40[2] = {4, 0}, j31[2] = {3, 1}, j22[2] = {2, 2};
-  const Frac g40 = interp_gamma(2, i22, j40), g31 = interp_gamma(2, i22, j31), g22 = interp_gamma(2, i22, j22);
-  const double G40 = (double)g40.n / g40.d, G31 = (double)g31.n / g31.d, G22 = (double)g22.n / g22.d;
-  const double weight[3] = {(2.0 * D * G40 + 2.0 * G31 + G22) / 24.0, 2.0 * G31 / 24.0, 2.0 * G22 / 24.0};
-  const long count[3] = {D, (long)D * (D - 1), (long)D * (D - 1) / 2};
-  const long rmax = D > 1 ? (long)D * (D - 1) : D;
+  const BiharmFamilies fams = biharm_families(D);
+  const double *weight = fams.weight;
+  const long *count = fams.count;
+  const long rmax = fams.rmax;
   const size_t vbytes = round256((size_t)rmax * D * es);
   void *vbuf = (char *)ws + (need - vbytes);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);

@@ -96,13 +96,14 @@ __global__ void colsum_stage1(const T *X, long row_stride, long second, int weig
 }
 
 // stage 2: out[j] = sum_c partial[c][j], j < d.  Block 0 also sums vec[n*vs], n < N, into vec_sum[0] if asked.
+// accumulate != 0: the sums are added to what out / vec_sum hold (several reverse passes into one gradient).
 template <typename T>
-__global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *vec, long vs, long N, T *vec_sum) {
+__global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *vec, long vs, long N, T *vec_sum, int accumulate) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j < d) {
     T acc = T(0);
     for (int c = 0; c < kSumChunks; ++c) acc += partial[(long)c * ld + j];
-    out[j] = acc;
+    out[j] = accumulate ? out[j] + acc : acc;
   }
   if (vec_sum != nullptr && blockIdx.x == 0) {
     // one wavefront sums the vector in a fixed order
@@ -116,13 +117,13 @@ __global__ void colsum_stage2(const T *partial, int ld, int d, T *out, const T *
       if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
       __syncthreads();
     }
-    if (threadIdx.x == 0) vec_sum[0] = red[0];
+    if (threadIdx.x == 0) vec_sum[0] = accumulate ? vec_sum[0] + red[0] : red[0];
   }
 }
 
 template <typename T>
 hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, int C, T *gw, T *gbias,
-                             T *scratch, hipStream_t s) {
+                             T *scratch, hipStream_t s, int accumulate) {
   // per output: the order-0 row weighted by gu[:, c] plus the collapsed row weighted by scale * gop[:, c]
   for (int c = 0; c < C; ++c) {
     const T *guc = gu ? gu + c : nullptr, *gopc = gop ? gop + c : nullptr;
@@ -131,29 +132,29 @@ hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double sc
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gw + (long)c * d, guc, (long)C, N,
-                       gbias + c);
+                       gbias + c, accumulate);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
 }
 template hipError_t launch_last_grads<float>(const float *, const float *, const float *, double, long, int, int, int, float *,
-                                             float *, float *, hipStream_t);
+                                             float *, float *, hipStream_t, int);
 template hipError_t launch_last_grads<double>(const double *, const double *, const double *, double, long, int, int, int, double *,
-                                              double *, double *, hipStream_t);
+                                              double *, double *, hipStream_t, int);
 
 template <typename T>
-hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s) {
+hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s, int accumulate) {
   hipLaunchKernelGGL(colsum_stage1<T>, dim3((ld + 255) / 256, kSumChunks), dim3(256), 0, s, Zbar, (long)rho * ld, (long)0, 0,
                      (const T *)nullptr, (const T *)nullptr, (long)1, 0.0, N, ld, scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_stage2<T>, dim3((ld + 255) / 256), dim3(256), 0, s, scratch, ld, d, gb, (const T *)nullptr, (long)1, (long)0,
-                     (T *)nullptr);
+                     (T *)nullptr, accumulate);
   return hipGetLastError();
 }
-template hipError_t launch_bias_grad<float>(const float *, long, int, int, int, float *, float *, hipStream_t);
-template hipError_t launch_bias_grad<double>(const double *, long, int, int, int, double *, double *, hipStream_t);
+template hipError_t launch_bias_grad<float>(const float *, long, int, int, int, float *, float *, hipStream_t, int);
+template hipError_t launch_bias_grad<double>(const double *, long, int, int, int, double *, double *, hipStream_t, int);
 
 // ---- weight gradient: C[i][j] = sum_m Zbar[m][i] H[m][j] ---------------------------------------------
 // Both operands are read as stored (k = row index m, feature index contiguous), so an LDS stage is
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T *Zb, int ld_out, con
 // the k range each (four running sums per thread keep several loads in flight), then the quarters are added.
 template <typename T>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const T *partials, int ksplit, long pi, long pj, int d_out, int d_in,
-                                                           T *gW) {
+                                                           T *gW, int accumulate) {
   __shared__ T red[4][64];
   const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
   const long total = (long)d_out * d_in;
@@ -326,12 +327,15 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const T *partials, in
   }
   red[g][o] = acc;
   __syncthreads();
-  if (g == 0 && idx < total) gW[idx] = (red[0][o] + red[1][o]) + (red[2][o] + red[3][o]);
+  if (g == 0 && idx < total) {
+    const T sum = (red[0][o] + red[1][o]) + (red[2][o] + red[3][o]);
+    gW[idx] = accumulate ? gW[idx] + sum : sum;
+  }
 }
 
 template <typename T>
 hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M, int d_out, int d_in, T *gW, T *partials,
-                        hipStream_t s) {
+                        hipStream_t s, int accumulate) {
   const WgradPlan p = wgrad_plan(M, d_out, d_in);
   constexpr size_t lds = 4 * (size_t)kWgK * kWgPitch * sizeof(T);
   static LdsLimitOnce lds_limit;
@@ -344,10 +348,10 @@ hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M
   const long blocks = ((long)d_out * d_in + 63) / 64;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(wgrad_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, partials, p.ksplit, (long)p.ti * kWgTile,
-                     (long)p.tj * kWgTile, d_out, d_in, gW);
+                     (long)p.tj * kWgTile, d_out, d_in, gW, accumulate);
   return hipGetLastError();
 }
-template hipError_t launch_wgrad<float>(const float *, int, const float *, int, long, int, int, float *, float *, hipStream_t);
-template hipError_t launch_wgrad<double>(const double *, int, const double *, int, long, int, int, double *, double *, hipStream_t);
+template hipError_t launch_wgrad<float>(const float *, int, const float *, int, long, int, int, float *, float *, hipStream_t, int);
+template hipError_t launch_wgrad<double>(const double *, int, const double *, int, long, int, int, double *, double *, hipStream_t, int);
 
 }  // namespace ctm

@@ -144,16 +144,17 @@ template <typename T> hipError_t launch_bwd_last(const BwdLastArgs<T> &a, hipStr
 // gbias[c] = sum_n gu[n][c]; scratch >= 65 * ld elements (reused output after output, in stream order)
 template <typename T>
 hipError_t launch_last_grads(const T *pair, const T *gu, const T *gop, double scale, long N, int ld, int d, int C, T *gw, T *gbias,
-                             T *scratch, hipStream_t s);
+                             T *scratch, hipStream_t s, int accumulate = 0);
 // gb[j] = sum_n Zbar[n * rho][j] (j < d); scratch >= 64 * ld elements
 template <typename T>
-hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s);
+hipError_t launch_bias_grad(const T *Zbar, long N, int rho, int ld, int d, T *gb, T *scratch, hipStream_t s, int accumulate = 0);
 // gW[i][j] = sum_m Zbar[m][i] * H[m][j], i < d_out, j < d_in (gW row-major [d_out][d_in]); split over row ranges,
-// partial sums in `partials` (wgrad_partial_elems elements), added in a fixed order
+// partial sums in `partials` (wgrad_partial_elems elements), added in a fixed order; accumulate != 0 in these three
+// launchers: add to what the output holds instead of overwriting it
 size_t wgrad_partial_elems(long M, int d_out, int d_in);
 template <typename T>
 hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M, int d_out, int d_in, T *gW, T *partials,
-                        hipStream_t s);
+                        hipStream_t s, int accumulate = 0);
 
 // Direction families of the exact biharmonic (interpolation with 4-jets): family 0: 4 e_d (D rows);
 // family 1: 3 e_d1 + e_d2, d1 != d2 (D(D-1) rows); family 2: 2 e_d1 + 2 e_d2, d1 < d2 (D(D-1)/2 rows).

@@ -127,7 +127,7 @@ def main():
               lambda m, x, u, op, w: ctm.ctm_biharmonic_exact(m, x, u, op, w),
               std_biharm,
               lambda N: lib.ctm_workspace_bytes_standard(mlp5.handle, 4, N, 20),
-              None)
+              lambda N: ctm.ctm_biharmonic_exact_tape_bytes(mlp5, N) + ctm.ctm_biharmonic_exact_backward_workspace_bytes(mlp5, N))
 
     # ---- stochastic operators: vary the number of samples at a fixed batch ---------------------------
     def stoch_row(name, mlp, D, K, N, Ss, col_fn, std_fn, diff_bytes, col_bytes=None):

@@ -101,6 +101,9 @@ def test_invalid_arguments_are_rejected_on_the_host():
     assert L.ctm_biharmonic_rand_fwd(None, None, 4, None, 5, 0, None, None, None, 0, None) == -1
     assert L.ctm_biharmonic_rand_bwd(None, 4, 5, None, 0, None, None, None, None, None, 0, None) == -1
     assert L.ctm_update_mlp(None, None, None, None) == -1
+    assert L.ctm_biharmonic_exact_fwd(None, None, 4, None, None, None, 0, None) == -1
+    assert L.ctm_biharmonic_exact_bwd(None, 4, None, 0, None, None, None, None, None, 0, None) == -1
+    assert L.ctm_biharmonic_exact_tape_bytes(None, 4) == 0 and L.ctm_biharmonic_exact_backward_workspace_bytes(None, 4) == 0
     for fn in (L.ctm_tape_bytes, L.ctm_backward_workspace_bytes, L.ctm_biharmonic_tape_bytes, L.ctm_biharmonic_backward_workspace_bytes):
         assert fn(None, 4, 5) == 0
     assert L.ctm_biharmonic_exact_workspace_bytes(None, 4) == 0

@@ -293,3 +293,69 @@ def test_autograd_wrapper_biharmonic():
     for l in range(3):
         assert rel(Ws[l].grad.cpu().numpy(), rW[l]) <= 1e-8 and rel(bs[l].grad.cpu().numpy(), rb[l]) <= 1e-8
     mlp.close()
+
+
+# ---- exact biharmonic: three order-4 tapes, three reverse passes added in a fixed order (Sec. 3.3, Eq. 12) ----
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N", [((1, 12, 1), 9), ((2, 16, 16, 1), 21), ((3, 24, 16, 2), 17), ((5, 32, 24, 1), 13)])
+def test_exact_biharmonic_weight_gradients_against_the_autograd_oracle(dtype, dims, N):
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import gradients as og
+    Ws, bs = synth.make_mlp(dims, N, 0.1, dtype)
+    x = synth.make_points(N, dims[0], N, dtype)
+    C = dims[-1]
+    rng = np.random.default_rng(N)
+    shape = (N,) if C == 1 else (N, C)
+    gu, gop = rng.standard_normal(shape).astype(dtype), rng.standard_normal(shape).astype(dtype)
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    print(f"case exact biharmonic backward dims={dims} N={N} {dtype.__name__}", flush=True)
+    mlp = ctm.ctm_create_mlp([t(W) for W in Ws], [t(b) for b in bs])
+    u, op, tape = ctm.ctm_biharmonic_exact_fwd(mlp, t(x))
+    u2, op2 = ctm.ctm_biharmonic_exact(mlp, t(x))
+    gW, gb = ctm.ctm_biharmonic_exact_bwd(mlp, N, tape, t(gu), t(gop))
+    gW2, gb2 = ctm.ctm_biharmonic_exact_bwd(mlp, N, tape, t(gu), t(gop))
+    torch.cuda.synchronize()
+    tolf = 1e-12 if dtype == np.float64 else 2e-5
+    assert (u - u2).abs().max().item() <= tolf * u2.abs().max().item()
+    assert (op - op2).abs().max().item() <= tolf * op2.abs().max().item()
+    for a, b in zip(gW + gb, gW2 + gb2):
+        assert torch.equal(a, b)   # accumulation over the families happens in a fixed order
+    _, rW, rb = og.biharmonic_exact_loss_grads(Ws, bs, x, gu.astype(np.float64), gop.astype(np.float64))
+    tol = 1e-9 if dtype == np.float64 else 2e-4
+    for l in range(len(dims) - 1):
+        eW, eb = rel(gW[l].double().cpu().numpy(), rW[l]), rel(gb[l].double().cpu().numpy(), rb[l])
+        print(f"  layer {l}: dW err {eW:.2e}  db err {eb:.2e}", flush=True)
+        assert eW <= tol and eb <= tol, (l, eW, eb)
+    mlp.close()
+
+
+def test_exact_biharmonic_autograd_wrapper_and_dimension_limit():
+    import torch
+    import paper_2505_13644_amd as ctm
+    from paper_2505_13644_amd.autograd import biharmonic_exact
+    from oracle import gradients as og
+    dev = torch.device("cuda:0")
+    dims, N = (2, 20, 20, 1), 30
+    Wn, bn = synth.make_mlp(dims, 21, 0.05, np.float64)
+    Ws = [torch.tensor(W, device=dev, requires_grad=True) for W in Wn]
+    bs = [torch.tensor(b, device=dev, requires_grad=True) for b in bn]
+    xn = synth.make_points(N, 2, 21, np.float64)
+    mlp = ctm.ctm_create_mlp([W.detach() for W in Ws], [b.detach() for b in bs])
+    u, op = biharmonic_exact(mlp, Ws, bs, torch.tensor(xn, device=dev))
+    loss = ((op - 1.0) ** 2).mean() + (u ** 2).mean()
+    loss.backward()
+    gu, gop = (2 * u / N).detach().cpu().numpy(), (2 * (op - 1.0) / N).detach().cpu().numpy()
+    _, rW, rb = og.biharmonic_exact_loss_grads(Wn, bn, xn, gu, gop)
+    for l in range(3):
+        assert rel(Ws[l].grad.cpu().numpy(), rW[l]) <= 1e-8 and rel(bs[l].grad.cpu().numpy(), rb[l]) <= 1e-8
+    mlp.close()
+    # D (D - 1) directions must fit one pass: D = 10 is refused on the host
+    W10, b10 = synth.make_mlp((10, 16, 1), 1, 0.0, np.float32)
+    m10 = ctm.ctm_create_mlp([torch.tensor(W, device=dev) for W in W10], None)
+    with pytest.raises(ctm.CtmError) as ei:
+        ctm.ctm_biharmonic_exact_tape_bytes(m10, 4)
+    assert "at most 84" in str(ei.value)
+    m10.close()
