@@ -359,3 +359,40 @@ def test_exact_biharmonic_autograd_wrapper_and_dimension_limit():
         ctm.ctm_biharmonic_exact_tape_bytes(m10, 4)
     assert "at most 84" in str(ei.value)
     m10.close()
+
+
+def test_full_size_gradients_are_additive_over_the_batch():
+    # At the benchmark size the oracle cannot follow (4096 Hessians of a 768-wide network), but the loss is a sum over
+    # points, so the gradient of the full batch must equal the sum of the gradients of its two halves (each half takes
+    # different row partitions in the weight-gradient GEMM), and a 32-point slice is checked against the oracle.
+    import torch
+    import paper_2505_13644_amd as ctm
+    from oracle import gradients as og
+    w = synth.WORKLOADS["c2"]
+    arrs = w.build()
+    N = w.N
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    rng = np.random.default_rng(11)
+    gu, gop = rng.standard_normal(N).astype(np.float32), rng.standard_normal(N).astype(np.float32)
+    x = t(arrs["x"])
+
+    def grads(sl):
+        n = sl.stop - sl.start
+        u, op, tape = ctm.ctm_laplacian_fwd(mlp, x[sl].contiguous(), None, 1.0)
+        gW, gb = ctm.ctm_laplacian_bwd(mlp, n, 50, 1.0, tape, t(gu[sl]), t(gop[sl]))
+        torch.cuda.synchronize()
+        return [g.double() for g in gW] + [g.double() for g in gb]
+
+    full = grads(slice(0, N))
+    a, b = grads(slice(0, N // 2)), grads(slice(N // 2, N))
+    for i, (f, p, q) in enumerate(zip(full, a, b)):
+        e = ((f - (p + q)).abs().max() / f.abs().max()).item()
+        assert e <= 1e-4, (i, e)
+    part = grads(slice(100, 132))
+    _, rW, rb = og.laplacian_loss_grads(arrs["Ws"], arrs["bs"], arrs["x"][100:132], None, 1.0,
+                                        gu[100:132].astype(np.float64), gop[100:132].astype(np.float64))
+    for i, ref in enumerate(rW + rb):
+        assert rel(part[i].cpu().numpy(), ref) <= 2e-4, i
+    mlp.close()
