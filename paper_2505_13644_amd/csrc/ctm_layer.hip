@@ -24,6 +24,8 @@
 // consecutive k values with one 16-byte LDS read and feeds them to KV successive MFMAs; since
 // A and B use the same assignment, the k-sum is merely taken in a permuted order.
 #include "ctm_internal.h"
+#include <type_traits>
+
 #include "ctm_rule.h"
 
 namespace ctm {
@@ -171,10 +173,6 @@ void layer_kernel(const LayerArgs<T> a) {
   };
 
   vacc acc[MB][NB];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = vacc{0, 0, 0, 0};
 
   // ---- k loop.  A stage is one k-block of BK = 4*KV values, i.e. MB steps of NB*KV MFMAs (one A
   // fragment against the NB B fragments).  The loop body covers two stages so that every LDS
@@ -199,8 +197,12 @@ void layer_kernel(const LayerArgs<T> a) {
   for (int nb = 0; nb < NB; ++nb) bf[0][nb] = *reinterpret_cast<const vld *>(Br + nb * 64 * LROW);
   af[0] = *reinterpret_cast<const vld *>(Ar);
 
+  // The first pair of stages is a copy of the loop body whose first MFMA per accumulator takes a literal zero as its C
+  // operand: no vector-ALU instructions to clear the accumulators (those of a starting workgroup would take issue
+  // cycles from the MFMAs of the workgroup it shares the CU with).
   const int k_last = a.ldin - BK;
-  for (int kp = 0; kp < npairs; ++kp) {
+  auto stage_pair = [&](int kp, auto first_tag) {
+    constexpr bool kFirst = decltype(first_tag)::value;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       // stage `half` reads LDS buffer `half`; the next k-block goes straight to the other buffer, which every wave
@@ -226,11 +228,14 @@ void layer_kernel(const LayerArgs<T> a) {
 #pragma unroll
         for (int j = 0; j < KV; ++j)
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) acc[st][nb] = mfma16(af[s & 1][j], bf[half][nb][j], acc[st][nb]);
+          for (int nb = 0; nb < NB; ++nb)
+            acc[st][nb] = mfma16(af[s & 1][j], bf[half][nb][j], (kFirst && half == 0 && j == 0) ? vacc{0, 0, 0, 0} : acc[st][nb]);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-  }
+  };
+  stage_pair(0, std::true_type{});
+  for (int kp = 1; kp < npairs; ++kp) stage_pair(kp, std::false_type{});
   // Each wave's last real fragment read and its last (surplus) loads completed before it entered the final barrier
   // above, so the stages can be reused for the C tile right away (the fragments fetched after that barrier are unused).
 
@@ -256,15 +261,16 @@ void layer_kernel(const LayerArgs<T> a) {
     const long ostep = a.ldout;
     if constexpr (WPP == 1) {  // a wavefront per point
       if (col_ok) {
-        for (int p = wave; p < p_valid; p += kThreads / 64) {
-          const T *c = Cs + (long)p * rho * CROW + j;
+        for (int p = wave_u; p < p_valid; p += kThreads / 64) {
+          const T *c = Cs + p * rho * CROW + j;
           const long n = p0 + p;
+          const long jg0 = (long)col_tile * BN + nb * 64;  // the wavefront's first column: n, jg0 are wavefront-uniform
           T *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
           if (a.bwd) {
             jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg, a.ldout, o, ostep, a);
           } else {
             if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
-            jet_rule<T>(c, CROW, bias, o, ostep, a);
+            jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))}, a);
           }
         }
       }

@@ -49,15 +49,34 @@ template <typename T> __device__ __forceinline__ T act_d5(int act, T t, T d1) {
 }
 
 // Where the rule's output rows go: `put(row, v)` stores the value of coefficient row `row` of the pair's column.
+// The column's address is `o` plus `lane_bytes`.  A caller whose wavefront works on one point passes a wavefront-uniform
+// `o` (the point's row 0 at the wavefront's first column) and the lane's column in `lane_bytes`: the row address is then
+// scalar arithmetic and the store takes it from SGPRs, which keeps 64-bit vector adds out of the rule's loop (vector-ALU
+// instructions of the rule take issue cycles away from the MFMAs of the workgroup that shares the CU).
 template <typename T> struct PlainRows {  // rows of T, `step` elements apart
   T *o;
   long step;
-  __device__ __forceinline__ void put(long row, T v) const { o[row * step] = v; }
+  mutable unsigned lane_bytes = 0;
+  __device__ __forceinline__ void put(long row, T v) const { store(row_base(row), lane_bytes, v); }
+  // the pieces of put(), for loops that keep the row address themselves (base: start of a row, voff: lane offset in bytes)
+  __device__ __forceinline__ char *row_base(long row) const { return reinterpret_cast<char *>(o + row * step); }
+  __device__ __forceinline__ long step_bytes() const { return step * (long)sizeof(T); }
+  __device__ __forceinline__ void store(char *base, unsigned &voff, T v) const {
+    asm volatile("" : "+v"(voff));  // keeps the 32 -> 64 bit extension next to the store, where it folds into the address mode
+    *reinterpret_cast<T *>(base + voff) = v;
+  }
 };
 struct Bf16Rows {  // rows of bf16 (the block between the layers of a plain-bf16 handle)
   __bf16 *o;
   long step;
-  __device__ __forceinline__ void put(long row, float v) const { o[row * step] = (__bf16)v; }
+  mutable unsigned lane_bytes = 0;
+  __device__ __forceinline__ void put(long row, float v) const { store(row_base(row), lane_bytes, v); }
+  __device__ __forceinline__ char *row_base(long row) const { return reinterpret_cast<char *>(o + row * step); }
+  __device__ __forceinline__ long step_bytes() const { return step * 2; }
+  __device__ __forceinline__ void store(char *base, unsigned &voff, float v) const {
+    asm volatile("" : "+v"(voff));
+    *reinterpret_cast<__bf16 *>(base + voff) = (__bf16)v;
+  }
 };
 
 // c: the pair's column in the staged C tile (row pitch CROW elements, rows = the point's coefficient rows).
@@ -123,14 +142,32 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
   if (a.order == 2) {
     if (active) {
       int i0 = 0;
-      for (; i0 + 3 < R; i0 += 4) {  // NG independent LDS reads in flight per trip
-        T z1[NG];
+      if (a.last) {
+        for (; i0 + 3 < R; i0 += 4) {  // NG independent LDS reads in flight per trip
+          T z1[NG];
 #pragma unroll
-        for (int k = 0; k < NG; ++k) z1[k] = c[(long)(1 + i0 + sub + k * WPP) * CROW];
+          for (int k = 0; k < NG; ++k) z1[k] = c[(1 + i0 + sub + k * WPP) * CROW];
 #pragma unroll
-        for (int k = 0; k < NG; ++k) {
-          sg[k] += z1[k] * z1[k];
-          if (!a.last) out.put(1 + i0 + sub + k * WPP, d1 * z1[k]);
+          for (int k = 0; k < NG; ++k) sg[k] += z1[k] * z1[k];
+        }
+      } else {
+        // one row address per trip (scalar when `out.o` is wavefront-uniform) and one constant lane offset per group:
+        // the loop body is 2 LDS reads, 2 vector-ALU instructions and 1 store per direction plus a handful of scalar ones
+        unsigned voff[NG];
+#pragma unroll
+        for (int k = 0; k < NG; ++k) voff[k] = out.lane_bytes + (unsigned)((sub + k * WPP) * out.step_bytes());
+        char *rb = out.row_base(1);
+        const long bump = 4 * out.step_bytes();
+        const T *cr = c + CROW;
+        for (; i0 + 3 < R; i0 += 4, rb += bump, cr += 4 * CROW) {
+          T z1[NG];
+#pragma unroll
+          for (int k = 0; k < NG; ++k) z1[k] = cr[(sub + k * WPP) * CROW];
+#pragma unroll
+          for (int k = 0; k < NG; ++k) {
+            sg[k] += z1[k] * z1[k];
+            out.store(rb, voff[k], d1 * z1[k]);
+          }
         }
       }
 #pragma unroll
@@ -188,7 +225,7 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
 // o: the pair's column in an output block of plain rows (row pitch ostep elements).
 template <typename T>
 __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, long ostep, const LayerArgs<T> &a) {
-  jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{o, ostep}, a);
+  jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{o, ostep, 0u}, a);
 }
 
 // Record the pre-activation rows of one (point, feature) pair (bias on the order-0 row only).
