@@ -265,26 +265,29 @@ void layer_kernel(const LayerArgs<T> a) {
           const T *c = Cs + p * rho * CROW + j;
           const long n = p0 + p;
           const long jg0 = (long)col_tile * BN + nb * 64;  // the wavefront's first column: n, jg0 are wavefront-uniform
-          T *o = a.Hout + (n * a.out_rows) * a.ldout + jg;
+          const unsigned voff = (unsigned)(j * sizeof(T));
+          T *o = a.Hout + (n * a.out_rows) * a.ldout + jg0;
           if (a.bwd) {
-            jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg, a.ldout, o, ostep, a);
+            jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg0, a.ldout, o, ostep, voff, a);
           } else {
-            if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
-            jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))}, a);
+            if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, voff, rho);
+            jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{o, ostep, voff}, a);
           }
         }
       }
     } else {
       // tiles of one or two points: the point's directions are shared out over 4 or 2 wavefronts (every thread
       // takes part: the rule holds a barrier)
-      const int p = WPP == 2 ? (wave >> 1) : 0;
-      const int sub = WPP == 2 ? (wave & 1) : wave;
+      const int p = WPP == 2 ? (wave_u >> 1) : 0;
+      const int sub = WPP == 2 ? (wave_u & 1) : wave_u;
       const bool active = col_ok && p < p_valid;
-      const T *c = Cs + (long)p * rho * CROW + j;
+      const T *c = Cs + p * rho * CROW + j;
       const long n = p0 + p;
-      const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg, ostep};
+      const long jg0 = (long)col_tile * BN + nb * 64;
+      const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))};
       T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 4 * 64 + j;
-      if (a.Zout && active && sub == 0) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg, a.ldout, rho);
+      if (a.Zout && active && sub == 0)
+        save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, (unsigned)(j * sizeof(T)), rho);
       jet_rule<T, PlainRows<T>, WPP>(c, CROW, bias, out, a, active, sub, red);
     }
   }

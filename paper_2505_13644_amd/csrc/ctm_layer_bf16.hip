@@ -290,20 +290,21 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     const long jg = (long)col_tile * BN + chunk * 64 + j;
     const bool col_ok = jg < a.ldout;
     const float bias = col_ok ? a.bias[jg] : 0.f;
+    // n (the point) is wavefront-uniform: the output row addresses are scalar, the lane's column is a byte offset
     auto rule = [&](const float *c, long n, bool active, int sub, float *red) {
-      const long o_off = (n * a.out_rows) * a.ldout + jg;
+      const long o_off = (n * a.out_rows) * a.ldout + (long)col_tile * BN + chunk * 64;
       if (a.out_bf16)
-        jet_rule<float, Bf16Rows, WPP>(c, CROW, bias, Bf16Rows{reinterpret_cast<__bf16 *>(a.Hout) + o_off, a.ldout}, a, active, sub, red);
+        jet_rule<float, Bf16Rows, WPP>(c, CROW, bias, Bf16Rows{reinterpret_cast<__bf16 *>(a.Hout) + o_off, a.ldout, (unsigned)(j * 2)}, a, active, sub, red);
       else
-        jet_rule<float, PlainRows<float>, WPP>(c, CROW, bias, PlainRows<float>{a.Hout + o_off, a.ldout}, a, active, sub, red);
+        jet_rule<float, PlainRows<float>, WPP>(c, CROW, bias, PlainRows<float>{a.Hout + o_off, a.ldout, (unsigned)(j * 4)}, a, active, sub, red);
     };
     if constexpr (WPP == 1) {  // a wavefront per point
       if (col_ok)
-        for (int p = wave; p < p_valid; p += kThreadsB / 64)
-          rule(Cs + (long)p * rho * CROW + j, p0 + p, true, 0, nullptr);
+        for (int p = wave_u; p < p_valid; p += kThreadsB / 64)
+          rule(Cs + p * rho * CROW + j, p0 + p, true, 0, nullptr);
     } else {  // one or two points per tile: 4 or 2 wavefronts share a point's directions (see jet_rule)
-      const int p = WPP == 2 ? (wave >> 1) : 0;
-      const int sub = WPP == 2 ? (wave & 1) : wave;
+      const int p = WPP == 2 ? (wave_u >> 1) : 0;
+      const int sub = WPP == 2 ? (wave_u & 1) : wave_u;
       const bool active = col_ok && p < p_valid;
       float *red = reinterpret_cast<float *>(lds_raw + TL::kRedOffset) + p * 4 * 64 + j;
       rule(Cs + (long)p * rho * CROW + j, p0 + p, active, sub, red);

@@ -228,11 +228,23 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, T *o, lon
   jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{o, ostep, 0u}, a);
 }
 
-// Record the pre-activation rows of one (point, feature) pair (bias on the order-0 row only).
+// Element at byte offset `voff` (the lane's column) of a row whose start `row` is the same for the whole wavefront:
+// the address is a scalar base plus a 32-bit lane offset, i.e. no vector-ALU address arithmetic.
+template <typename T> __device__ __forceinline__ T lane_load(const T *row, unsigned &voff) {
+  asm volatile("" : "+v"(voff));  // see PlainRows::store
+  return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(row) + voff);
+}
+template <typename T> __device__ __forceinline__ void lane_store(T *row, unsigned &voff, T v) {
+  asm volatile("" : "+v"(voff));
+  *reinterpret_cast<T *>(reinterpret_cast<char *>(row) + voff) = v;
+}
+
+// Record the pre-activation rows of one (point, feature) pair (bias on the order-0 row only).  zo: the point's row 0
+// at the wavefront's first column (wavefront-uniform), voff: the lane's column in bytes.
 template <typename T>
-__device__ __forceinline__ void save_preactivations(const T *c, int CROW, T bias, T *zo, long zstep, int rho) {
-  zo[0] = c[0] + bias;
-  for (int r = 1; r < rho; ++r) zo[r * zstep] = c[(long)r * CROW];
+__device__ __forceinline__ void save_preactivations(const T *c, int CROW, T bias, T *zo, long zstep, unsigned voff, int rho) {
+  lane_store<T>(zo, voff, c[0] + bias);
+  for (int r = 1; r < rho; ++r) lane_store<T>(zo + r * zstep, voff, c[r * CROW]);
 }
 
 // Reverse of the collapsed rule for one (point, feature) pair.  z are the recorded pre-activations, hb the
@@ -248,48 +260,51 @@ __device__ __forceinline__ void save_preactivations(const T *c, int CROW, T bias
 //   zb_{1,r} = d1 hb_1 + 2 d2 z1 hb_2 + 3 (d3 z1^2 + d2 z2) hb_3 + 4 (d4 z1^3 + 3 d3 z1 z2 + d2 z3) hb_4
 //   zb_0     = d1 hb_0 + sum_r [ d2 z1 hb_1 + (d3 z1^2 + d2 z2) hb_2 + (d4 z1^3 + 3 d3 z1 z2 + d2 z3) hb_3 ]
 //              + hb_4 [ d2 z_4 + sum_r (d5 z1^4 + 6 d4 z1^2 z2 + 4 d3 z1 z3 + 3 d3 z2^2) ]
-// c: cotangent column in the staged C tile; zs: recorded column; o: output column.
+// c: cotangent column in the staged C tile; zs / o: the point's row 0 of the recorded block / of the output block at the
+// wavefront's first column (wavefront-uniform); voff: the lane's column in bytes.
 template <typename T>
-__device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, long zstep, T *o, long ostep, const LayerArgs<T> &a) {
+__device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, long zstep, T *o, long ostep, unsigned voff,
+                                             const LayerArgs<T> &a) {
   const int R = a.R;
-  const T z0 = zs[0];
+  const T z0 = lane_load<T>(zs, voff);
   T t, d1;
   act_eval<T>(a.act, z0, t, d1);
   const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
   if (a.order == 2) {
-    const T hb0 = c[0], hb2 = c[(long)(R + 1) * CROW];
-    const T z2 = zs[(long)(R + 1) * zstep];
+    const T hb0 = c[0], hb2 = c[(R + 1) * CROW];
+    const T z2 = lane_load<T>(zs + (R + 1) * zstep, voff);
+    const T w = T(2) * d2 * hb2;
     T s = T(0), dot = T(0);
     for (int r = 1; r <= R; ++r) {
-      const T z1 = zs[(long)r * zstep], hb1 = c[(long)r * CROW];
+      const T z1 = lane_load<T>(zs + r * zstep, voff), hb1 = c[r * CROW];
       s += z1 * z1;
       dot += hb1 * z1;
-      o[r * ostep] = d1 * hb1 + T(2) * d2 * z1 * hb2;
+      lane_store<T>(o + r * ostep, voff, d1 * hb1 + w * z1);
     }
-    o[(R + 1) * ostep] = d1 * hb2;
-    o[0] = d1 * hb0 + d2 * (dot + hb2 * z2) + d3 * s * hb2;
+    lane_store<T>(o + (R + 1) * ostep, voff, d1 * hb2);
+    lane_store<T>(o, voff, d1 * hb0 + d2 * (dot + hb2 * z2) + d3 * s * hb2);
   } else {
     const T d4 = act_d4<T>(a.act, t, d1), d5 = act_d5<T>(a.act, t, d1);
-    const T hb0 = c[0], hb4 = c[(long)(3 * R + 1) * CROW];
-    const T z4 = zs[(long)(3 * R + 1) * zstep];
+    const T hb0 = c[0], hb4 = c[(3 * R + 1) * CROW];
+    const T z4 = lane_load<T>(zs + (3 * R + 1) * zstep, voff);
     T acc = T(0), s4 = T(0);
     for (int r = 0; r < R; ++r) {
-      const T *zr = zs + (long)(1 + 3 * r) * zstep;
-      const T *cr = c + (long)(1 + 3 * r) * CROW;
-      T *orow = o + (long)(1 + 3 * r) * ostep;
-      const T z1 = zr[0], z2 = zr[zstep], z3 = zr[2 * zstep];
+      const T *zr = zs + (1 + 3 * r) * zstep;
+      const T *cr = c + (1 + 3 * r) * CROW;
+      T *orow = o + (1 + 3 * r) * ostep;
+      const T z1 = lane_load<T>(zr, voff), z2 = lane_load<T>(zr + zstep, voff), z3 = lane_load<T>(zr + 2 * zstep, voff);
       const T hb1 = cr[0], hb2 = cr[CROW], hb3 = cr[2 * CROW];
       const T z1s = z1 * z1;
       const T p2 = d3 * z1s + d2 * z2;                              // d h_2 / d z_0
       const T p3 = d4 * z1s * z1 + T(3) * d3 * z1 * z2 + d2 * z3;   // d h_3 / d z_0
-      orow[0] = d1 * hb1 + T(2) * d2 * z1 * hb2 + T(3) * p2 * hb3 + T(4) * p3 * hb4;
-      orow[ostep] = d1 * hb2 + T(3) * d2 * z1 * hb3 + T(6) * p2 * hb4;
-      orow[2 * ostep] = d1 * hb3 + T(4) * d2 * z1 * hb4;
+      lane_store<T>(orow, voff, d1 * hb1 + T(2) * d2 * z1 * hb2 + T(3) * p2 * hb3 + T(4) * p3 * hb4);
+      lane_store<T>(orow + ostep, voff, d1 * hb2 + T(3) * d2 * z1 * hb3 + T(6) * p2 * hb4);
+      lane_store<T>(orow + 2 * ostep, voff, d1 * hb3 + T(4) * d2 * z1 * hb4);
       acc += d2 * z1 * hb1 + p2 * hb2 + p3 * hb3;
       s4 += d5 * z1s * z1s + T(6) * d4 * z1s * z2 + T(4) * d3 * z1 * z3 + T(3) * d3 * z2 * z2;
     }
-    o[(long)(3 * R + 1) * ostep] = d1 * hb4;
-    o[0] = d1 * hb0 + acc + hb4 * (d2 * z4 + s4);
+    lane_store<T>(o + (3 * R + 1) * ostep, voff, d1 * hb4);
+    lane_store<T>(o, voff, d1 * hb0 + acc + hb4 * (d2 * z4 + s4));
   }
 }
 
