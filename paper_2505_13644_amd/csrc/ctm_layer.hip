@@ -67,23 +67,34 @@ template <typename T, int MB> struct Tile {
   static constexpr int A_STAGE = BM * LROW;
   static constexpr int B_STAGE = BN * LROW;
   static constexpr int CCOLS = 64;                // the C tile is staged 64 columns at a time
-  static constexpr int CROW = CCOLS + PADE;       // LDS row pitch of the staged C chunk
+  // LDS row pitch of the staged C chunk: padded so that the four row groups of an accumulator store hit different
+  // banks -- unless the pad is what keeps a third workgroup off the CU (MB = 13 in fp32: 52 KiB without, 55 KiB with)
+  static constexpr size_t kCuLds = 160 * 1024;
   static constexpr size_t kStageBytes = 2 * (size_t)(A_STAGE + B_STAGE) * sizeof(T);
+  static constexpr bool kDropPad = 3 * (size_t)BM * (CCOLS + PADE) * sizeof(T) > kCuLds && 3 * (size_t)BM * CCOLS * sizeof(T) <= kCuLds &&
+                                   3 * kStageBytes <= kCuLds;
+  static constexpr int CROW = CCOLS + (kDropPad ? 0 : PADE);
   static constexpr size_t kCBytes = (size_t)BM * CROW * sizeof(T);
-  // behind them: the group sums that wavefronts sharing a point exchange (2 point slots x 4 groups x 64 columns)
+  // behind them: the group sums that wavefronts sharing a point hand to the point's first wavefront (two points x 2
+  // slots when two wavefronts share a point, one point x 3 slots when four do; 64 columns per slot)
   static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
-  static constexpr size_t kRedBytes = 2 * 4 * 64 * sizeof(T);   // only allocated by the kernels that share points (WPP > 1)
+  static constexpr size_t kRedBytes = 4 * 64 * sizeof(T);   // only allocated by the kernels that share points (WPP > 1)
+  // Workgroups per CU the kernel is compiled for (= waves per SIMD: the register budget is 512 / that, rounded down to 8):
+  // the accumulators alone take 8 * MB registers (fp32: MB x 2 column blocks x 4; fp64: MB x 1 x 8).
+  static constexpr int kWgPerCu = MB <= 9 ? 4 : MB <= 13 ? 3 : 2;
   static constexpr size_t kLdsBytes = kRedOffset + kRedBytes;
   static_assert(BK * sizeof(T) == 64 && BN % 16 == 0, "a 16-row chunk of a stage is one 1 KiB LDS-direct load");
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
 };
 
-// amdgpu_waves_per_eu(2, 2) caps the kernel at 256 registers per lane.  With the cap the compiler
-// keeps the accumulators in ordinary VGPRs and issues MFMAs on them directly; without it (512
-// registers allowed) it parks them in AGPRs and copies each block back and forth around every
-// MFMA group, which left the matrix pipe idle almost half of the time.
+// amdgpu_waves_per_eu caps the registers per lane (4 waves per SIMD: 128, 3: 168, 2: 256).  With a cap the compiler
+// keeps the accumulators in ordinary VGPRs and issues MFMAs on them directly; without one (512 registers allowed) it
+// parks them in AGPRs and copies each block back and forth around every MFMA group, which left the matrix pipe idle
+// almost half of the time.  Three or four resident workgroups instead of two matter because a workgroup spends more
+// than half of its life outside the k loop (prologue, epilogue: their vector-ALU instructions only get the issue slots
+// the MFMA stream of a co-resident workgroup leaves): the more neighbours, the rarer the moments without MFMAs in flight.
 template <typename T, int MB, int WPP>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Tile<T, MB>::kWgPerCu, Tile<T, MB>::kWgPerCu)))
 void layer_kernel(const LayerArgs<T> a) {
   using TL = Tile<T, MB>;
   using vld = typename Vec<T>::ld;
@@ -285,7 +296,7 @@ void layer_kernel(const LayerArgs<T> a) {
       const long n = p0 + p;
       const long jg0 = (long)col_tile * BN + nb * 64;
       const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))};
-      T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 4 * 64 + j;
+      T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 2 * 64 + j;  // p > 0 only when two wavefronts share a point
       if (a.Zout && active && sub == 0)
         save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, (unsigned)(j * sizeof(T)), rho);
       jet_rule<T, PlainRows<T>, WPP>(c, CROW, bias, out, a, active, sub, red);

@@ -44,7 +44,10 @@ template <int MB, int NSPLIT> struct TileB {
   static constexpr int UPR = BK / 8;              // 8-element units per row (= 4)
   static constexpr int A_LD = (BM * UPR + kThreadsB - 1) / kThreadsB;
   static constexpr int B_LD = (BN * UPR) / kThreadsB;          // per plane
-  static constexpr int CROW = 64 + 4;
+  // Workgroups per CU the kernel is compiled for: the plain variant's registers (8 * MB accumulators + fragments) allow
+  // three up to MB = 13; its staged C chunk then drops the bank-conflict pad at MB = 13, which is what lets the third fit
+  static constexpr int kWgPerCu = (NSPLIT == 1 && MB <= 13) ? 3 : 2;
+  static constexpr int CROW = 64 + ((kWgPerCu == 3 && 3 * (size_t)BM * 68 * 4 > 160 * 1024) ? 0 : 4);
   // The split variant keeps ONE stage in LDS (two barriers per k step) so that two workgroups fit a
   // CU and cover each other's barriers, conversions and load latency; the plain variant's stage is
   // half as large and is double-buffered.
@@ -53,7 +56,7 @@ template <int MB, int NSPLIT> struct TileB {
   static constexpr size_t kCBytes = (size_t)BM * CROW * 4;
   // behind them: the group sums that wavefronts sharing a point exchange (2 point slots x 4 groups x 64 columns)
   static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
-  static constexpr size_t kRedBytes = 2 * 4 * 64 * sizeof(float);   // only allocated by the kernels that share points (WPP > 1)
+  static constexpr size_t kRedBytes = 4 * 64 * sizeof(float);   // only allocated by the kernels that share points (WPP > 1)
   static constexpr size_t kLdsBytes = kRedOffset + kRedBytes;
   static_assert(kLdsBytes <= 160 * 1024, "tile does not fit the 160 KiB LDS of a CU");
 };
@@ -70,7 +73,7 @@ __device__ __forceinline__ void split8(const f32x4 &x0, const f32x4 &x1, bf16x8 
 }
 
 template <int MB, int NSPLIT, int WPP>
-__global__ __launch_bounds__(kThreadsB) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ __launch_bounds__(kThreadsB) __attribute__((amdgpu_waves_per_eu(TileB<MB, NSPLIT>::kWgPerCu, TileB<MB, NSPLIT>::kWgPerCu)))
 void layer_kernel_bf16(const LayerArgs<float> a) {
   using TL = TileB<MB, NSPLIT>;
   constexpr int MBH = TL::MBH, BN = TL::BN, BK = TL::BK, PITCH = TL::PITCH, UPR = TL::UPR, CROW = TL::CROW;
@@ -306,7 +309,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
       const int p = WPP == 2 ? (wave_u >> 1) : 0;
       const int sub = WPP == 2 ? (wave_u & 1) : wave_u;
       const bool active = col_ok && p < p_valid;
-      float *red = reinterpret_cast<float *>(lds_raw + TL::kRedOffset) + p * 4 * 64 + j;
+      float *red = reinterpret_cast<float *>(lds_raw + TL::kRedOffset) + p * 2 * 64 + j;
       rule(Cs + (long)p * rho * CROW + j, p0 + p, active, sub, red);
     }
   }

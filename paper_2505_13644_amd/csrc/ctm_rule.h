@@ -84,7 +84,8 @@ struct Bf16Rows {  // rows of bf16 (the block between the layers of a plain-bf16
 // The sum over directions is always taken the same way: direction i (counted from 0) belongs to group i % 4, each
 // group is summed in order of i, and the four group sums are combined as (g0 + g1) + (g2 + g3).  WPP wavefronts
 // (1, 2 or 4) share a point: wavefront `sub` takes the groups sub, sub + WPP, ... and writes their per-direction rows;
-// for WPP > 1 the group sums meet in LDS (`red`: this pair's first slot, group stride 64 elements) and wavefront 0
+// for WPP > 1 the group sums of the other wavefronts reach wavefront 0 through LDS (`red`: this pair's first slot, slot
+// stride 64 elements, kRedSlots(WPP) slots per point) and wavefront 0
 // writes the collapsed row.  The result is therefore bit-identical for every WPP, i.e. for every tile shape.
 // With WPP > 1 every thread of the workgroup must make the call (it holds a barrier); threads without a valid
 // pair pass active = false.  Un-collapsed (standard) mode has no sum and is only built for WPP = 1.
@@ -207,11 +208,16 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
     if (!active) return;
     s = (sg[0] + sg[1]) + (sg[2] + sg[3]);
   } else {
+    // wavefronts 1 .. WPP-1 hand their group sums to wavefront 0: slot (group - 1) / 2 for WPP = 2 (groups 1, 3),
+    // slot group - 1 for WPP = 4 (groups 1, 2, 3)
+    if (sub != 0) {
 #pragma unroll
-    for (int k = 0; k < NG; ++k) red[(sub + k * WPP) * 64] = sg[k];
+      for (int k = 0; k < NG; ++k) red[(WPP == 2 ? k : sub - 1) * 64] = sg[k];
+    }
     __syncthreads();
     if (!active || sub != 0) return;
-    s = (red[0] + red[64]) + (red[128] + red[192]);
+    if constexpr (WPP == 2) s = (sg[0] + red[0]) + (sg[1] + red[64]);
+    else s = (sg[0] + red[0]) + (red[64] + red[128]);
   }
   if (a.order == 2) {
     const T z2 = c[(long)(R + 1) * CROW];
