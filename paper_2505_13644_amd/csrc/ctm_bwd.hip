@@ -11,6 +11,8 @@
 //                      Hbar_prev = Zbar W, then the reverse rule                                -> layer_kernel (bwd)
 // All reductions over points use fixed partitions and a fixed summation order (no atomics).
 #include "ctm_internal.h"
+
+#include <type_traits>
 #include "ctm_rule.h"
 
 namespace ctm {
@@ -298,6 +300,149 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T *Zb, int ld_out, con
       }
 }
 
+// fp32 version with LDS-direct loads (global_load_lds_dwordx4, as in the stacked-GEMM kernel): a stage is [16 k][128
+// features] per operand, unpadded (a wave instruction brings 1 KiB = two rows), two buffers; the 16-byte units of a row are
+// stored XOR-swizzled with 4 * (row & 3), so that the four k rows a fragment read touches fall into different banks.  All
+// addresses are a scalar base advanced by scalar adds plus constant per-lane offsets: the k loop holds LDS reads, MFMAs, the
+// loads and one barrier per stage and no vector-ALU instruction (the guards and 64-bit address arithmetic of the generic
+// kernel below cost its MFMA stream a fifth of its issue cycles).  Columns past the operand's width re-read column 0 of the
+// tile: they only reach output entries the reduction never reads.  A ragged last stage (fewer than 16 rows) goes through
+// registers with zero fill.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, long M, long rows_per, int tj, float *partials) {
+  extern __shared__ __align__(16) unsigned char wg_lds[];
+  constexpr unsigned kOperand = kWgK * kWgTile * sizeof(float);  // 8 KiB
+  constexpr unsigned kBuffer = 2 * kOperand;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int lr = lane & 15, lg = lane >> 4;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int tile = blockIdx.x;
+  const int ti = tile / tj, tjx = tile % tj;
+  const int ks = blockIdx.y;
+  const long m0 = ks * rows_per;
+  const long m1 = (m0 + rows_per < M) ? m0 + rows_per : M;
+  const int i0 = ti * kWgTile, j0 = tjx * kWgTile;
+  const int nfull = (int)((m1 - m0) / kWgK);    // rows_per is a multiple of 16 below 2^35
+  const int tail = (int)((m1 - m0) - (long)nfull * kWgK);
+
+  // ---- loads: chunk c of a stage = rows 2c', 2c'+1 of operand c / 8 (c' = c % 8); wave w takes chunks w, w+4, w+8, w+12
+  unsigned c_voff[4];
+  unsigned c_lds[4];
+  {
+    const int r2 = lane >> 5, us = lane & 31;  // row inside the chunk, LDS unit slot
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = wave_u + 4 * i;
+      const int row = 2 * (c & 7) + r2;
+      const int u = us ^ ((row & 3) * 4);      // the global unit this slot holds
+      const bool isA = i < 2;
+      const int ld = isA ? ld_out : ld_in;
+      const int c0 = isA ? i0 : j0;
+      const int col = (c0 + u * 4 < ld) ? c0 + u * 4 : c0;
+      c_voff[i] = (unsigned)(((long)row * ld + col) * sizeof(float));
+      c_lds[i] = (unsigned)((isA ? 0u : kOperand) + (c & 7) * 1024u);
+    }
+  }
+  const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)wg_lds;
+  auto issue = [&](int buf, const float *ga, const float *gb) {   // ga, gb: first row of the stage in either operand (uniform)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned off = lds_base + buf * kBuffer + c_lds[i];
+      const float *g = i < 2 ? ga : gb;
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(c_voff[i]), "s"(off), "s"(g) : "memory");
+    }
+  };
+
+  // ---- fragment addresses: element (k row, feature) sits at row * 512 + ((feature / 4) ^ 4 * (row & 3)) * 16 + feature % 4 * 4
+  const float *Af[4], *Bf[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int ua = (wi * 16 + a * 4 + (lr >> 2)) ^ (lg * 4), ub = (wj * 16 + a * 4 + (lr >> 2)) ^ (lg * 4);
+    Af[a] = reinterpret_cast<const float *>(wg_lds + lg * 512 + ua * 16 + (lr & 3) * 4);
+    Bf[a] = reinterpret_cast<const float *>(wg_lds + kOperand + lg * 512 + ub * 16 + (lr & 3) * 4);
+  }
+
+  wf32x4 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) acc[a][b] = wf32x4{0, 0, 0, 0};
+
+  auto stage_mfmas = [&](int buf) {
+#pragma unroll
+    for (int kk = 0; kk < kWgK / 4; ++kk) {
+      float af[4], bf[4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) af[a] = Af[a][(buf * kBuffer + kk * 4 * 512) / 4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) bf[b] = Bf[b][(buf * kBuffer + kk * 4 * 512) / 4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[a], bf[b], acc[a][b], 0, 0, 0);
+    }
+  };
+
+  if (nfull > 0) {
+    const float *ga = Zb + m0 * ld_out, *gb = H + m0 * ld_in;
+    const long sa = (long)kWgK * ld_out, sb = (long)kWgK * ld_in;
+    issue(0, ga, gb);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int st = 0; st < nfull; st += 2) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        if (half == 1 && st + 1 >= nfull) break;   // uniform
+        // the other buffer was read during the previous stage, which ended with a barrier; the last stage re-fetches itself
+        if (st + half + 1 < nfull) {
+          ga += sa;
+          gb += sb;
+        }
+        issue(half ^ 1, ga, gb);
+        stage_mfmas(half);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of the next stage has landed
+        __syncthreads();
+      }
+    }
+  }
+  if (tail > 0) {
+    // fewer than 16 rows left: through registers, rows past the end are zeros.  Every wave passed the barrier that ends
+    // the last full stage (and its surplus loads have landed), so buffer 0 is free.
+    const long mt = m0 + (long)nfull * kWgK;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int u4 = tid + q * 256;           // 512 units of 16 bytes per operand
+      const int row = u4 / 32, us = u4 % 32;
+      const int u = us ^ ((row & 3) * 4);
+      wf32x4 za = {0, 0, 0, 0}, zb = {0, 0, 0, 0};
+      if (row < tail) {
+        if (i0 + u * 4 < ld_out) za = *reinterpret_cast<const wf32x4 *>(Zb + (mt + row) * ld_out + i0 + u * 4);
+        if (j0 + u * 4 < ld_in) zb = *reinterpret_cast<const wf32x4 *>(H + (mt + row) * ld_in + j0 + u * 4);
+      }
+      *reinterpret_cast<wf32x4 *>(wg_lds + row * 512 + us * 16) = za;
+      *reinterpret_cast<wf32x4 *>(wg_lds + kOperand + row * 512 + us * 16) = zb;
+    }
+    __syncthreads();
+    stage_mfmas(0);
+  }
+
+  // partial tile -> partials[ks][i][j] (padded to whole tiles)
+  const long pi = (long)gridDim.x / tj * kWgTile;  // padded rows
+  const long pj = (long)tj * kWgTile;
+  float *P = partials + (long)ks * pi * pj;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const long i = i0 + wi * 64 + a * 16 + lg * 4 + v;
+        const long j = j0 + wj * 64 + b * 16 + lr;
+        P[i * pj + j] = acc[a][b][v];
+      }
+}
+
 // gW[i][j] = sum_k partials[k][i][j] in a fixed order: a block takes 64 outputs, its four wavefronts a quarter of
 // the k range each (four running sums per thread keep several loads in flight), then the quarters are added.
 template <typename T>
@@ -337,12 +482,21 @@ template <typename T>
 hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M, int d_out, int d_in, T *gW, T *partials,
                         hipStream_t s, int accumulate) {
   const WgradPlan p = wgrad_plan(M, d_out, d_in);
-  constexpr size_t lds = 4 * (size_t)kWgK * kWgPitch * sizeof(T);
-  static LdsLimitOnce lds_limit;
-  hipError_t ea = lds_limit.ensure(reinterpret_cast<const void *>(&wgrad_kernel<T>), lds);
-  if (ea != hipSuccess) return ea;
-  hipLaunchKernelGGL(wgrad_kernel<T>, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
-                     p.rows_per, p.tj, partials);
+  if (p.ti * p.tj <= 0 || p.ksplit <= 0 || p.ksplit > 65535) return hipErrorInvalidValue;
+  if constexpr (std::is_same<T, float>::value) {
+    // 16-byte loads: both operands must be 16-byte aligned (their row pitches are multiples of 32 elements)
+    if ((reinterpret_cast<size_t>(Zbar) | reinterpret_cast<size_t>(H)) & 15) return hipErrorInvalidValue;
+    constexpr size_t lds = 4 * (size_t)kWgK * kWgTile * sizeof(float);
+    hipLaunchKernelGGL(wgrad_kernel_f32, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
+                       p.rows_per, p.tj, partials);
+  } else {
+    constexpr size_t lds = 4 * (size_t)kWgK * kWgPitch * sizeof(T);
+    static LdsLimitOnce lds_limit;
+    hipError_t ea = lds_limit.ensure(reinterpret_cast<const void *>(&wgrad_kernel<T>), lds);
+    if (ea != hipSuccess) return ea;
+    hipLaunchKernelGGL(wgrad_kernel<T>, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
+                       p.rows_per, p.tj, partials);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long blocks = ((long)d_out * d_in + 63) / 64;
