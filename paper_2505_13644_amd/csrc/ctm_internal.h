@@ -61,13 +61,13 @@ template <typename T> struct LayerArgs {
   int order;         // 2 or 4
   int R;             // directions in this pass
   int last;          // emit only the 0-th and the highest-order row(s)
-  int act;           // 0 tanh, 1 identity
+  int act;           // 0 tanh, 1 identity, 2 sin
   int standard;      // 1: un-collapsed Taylor mode (1 + K*R rows per point), for comparison
   int out_rows;      // rows per point in Hout: rho, or when last: 2 (collapsed) / 1 + R (standard)
   T *Zout;           // forward that records a tape: the pre-activation rows [n_points * rho][ldout] go here too (else nullptr)
   const T *Zsaved;   // bwd == 1: recorded pre-activations of the layer whose rule is reversed, [n_points * rho][ldout]
   int bwd;           // 1: Hin holds cotangents, W the transposed weights, and the epilogue is the reverse of the
-                     //    order-2 collapsed rule (writes the cotangents of the pre-activations)
+                     //    collapsed rule of that order (writes the cotangents of the pre-activations)
   int wpp = 1;  // wavefronts sharing one point in the rule: 4 / P for tiles of 1 or 2 points (forward, collapsed), else 1
   // plain-bf16 kernel only: Hin is a bf16 plane [rows][ldin]; out_bf16 != 0: Hout is one too (0: rows of T, the
   // last hidden layer's output for the final kernel)

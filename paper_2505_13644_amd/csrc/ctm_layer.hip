@@ -6,7 +6,7 @@
 //   then the activation's Taylor rule on the rows of the point (ctm_rule.h), in which the
 //   highest-order row is the one already summed over the directions.
 // The same kernel runs the reverse pass: with cotangents as input rows and W transposed it
-// computes Hbar = Zbar W and applies the reverse of the order-2 rule as its epilogue.
+// computes Hbar = Zbar W and applies the reverse of the rule (order 2 or 4) as its epilogue.
 //
 // Layout.  The block is point-major: rows n*rho .. n*rho + rho - 1 belong to point n
 // (row 0: order 0; then the per-direction rows; last row: the collapsed one), each row
@@ -14,9 +14,10 @@
 // times 64*NB output features, so the sum over directions never leaves the workgroup:
 // the accumulators are staged through LDS (64 columns at a time) and each thread then walks
 // the rows of one (point, feature) pair, keeping the running sums in registers.
-// LDS per workgroup stays below 80 KiB for fp32 so that two workgroups share a CU and one's
-// epilogue, barriers and first loads overlap with the other's MFMAs.  The A and B tiles of a k-block
+// Registers and LDS per workgroup are kept low enough for two to four workgroups per CU (Tile::kWgPerCu), so that
+// one's prologue, epilogue and barriers fall under the MFMAs of the others.  The A and B tiles of a k-block
 // reach LDS by LDS-direct loads (no register staging), double-buffered one k-block ahead.
+// The same kernel also reverses the order-4 rule (the reverse pass of the randomized / exact biharmonic).
 //
 // MFMA use: v_mfma_{f32,f64}_16x16x4.  Lane l supplies A[row l%16][k l/16] and
 // B[k l/16][col l%16]; it receives four elements of column l%16 of D, in rows
