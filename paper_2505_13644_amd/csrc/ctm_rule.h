@@ -280,13 +280,30 @@ __device__ __forceinline__ void jet_rule_bwd(const T *c, int CROW, const T *zs, 
     const T hb0 = c[0], hb2 = c[(R + 1) * CROW];
     const T z2 = lane_load<T>(zs + (R + 1) * zstep, voff);
     const T w = T(2) * d2 * hb2;
-    T s = T(0), dot = T(0);
-    for (int r = 1; r <= R; ++r) {
+    // four directions per trip, their loads issued together (the recorded rows come from HBM / L2); the two sums are
+    // kept in four interleaved groups and combined as (g0 + g1) + (g2 + g3)
+    T sg[4] = {T(0), T(0), T(0), T(0)}, dg[4] = {T(0), T(0), T(0), T(0)};
+    int r = 1;
+    for (; r + 3 <= R; r += 4) {
+      T z1[4], hb1[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) z1[k] = lane_load<T>(zs + (r + k) * zstep, voff);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) hb1[k] = c[(r + k) * CROW];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        sg[k] += z1[k] * z1[k];
+        dg[k] += hb1[k] * z1[k];
+        lane_store<T>(o + (r + k) * ostep, voff, d1 * hb1[k] + w * z1[k]);
+      }
+    }
+    for (int k = 0; r <= R; ++r, ++k) {
       const T z1 = lane_load<T>(zs + r * zstep, voff), hb1 = c[r * CROW];
-      s += z1 * z1;
-      dot += hb1 * z1;
+      sg[k] += z1 * z1;
+      dg[k] += hb1 * z1;
       lane_store<T>(o + r * ostep, voff, d1 * hb1 + w * z1);
     }
+    const T s = (sg[0] + sg[1]) + (sg[2] + sg[3]), dot = (dg[0] + dg[1]) + (dg[2] + dg[3]);
     lane_store<T>(o + (R + 1) * ostep, voff, d1 * hb2);
     lane_store<T>(o, voff, d1 * hb0 + d2 * (dot + hb2 * z2) + d3 * s * hb2);
   } else {
