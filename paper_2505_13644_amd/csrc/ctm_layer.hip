@@ -94,7 +94,9 @@ template <typename T, int MB> struct Tile {
 // almost half of the time.  Three or four resident workgroups instead of two matter because a workgroup spends more
 // than half of its life outside the k loop (prologue, epilogue: their vector-ALU instructions only get the issue slots
 // the MFMA stream of a co-resident workgroup leaves): the more neighbours, the rarer the moments without MFMAs in flight.
-template <typename T, int MB, int WPP>
+// PLAIN = true is the forward pass in collapsed mode without a tape (what the operator entry points launch): the reverse
+// rule, the tape stores and the un-collapsed layout are compiled out, which also relieves the scalar registers.
+template <typename T, int MB, int WPP, bool PLAIN>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Tile<T, MB>::kWgPerCu, Tile<T, MB>::kWgPerCu)))
 void layer_kernel(const LayerArgs<T> a) {
   using TL = Tile<T, MB>;
@@ -279,7 +281,9 @@ void layer_kernel(const LayerArgs<T> a) {
           const long jg0 = (long)col_tile * BN + nb * 64;  // the wavefront's first column: n, jg0 are wavefront-uniform
           const unsigned voff = (unsigned)(j * sizeof(T));
           T *o = a.Hout + (n * a.out_rows) * a.ldout + jg0;
-          if (a.bwd) {
+          if constexpr (PLAIN) {
+            jet_rule<T, PlainRows<T>, 1, false>(c, CROW, bias, PlainRows<T>{o, ostep, voff}, a);
+          } else if (a.bwd) {
             jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg0, a.ldout, o, ostep, voff, a);
           } else {
             if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, voff, rho);
@@ -298,23 +302,31 @@ void layer_kernel(const LayerArgs<T> a) {
       const long jg0 = (long)col_tile * BN + nb * 64;
       const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))};
       T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 2 * 64 + j;  // p > 0 only when two wavefronts share a point
-      if (a.Zout && active && sub == 0)
-        save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, (unsigned)(j * sizeof(T)), rho);
-      jet_rule<T, PlainRows<T>, WPP>(c, CROW, bias, out, a, active, sub, red);
+      if constexpr (!PLAIN) {
+        if (a.Zout && active && sub == 0)
+          save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, (unsigned)(j * sizeof(T)), rho);
+      }
+      jet_rule<T, PlainRows<T>, WPP, false>(c, CROW, bias, out, a, active, sub, red);
     }
   }
 }
 
-template <typename T, int MB, int WPP> static hipError_t launch_wpp(const LayerArgs<T> &a, hipStream_t s) {
+template <typename T, int MB, int WPP, bool PLAIN> static hipError_t launch_kernel(const LayerArgs<T> &a, hipStream_t s) {
   using TL = Tile<T, MB>;
   static LdsLimitOnce lds_limit;
-  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB, WPP>), TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0));
+  const size_t lds = TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0);
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB, WPP, PLAIN>), lds);
   if (e != hipSuccess) return e;
   const long n_tiles = a.n_row_tiles * a.n_col_tiles;
   const long grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
   if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((layer_kernel<T, MB, WPP>), dim3((unsigned)grid), dim3(kThreads), TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0), s, a);
+  hipLaunchKernelGGL((layer_kernel<T, MB, WPP, PLAIN>), dim3((unsigned)grid), dim3(kThreads), lds, s, a);
   return hipGetLastError();
+}
+
+template <typename T, int MB, int WPP> static hipError_t launch_wpp(const LayerArgs<T> &a, hipStream_t s) {
+  const bool plain = !a.bwd && !a.standard && a.Zout == nullptr;
+  return plain ? launch_kernel<T, MB, WPP, true>(a, s) : launch_kernel<T, MB, WPP, false>(a, s);
 }
 
 // wpp wavefronts share a point in the rule (tiles of 1 or 2 points; forward, collapsed mode only)

@@ -89,7 +89,8 @@ struct Bf16Rows {  // rows of bf16 (the block between the layers of a plain-bf16
 // writes the collapsed row.  The result is therefore bit-identical for every WPP, i.e. for every tile shape.
 // With WPP > 1 every thread of the workgroup must make the call (it holds a barrier); threads without a valid
 // pair pass active = false.  Un-collapsed (standard) mode has no sum and is only built for WPP = 1.
-template <typename T, typename Out, int WPP = 1>
+// STD = false compiles the un-collapsed branch out (callers that are never launched in that mode).
+template <typename T, typename Out, int WPP = 1, bool STD = true>
 __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out &out, const LayerArgs<T> &a, bool active = true,
                                          int sub = 0, T *red = nullptr) {
   constexpr int NG = 4 / WPP;  // groups per wavefront
@@ -101,7 +102,7 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
     d2 = act_d2<T>(a.act, t, d1);
     if (sub == 0) out.put(0, t);
   }
-  if (a.standard) {
+  if (STD && a.standard) {
     // un-collapsed ("standard") Taylor mode, kept for comparison: every direction carries its own
     // highest-order row (1 + K*R rows per point) and the sum over directions is taken after the last layer
     if (!active) return;
