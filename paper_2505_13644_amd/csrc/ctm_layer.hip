@@ -114,15 +114,17 @@ void layer_kernel(const LayerArgs<T> a) {
   // ---- which tile: workgroups are dealt round-robin to the 8 XCDs, each with its own L2.
   // Give every XCD one contiguous run of tiles, ordered so that the column tiles of one
   // row tile (which read the same rows of Hin) are neighbours in time on the same L2.
-  const long n_tiles = a.n_row_tiles * a.n_col_tiles;
-  const int xcd = blockIdx.x % kXcds;
-  const long slot = blockIdx.x / kXcds;
-  const long base = n_tiles / kXcds, rem = n_tiles % kXcds;
-  const long mine = base + (xcd < rem ? 1 : 0);
+  // (the launcher keeps the tile count below 2^31, so 32-bit arithmetic does: a 64-bit division is some forty vector-ALU
+  // instructions that a starting workgroup would take from its neighbours' MFMAs)
+  const unsigned n_tiles = (unsigned)(a.n_row_tiles * a.n_col_tiles);
+  const unsigned xcd = blockIdx.x % kXcds;
+  const unsigned slot = blockIdx.x / kXcds;
+  const unsigned base = n_tiles / kXcds, rem = n_tiles % kXcds;
+  const unsigned mine = base + (xcd < rem ? 1 : 0);
   if (slot >= mine) return;
-  const long tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
-  const long row_tile = tile / a.n_col_tiles;
-  const int col_tile = (int)(tile % a.n_col_tiles);
+  const unsigned tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  const long row_tile = tile / (unsigned)a.n_col_tiles;
+  const int col_tile = (int)(tile % (unsigned)a.n_col_tiles);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;

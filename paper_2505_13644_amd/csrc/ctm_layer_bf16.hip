@@ -83,15 +83,15 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   __bf16 *lds = reinterpret_cast<__bf16 *>(lds_raw);
   float *Cs = reinterpret_cast<float *>(lds_raw);   // reuses the stages after the k loop
 
-  const long n_tiles = a.n_row_tiles * a.n_col_tiles;
-  const int xcd = blockIdx.x % kXcdsB;
-  const long slot = blockIdx.x / kXcdsB;
-  const long base = n_tiles / kXcdsB, rem = n_tiles % kXcdsB;
-  const long mine = base + (xcd < rem ? 1 : 0);
+  const unsigned n_tiles = (unsigned)(a.n_row_tiles * a.n_col_tiles);   // below 2^31 (checked at launch): 32-bit index arithmetic
+  const unsigned xcd = blockIdx.x % kXcdsB;
+  const unsigned slot = blockIdx.x / kXcdsB;
+  const unsigned base = n_tiles / kXcdsB, rem = n_tiles % kXcdsB;
+  const unsigned mine = base + (xcd < rem ? 1 : 0);
   if (slot >= mine) return;
-  const long tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
-  const long row_tile = tile / a.n_col_tiles;
-  const int col_tile = (int)(tile % a.n_col_tiles);
+  const unsigned tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
+  const long row_tile = tile / (unsigned)a.n_col_tiles;
+  const int col_tile = (int)(tile % (unsigned)a.n_col_tiles);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
