@@ -37,12 +37,27 @@ template <typename T> __global__ void bwd_last_kernel(const BwdLastArgs<T> a) {
     act_eval<T>(a.act, zs[0], t, d1);
     const T d2 = act_d2<T>(a.act, t, d1), d3 = act_d3<T>(a.act, t, d1);
     if (a.order == 2) {
-      T s = T(0);
-      for (int r = 1; r <= R; ++r) {
-        const T z1 = zs[r * step];
-        s += z1 * z1;
-        o[r * step] = T(2) * d2 * z1 * hbK;
+      // four directions per trip so that their loads are in flight together (the compiler may not move a load across
+      // the store before it: it cannot tell that the two blocks do not overlap)
+      const T w2 = T(2) * d2 * hbK;
+      T sg[4] = {T(0), T(0), T(0), T(0)};
+      int r = 1;
+      for (; r + 3 <= R; r += 4) {
+        T z1[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) z1[k] = zs[(r + k) * step];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          sg[k] += z1[k] * z1[k];
+          o[(r + k) * step] = w2 * z1[k];
+        }
       }
+      for (int k = 0; r <= R; ++r, ++k) {
+        const T z1 = zs[r * step];
+        sg[k] += z1 * z1;
+        o[r * step] = w2 * z1;
+      }
+      const T s = (sg[0] + sg[1]) + (sg[2] + sg[3]);
       o[(R + 1) * step] = d1 * hbK;
       o[0] = d1 * hb0 + d2 * hbK * zs[(R + 1) * step] + d3 * s * hbK;
     } else {  // the order-4 reverse rule (ctm_rule.h) with hb_1 = hb_2 = hb_3 = 0
