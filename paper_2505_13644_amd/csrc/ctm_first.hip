@@ -37,7 +37,10 @@ constexpr int kFirstPoints = 16;  // points per workgroup
 constexpr int kFirstDmax = 64;    // input widths up to this are held in registers
 
 // BF = 0: out holds rows of T; BF = 1: out is written as bf16 (input of the plain-bf16 GEMM kernel).
-template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
+// DM: the input width rounded up to 8, 16, 32 or 64 -- the length of the register-resident weight row and of the dot
+// products (a 5-dimensional problem should not pay for 64 inputs).
+template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
+  constexpr int kFirstDmax = DM;   // shadows the global limit inside this kernel
   __shared__ T xs[kFirstPoints][kFirstDmax];
   const int tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
@@ -58,10 +61,13 @@ template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer
   T t[kFirstPoints], d1[kFirstPoints];
 #pragma unroll
   for (int p = 0; p < kFirstPoints; ++p) {
-    T z0 = bias;
+    t[p] = d1[p] = T(0);
+    if (p < np) {   // uniform: a short last chunk (or a tiny batch) skips the activations of absent points
+      T z0 = bias;
 #pragma unroll
-    for (int k = 0; k < kFirstDmax; ++k) z0 += w[k] * xs[p][k];   // k >= D: both factors are zero
-    act_eval<T>(a.act, z0, t[p], d1[p]);
+      for (int k = 0; k < kFirstDmax; ++k) z0 += w[k] * xs[p][k];   // k >= D: both factors are zero
+      act_eval<T>(a.act, z0, t[p], d1[p]);
+    }
   }
 
   const long ld = a.ld1;
@@ -250,6 +256,24 @@ template <typename T> static hipError_t launch_first_pp(const FirstArgs<T> &a, h
   return hipGetLastError();
 }
 
+template <typename T, int DM> static hipError_t launch_first_dm(const FirstArgs<T> &b, dim3 grid, hipStream_t s) {
+  if constexpr (std::is_same<T, float>::value) {
+    if (b.out_bf16) {
+      hipLaunchKernelGGL((first_layer_kernel<T, 1, DM>), grid, dim3(256), 0, s, b);
+      return hipGetLastError();
+    }
+  }
+  if (b.out_bf16) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((first_layer_kernel<T, 0, DM>), grid, dim3(256), 0, s, b);
+  return hipGetLastError();
+}
+template <typename T> static hipError_t launch_first_width(const FirstArgs<T> &b, dim3 grid, hipStream_t s) {
+  if (b.D <= 8) return launch_first_dm<T, 8>(b, grid, s);
+  if (b.D <= 16) return launch_first_dm<T, 16>(b, grid, s);
+  if (b.D <= 32) return launch_first_dm<T, 32>(b, grid, s);
+  return launch_first_dm<T, 64>(b, grid, s);
+}
+
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s) {
   if (a.v_sn != 0) return launch_first_pp<T>(a, s);
   hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256, a.R), dim3(256), 0, s, a);
@@ -266,14 +290,8 @@ template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t
     b.N = a.N - c0 * kFirstPoints;
     if (b.N > nc * kFirstPoints) b.N = nc * kFirstPoints;
     const dim3 grid((a.ld1 + 255) / 256, (unsigned)nc);
-    bool launched = false;
-    if constexpr (std::is_same<T, float>::value) {
-      if (a.out_bf16) { hipLaunchKernelGGL((first_layer_kernel<T, 1>), grid, dim3(256), 0, s, b); launched = true; }
-    }
-    if (!launched) {
-      if (a.out_bf16) return hipErrorInvalidValue;
-      hipLaunchKernelGGL((first_layer_kernel<T, 0>), grid, dim3(256), 0, s, b);
-    }
+    e = launch_first_width<T>(b, grid, s);
+    if (e != hipSuccess) return e;
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
