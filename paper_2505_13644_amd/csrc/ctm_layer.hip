@@ -67,7 +67,7 @@ template <typename T, int MB> struct Tile {
   static constexpr int LROW = BK;                 // LDS row pitch of a stage, elements: 64 bytes, no padding (LDS-direct loads)
   static constexpr int A_STAGE = BM * LROW;
   static constexpr int B_STAGE = BN * LROW;
-  static constexpr int CCOLS = 64;                // the C tile is staged 64 columns at a time
+  static constexpr int CCOLS = 256 / sizeof(T);   // the C tile is staged in two chunks of 256 bytes per row: 64 fp32 / 32 fp64 columns
   // LDS row pitch of the staged C chunk: padded so that the four row groups of an accumulator store hit different
   // banks -- unless the pad is what keeps a third workgroup off the CU (MB = 13 in fp32: 52 KiB without, 55 KiB with)
   static constexpr size_t kCuLds = 160 * 1024;
@@ -259,25 +259,37 @@ void layer_kernel(const LayerArgs<T> a) {
   // Each wave's last real fragment read and its last (surplus) loads completed before it entered the final barrier
   // above, so the stages can be reused for the C tile right away (the fragments fetched after that barrier are unused).
 
-  // ---- epilogue, 64 output columns at a time (wave w holds columns nb*64 + w*16 .. +15 of the
-  // tile in acc[.][nb]): stage that chunk of the accumulators through LDS, then apply the
-  // collapsed jet rule with one thread per (point, feature) pair, walking the point's rows in
-  // order.
+  // ---- epilogue, one chunk of CCOLS output columns at a time (fp32: chunk c is the column block acc[.][c], wave w
+  // holds its columns w*16 .. +15; fp64: chunk c is the 16 columns each of the waves 2c and 2c+1): stage that chunk of
+  // the accumulators through LDS, then apply the collapsed jet rule with one thread per (point, feature) pair, walking
+  // the point's rows in order.  With fp64 only the lower half of a wavefront has a column.
   if constexpr (MB > 9) __builtin_amdgcn_s_setprio(0);
   const int rho = a.rho;
   const int j = tid & 63;
+  constexpr int CCOLS = TL::CCOLS;
+  static_assert(BN / CCOLS == 2, "two chunks per tile");
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) {
+  for (int nb = 0; nb < 2; ++nb) {
     if (nb > 0) __syncthreads();  // the previous chunk has been consumed
+    if constexpr (NB == 2) {
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        Cs[(mb * 16 + Vec<T>::out_row(lg, v)) * CROW + wave * 16 + lr] = acc[mb][nb][v];
+        for (int v = 0; v < 4; ++v)
+          Cs[(mb * 16 + Vec<T>::out_row(lg, v)) * CROW + wave * 16 + lr] = acc[mb][nb][v];
+    } else {
+      if ((wave_u >> 1) == nb) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            Cs[(mb * 16 + Vec<T>::out_row(lg, v)) * CROW + (wave_u & 1) * 16 + lr] = acc[mb][0][v];
+      }
+    }
     __syncthreads();
 
-    const long jg = (long)col_tile * BN + nb * 64 + j;
-    const bool col_ok = jg < a.ldout;
+    const long jg = (long)col_tile * BN + nb * CCOLS + j;
+    const bool col_ok = j < CCOLS && jg < a.ldout;
     const T bias = col_ok ? a.bias[jg] : T(0);
     const long ostep = a.ldout;
     if constexpr (WPP == 1) {  // a wavefront per point
@@ -285,7 +297,7 @@ void layer_kernel(const LayerArgs<T> a) {
         for (int p = wave_u; p < p_valid; p += kThreads / 64) {
           const T *c = Cs + p * rho * CROW + j;
           const long n = p0 + p;
-          const long jg0 = (long)col_tile * BN + nb * 64;  // the wavefront's first column: n, jg0 are wavefront-uniform
+          const long jg0 = (long)col_tile * BN + nb * CCOLS;  // the wavefront's first column: n, jg0 are wavefront-uniform
           const unsigned voff = (unsigned)(j * sizeof(T));
           T *o = a.Hout + (n * a.out_rows) * a.ldout + jg0;
           if constexpr (PLAIN) {
@@ -306,7 +318,7 @@ void layer_kernel(const LayerArgs<T> a) {
       const bool active = col_ok && p < p_valid;
       const T *c = Cs + p * rho * CROW + j;
       const long n = p0 + p;
-      const long jg0 = (long)col_tile * BN + nb * 64;
+      const long jg0 = (long)col_tile * BN + nb * CCOLS;
       const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))};
       T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 2 * 64 + j;  // p > 0 only when two wavefronts share a point
       if constexpr (!PLAIN) {
