@@ -176,16 +176,17 @@ void layer_kernel(const LayerArgs<T> a) {
     }
   }
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)lds_raw;
+  auto issue_one = [&](int buf, int k0, int i) {   // i: compile-time after unrolling
+    if (wave_u + 4 * i < kChunks) {
+      const unsigned off = lds_base + c_off[i] + buf * c_step[i];
+      const T *g = c_base[i] + k0;   // uniform
+      // M0 carries the LDS byte address; the compiler does not model this load, so the waits below are explicit
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(c_voff[i]), "s"(off), "s"(g) : "memory");
+    }
+  };
   auto issue = [&](int buf, int k0) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      if (wave_u + 4 * i < kChunks) {
-        const unsigned off = lds_base + c_off[i] + buf * c_step[i];
-        const T *g = c_base[i] + k0;   // uniform
-        // M0 carries the LDS byte address; the compiler does not model this load, so the waits below are explicit
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(c_voff[i]), "s"(off), "s"(g) : "memory");
-      }
-    }
+    for (int i = 0; i < NCH; ++i) issue_one(buf, k0, i);
   };
 
   vacc acc[MB][NB];
@@ -224,13 +225,17 @@ void layer_kernel(const LayerArgs<T> a) {
       // stage `half` reads LDS buffer `half`; the next k-block goes straight to the other buffer, which every wave
       // finished reading before the previous barrier (the very last stage re-fetches its own block, unused)
       const int k_next = (2 * kp + half + 1) * BK < k_last ? (2 * kp + half + 1) * BK : k_last;
-      issue(half ^ 1, k_next);
       const T *Ac = Ar + half * TL::A_STAGE;
       const T *An = Ar + (half ^ 1) * TL::A_STAGE;
       const T *Bn = Br + (half ^ 1) * TL::B_STAGE;
 #pragma unroll
       for (int st = 0; st < MB; ++st) {
         const int s = half * MB + st;  // fragment slot parity runs across both stages
+        // this wave's loads of the next k-block, one at a time between the MFMA groups of steps 1, ..: a load instruction
+        // holds the wave's issue for some 50 cycles, which the MFMAs already queued from the previous step cover
+#pragma unroll
+        for (int i = 0; i < NCH; ++i)
+          if (st == 1 + i * (MB - 1) / NCH) issue_one(half ^ 1, k_next, i);
         if (st + 1 < MB) {
           af[(s + 1) & 1] = *reinterpret_cast<const vld *>(Ac + (st + 1) * 16 * LROW);
         } else {
