@@ -194,8 +194,8 @@ void layer_kernel(const LayerArgs<T> a) {
   // ---- k loop.  A stage is one k-block of BK = 4*KV values, i.e. MB steps of NB*KV MFMAs (one A
   // fragment against the NB B fragments).  The loop body covers two stages so that every LDS
   // buffer and fragment slot is a compile-time choice.  Within a stage:
-  //   * the LDS-direct loads of the next k-block are issued first, into the other buffer -- every wave
-  //     finished reading that buffer before the previous barrier;
+  //   * the LDS-direct loads of the next k-block go into the other buffer -- every wave finished reading that buffer
+  //     before the previous barrier -- one at a time, spread over the steps of the stage;
   //   * every step fetches the next step's A fragment before issuing its own MFMAs;
   //   * the last step waits for this wave's loads (vmcnt), passes the barrier (after which the other
   //     buffer is complete) and fetches the first fragments of the next stage, so they arrive
@@ -231,11 +231,6 @@ void layer_kernel(const LayerArgs<T> a) {
 #pragma unroll
       for (int st = 0; st < MB; ++st) {
         const int s = half * MB + st;  // fragment slot parity runs across both stages
-        // this wave's loads of the next k-block, one at a time between the MFMA groups of steps 1, ..: a load instruction
-        // holds the wave's issue for some 50 cycles, which the MFMAs already queued from the previous step cover
-#pragma unroll
-        for (int i = 0; i < NCH; ++i)
-          if (st == 1 + i * (MB - 1) / NCH) issue_one(half ^ 1, k_next, i);
         if (st + 1 < MB) {
           af[(s + 1) & 1] = *reinterpret_cast<const vld *>(Ac + (st + 1) * 16 * LROW);
         } else {
@@ -247,10 +242,21 @@ void layer_kernel(const LayerArgs<T> a) {
         }
         __builtin_amdgcn_sched_barrier(0);  // keep the fetches ahead of this step's MFMAs
 #pragma unroll
-        for (int j = 0; j < KV; ++j)
+        for (int j = 0; j < KV; ++j) {
+          if (j == KV / 2) {
+            // this wave's loads of the next k-block, one at a time in the middle of the MFMA group of steps 0, 2, ..: a
+            // load instruction holds the wave's issue for some 50 cycles, which the MFMAs queued just before it cover
+            // (all of them at the top of the stage cost a wave that is alone on its SIMD 7.5 % of its MFMA rate)
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NCH; ++i)
+              if (st == i * (MB - 1) / NCH) issue_one(half ^ 1, k_next, i);
+            __builtin_amdgcn_sched_barrier(0);
+          }
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
             acc[st][nb] = mfma16(af[s & 1][j], bf[half][nb][j], (kFirst && half == 0 && j == 0) ? vacc{0, 0, 0, 0} : acc[st][nb]);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
