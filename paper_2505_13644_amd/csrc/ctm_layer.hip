@@ -218,6 +218,7 @@ void layer_kernel(const LayerArgs<T> a) {
   // operand: no vector-ALU instructions to clear the accumulators (those of a starting workgroup would take issue
   // cycles from the MFMAs of the workgroup it shares the CU with).
   const int k_last = a.ldin - BK;
+  constexpr bool kLoadMid = MB > 9;
   auto stage_pair = [&](int kp, auto first_tag) {
     constexpr bool kFirst = decltype(first_tag)::value;
 #pragma unroll
@@ -231,6 +232,11 @@ void layer_kernel(const LayerArgs<T> a) {
 #pragma unroll
       for (int st = 0; st < MB; ++st) {
         const int s = half * MB + st;  // fragment slot parity runs across both stages
+        if constexpr (!kLoadMid) {
+#pragma unroll
+          for (int i = 0; i < NCH; ++i)
+            if (st == 1 + i * (MB - 1) / NCH) issue_one(half ^ 1, k_next, i);
+        }
         if (st + 1 < MB) {
           af[(s + 1) & 1] = *reinterpret_cast<const vld *>(Ac + (st + 1) * 16 * LROW);
         } else {
@@ -243,10 +249,11 @@ void layer_kernel(const LayerArgs<T> a) {
         __builtin_amdgcn_sched_barrier(0);  // keep the fetches ahead of this step's MFMAs
 #pragma unroll
         for (int j = 0; j < KV; ++j) {
-          if (j == KV / 2) {
-            // this wave's loads of the next k-block, one at a time in the middle of the MFMA group of steps 0, 2, ..: a
-            // load instruction holds the wave's issue for some 50 cycles, which the MFMAs queued just before it cover
-            // (all of them at the top of the stage cost a wave that is alone on its SIMD 7.5 % of its MFMA rate)
+          if (kLoadMid && j == KV / 2) {
+            // this wave's loads of the next k-block, one at a time, spread over the steps of the stage instead of all at
+            // its top (bursts of load instructions from every wave cost 1.2 %).  Tall tiles issue them in the middle of
+            // a step's MFMA group, short ones (MB <= 9, four workgroups per CU) at the start of a step: measured, each
+            // 0.3 - 4 % better than the other position on its tile heights.
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < NCH; ++i)
