@@ -158,6 +158,7 @@ def small_case(dims, N, dtype, seed, R=None, kind="gaussian", per_point=True, bi
     ((6, 40, 24, 1), 70, 9, False),        # shared directions [R, D]
     ((4, 48, 48, 48, 1), 33, 21, True),    # per-point directions
     ((50, 96, 1), 9, 150, False),          # more rows per point than half a tile
+    ((50, 160, 96, 1), 41, None, False),   # the benchmark's 52 rows per point: tallest tile, four points each, several column tiles
 ])
 def test_laplacian_shapes(dtype, dims, N, R, per_point):
     arrs = small_case(dims, N, dtype, seed=len(dims) + N, R=R, per_point=per_point)
