@@ -63,6 +63,21 @@ def test_named_workloads_reduced_batch(name, N):
         check((got[0][idx], got[1][idx]), ref_h, w.tol, "c2 full-Hessian trace")
 
 
+def test_benchmark_shape_in_fp64_sampled():
+    # the benchmark's network, batch and directions with every array widened to fp64: the fp64 kernels at the tile
+    # shape and launch size the fp32 benchmark uses (three workgroups per CU, two 32-column chunks per tile)
+    w = synth.WORKLOADS["c2"]
+    arrs = w.build()
+    wide = lambda v: [a.astype(np.float64) for a in v] if isinstance(v, list) else (v.astype(np.float64) if isinstance(v, np.ndarray) else v)
+    arrs = {k: wide(v) for k, v in arrs.items()}
+    print(f"case c2 in fp64, full N={w.N}", flush=True)
+    gu, go = gpu_run(arrs, w.op)
+    idx = np.sort(np.random.default_rng(5).choice(w.N, 10, replace=False))
+    idx[0], idx[-1] = 0, w.N - 1
+    check((gu[idx], go[idx]), oracle_run(arrs, w.op, idx=idx), TOL64, "c2 in fp64, full-size sample")
+    assert np.all(np.isfinite(go)) and np.all(np.isfinite(gu))
+
+
 @pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c3", 48), ("c4", 64), ("c5", 48), ("e1", 12)])
 def test_named_workloads_full_size_sampled(name, n_sample):
     # the launch configuration the benchmark times; the oracle checks a seeded sample of points
