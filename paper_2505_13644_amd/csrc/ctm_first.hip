@@ -40,22 +40,21 @@ constexpr int kFirstDmax = 64;    // input widths up to this are held in registe
 // DM: the input width rounded up to 8, 16, 32 or 64 -- the length of the register-resident weight row and of the dot
 // products (a 5-dimensional problem should not pay for 64 inputs).
 template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
-  constexpr int kFirstDmax = DM;   // shadows the global limit inside this kernel
-  __shared__ T xs[kFirstPoints][kFirstDmax];
+  __shared__ T xs[kFirstPoints][DM];
   const int tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
   const long n0 = (long)blockIdx.y * kFirstPoints;
   const int np = (int)((a.N - n0) < kFirstPoints ? (a.N - n0) : kFirstPoints);
-  for (int i = tid; i < kFirstPoints * kFirstDmax; i += 256) {  // unused entries must be zero, not stale
-    const int p = i / kFirstDmax, k = i % kFirstDmax;
+  for (int i = tid; i < kFirstPoints * DM; i += 256) {  // unused entries must be zero, not stale
+    const int p = i / DM, k = i % DM;
     xs[p][k] = (p < np && k < a.D) ? a.x[(n0 + p) * a.D + k] : T(0);
   }
   __syncthreads();
   if (j >= a.ld1) return;
 
-  T w[kFirstDmax];
+  T w[DM];
 #pragma unroll
-  for (int k = 0; k < kFirstDmax; ++k) w[k] = k < a.D ? a.W[(long)j * a.ld0 + k] : T(0);
+  for (int k = 0; k < DM; ++k) w[k] = k < a.D ? a.W[(long)j * a.ld0 + k] : T(0);
   const T bias = a.bias[j];
 
   T t[kFirstPoints], d1[kFirstPoints];
@@ -65,7 +64,7 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
     if (p < np) {   // uniform: a short last chunk (or a tiny batch) skips the activations of absent points
       T z0 = bias;
 #pragma unroll
-      for (int k = 0; k < kFirstDmax; ++k) z0 += w[k] * xs[p][k];   // k >= D: both factors are zero
+      for (int k = 0; k < DM; ++k) z0 += w[k] * xs[p][k];   // k >= D: both factors are zero
       act_eval<T>(a.act, z0, t[p], d1[p]);
     }
   }
@@ -291,8 +290,6 @@ template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t
     if (b.N > nc * kFirstPoints) b.N = nc * kFirstPoints;
     const dim3 grid((a.ld1 + 255) / 256, (unsigned)nc);
     e = launch_first_width<T>(b, grid, s);
-    if (e != hipSuccess) return e;
-    e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
