@@ -94,9 +94,15 @@ template <typename T, int MB> struct Tile {
 // almost half of the time.  Three or four resident workgroups instead of two matter because a workgroup spends more
 // than half of its life outside the k loop (prologue, epilogue: their vector-ALU instructions only get the issue slots
 // the MFMA stream of a co-resident workgroup leaves): the more neighbours, the rarer the moments without MFMAs in flight.
-// PLAIN = true is the forward pass in collapsed mode without a tape (what the operator entry points launch): the reverse
-// rule, the tape stores and the un-collapsed layout are compiled out, which also relieves the scalar registers.
-template <typename T, int MB, int WPP, bool PLAIN>
+// MODE picks the epilogue at compile time -- one instance per use instead of one kernel with every path in it, which also
+// relieves the scalar registers (12 instead of 70 spilled in the plain forward instance; their lane reads and writes are
+// vector-ALU instructions):
+//   kPlain    forward, collapsed, no tape (what the operator entry points launch)
+//   kTape     forward, collapsed, the pre-activation rows are recorded too
+//   kReverse  reverse pass: the epilogue is the reverse of the rule
+//   kStandard forward in the un-collapsed layout (comparison path)
+enum LayerMode { kPlain = 0, kTape = 1, kReverse = 2, kStandard = 3 };
+template <typename T, int MB, int WPP, int MODE>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(Tile<T, MB>::kWgPerCu, Tile<T, MB>::kWgPerCu)))
 void layer_kernel(const LayerArgs<T> a) {
   using TL = Tile<T, MB>;
@@ -318,13 +324,11 @@ void layer_kernel(const LayerArgs<T> a) {
           const long jg0 = (long)col_tile * BN + nb * CCOLS;  // the wavefront's first column: n, jg0 are wavefront-uniform
           const unsigned voff = (unsigned)(j * sizeof(T));
           T *o = a.Hout + (n * a.out_rows) * a.ldout + jg0;
-          if constexpr (PLAIN) {
-            jet_rule<T, PlainRows<T>, 1, false>(c, CROW, bias, PlainRows<T>{o, ostep, voff}, a);
-          } else if (a.bwd) {
+          if constexpr (MODE == kReverse) {
             jet_rule_bwd<T>(c, CROW, a.Zsaved + (n * rho) * a.ldout + jg0, a.ldout, o, ostep, voff, a);
           } else {
-            if (a.Zout) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, voff, rho);
-            jet_rule<T, PlainRows<T>, 1>(c, CROW, bias, PlainRows<T>{o, ostep, voff}, a);
+            if constexpr (MODE == kTape) save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, voff, rho);
+            jet_rule<T, PlainRows<T>, 1, MODE == kStandard>(c, CROW, bias, PlainRows<T>{o, ostep, voff}, a);
           }
         }
       }
@@ -339,8 +343,8 @@ void layer_kernel(const LayerArgs<T> a) {
       const long jg0 = (long)col_tile * BN + nb * CCOLS;
       const PlainRows<T> out{a.Hout + (n * a.out_rows) * a.ldout + jg0, ostep, (unsigned)(j * sizeof(T))};
       T *red = reinterpret_cast<T *>(lds_raw + TL::kRedOffset) + p * 2 * 64 + j;  // p > 0 only when two wavefronts share a point
-      if constexpr (!PLAIN) {
-        if (a.Zout && active && sub == 0)
+      if constexpr (MODE == kTape) {
+        if (active && sub == 0)
           save_preactivations<T>(c, CROW, bias, a.Zout + (n * rho) * a.ldout + jg0, a.ldout, (unsigned)(j * sizeof(T)), rho);
       }
       jet_rule<T, PlainRows<T>, WPP, false>(c, CROW, bias, out, a, active, sub, red);
@@ -348,22 +352,30 @@ void layer_kernel(const LayerArgs<T> a) {
   }
 }
 
-template <typename T, int MB, int WPP, bool PLAIN> static hipError_t launch_kernel(const LayerArgs<T> &a, hipStream_t s) {
+template <typename T, int MB, int WPP, int MODE> static hipError_t launch_kernel(const LayerArgs<T> &a, hipStream_t s) {
   using TL = Tile<T, MB>;
   static LdsLimitOnce lds_limit;
   const size_t lds = TL::kRedOffset + (WPP > 1 ? TL::kRedBytes : 0);
-  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB, WPP, PLAIN>), lds);
+  hipError_t e = lds_limit.ensure(reinterpret_cast<const void *>(&layer_kernel<T, MB, WPP, MODE>), lds);
   if (e != hipSuccess) return e;
   const long n_tiles = a.n_row_tiles * a.n_col_tiles;
   const long grid = (n_tiles + kXcds - 1) / kXcds * kXcds;
   if (grid <= 0 || grid > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((layer_kernel<T, MB, WPP, PLAIN>), dim3((unsigned)grid), dim3(kThreads), lds, s, a);
+  hipLaunchKernelGGL((layer_kernel<T, MB, WPP, MODE>), dim3((unsigned)grid), dim3(kThreads), lds, s, a);
   return hipGetLastError();
 }
 
 template <typename T, int MB, int WPP> static hipError_t launch_wpp(const LayerArgs<T> &a, hipStream_t s) {
-  const bool plain = !a.bwd && !a.standard && a.Zout == nullptr;
-  return plain ? launch_kernel<T, MB, WPP, true>(a, s) : launch_kernel<T, MB, WPP, false>(a, s);
+  // the modes exclude one another: the reverse pass and the un-collapsed layout record no tape
+  if ((a.bwd != 0) + (a.standard != 0) + (a.Zout != nullptr) > 1) return hipErrorInvalidValue;
+  if (a.Zout != nullptr) return launch_kernel<T, MB, WPP, kTape>(a, s);
+  if constexpr (WPP == 1) {  // wavefronts share points only in the collapsed forward passes
+    if (a.bwd) return launch_kernel<T, MB, WPP, kReverse>(a, s);
+    if (a.standard) return launch_kernel<T, MB, WPP, kStandard>(a, s);
+  } else {
+    if (a.bwd || a.standard) return hipErrorInvalidValue;
+  }
+  return launch_kernel<T, MB, WPP, kPlain>(a, s);
 }
 
 // wpp wavefronts share a point in the rule (tiles of 1 or 2 points; forward, collapsed mode only)
