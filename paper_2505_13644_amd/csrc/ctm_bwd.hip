@@ -316,13 +316,14 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T *Zb, int ld_out, con
 }
 
 // fp32 version with LDS-direct loads (global_load_lds_dwordx4, as in the stacked-GEMM kernel): a stage is [16 k][128
-// features] per operand, unpadded (a wave instruction brings 1 KiB = two rows), two buffers; the 16-byte units of a row are
-// stored XOR-swizzled with 4 * (row & 3), so that the four k rows a fragment read touches fall into different banks.  All
-// addresses are a scalar base advanced by scalar adds plus constant per-lane offsets: the k loop holds LDS reads, MFMAs, the
-// loads and one barrier per stage and no vector-ALU instruction (the guards and 64-bit address arithmetic of the generic
-// kernel below cost its MFMA stream a fifth of its issue cycles).  Columns past the operand's width re-read column 0 of the
-// tile: they only reach output entries the reduction never reads.  A ragged last stage (fewer than 16 rows) goes through
-// registers with zero fill.
+// features] per operand, unpadded (a wave instruction brings 1 KiB = two rows), two buffers.  Within a wave's 64 x 64
+// block the MFMA row / column index l of block a stands for feature 4 l + a, so the four values a lane needs of one k row
+// are 16 contiguous bytes: one ds_read_b128 per operand and k group (the 16 lanes of a quarter-wave read 256 contiguous
+// bytes, conflict-free without any swizzle).  All addresses are a scalar base advanced by scalar adds plus constant
+// per-lane offsets: the k loop holds LDS reads, MFMAs, the loads and one barrier per stage and no vector-ALU instruction
+// (the guards and 64-bit address arithmetic of the generic kernel above cost its MFMA stream a fifth of its issue
+// cycles).  Columns past the operand's width re-read column 0 of the tile: they only reach output entries the reduction
+// never reads.  A ragged last stage (fewer than 16 rows) goes through registers with zero fill.
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, long M, long rows_per, int tj, float *partials) {
   extern __shared__ __align__(16) unsigned char wg_lds[];
@@ -345,12 +346,11 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
   unsigned c_voff[4];
   unsigned c_lds[4];
   {
-    const int r2 = lane >> 5, us = lane & 31;  // row inside the chunk, LDS unit slot
+    const int r2 = lane >> 5, u = lane & 31;  // row inside the chunk, 16-byte unit of the row
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = wave_u + 4 * i;
       const int row = 2 * (c & 7) + r2;
-      const int u = us ^ ((row & 3) * 4);      // the global unit this slot holds
       const bool isA = i < 2;
       const int ld = isA ? ld_out : ld_in;
       const int c0 = isA ? i0 : j0;
@@ -369,14 +369,9 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
     }
   };
 
-  // ---- fragment addresses: element (k row, feature) sits at row * 512 + ((feature / 4) ^ 4 * (row & 3)) * 16 + feature % 4 * 4
-  const float *Af[4], *Bf[4];
-#pragma unroll
-  for (int a = 0; a < 4; ++a) {
-    const int ua = (wi * 16 + a * 4 + (lr >> 2)) ^ (lg * 4), ub = (wj * 16 + a * 4 + (lr >> 2)) ^ (lg * 4);
-    Af[a] = reinterpret_cast<const float *>(wg_lds + lg * 512 + ua * 16 + (lr & 3) * 4);
-    Bf[a] = reinterpret_cast<const float *>(wg_lds + kOperand + lg * 512 + ub * 16 + (lr & 3) * 4);
-  }
+  // ---- fragments: lane (lr, lg) reads features 4 lr .. 4 lr + 3 of k row 4 kk + lg of its wave's 64-feature strip
+  const wf32x4 *Af = reinterpret_cast<const wf32x4 *>(wg_lds + lg * 512 + wi * 256 + lr * 16);
+  const wf32x4 *Bf = reinterpret_cast<const wf32x4 *>(wg_lds + kOperand + lg * 512 + wj * 256 + lr * 16);
 
   wf32x4 acc[4][4];
 #pragma unroll
@@ -387,11 +382,7 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
   auto stage_mfmas = [&](int buf) {
 #pragma unroll
     for (int kk = 0; kk < kWgK / 4; ++kk) {
-      float af[4], bf[4];
-#pragma unroll
-      for (int a = 0; a < 4; ++a) af[a] = Af[a][(buf * kBuffer + kk * 4 * 512) / 4];
-#pragma unroll
-      for (int b = 0; b < 4; ++b) bf[b] = Bf[b][(buf * kBuffer + kk * 4 * 512) / 4];
+      const wf32x4 af = Af[(buf * kBuffer + kk * 4 * 512) / 16], bf = Bf[(buf * kBuffer + kk * 4 * 512) / 16];
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -428,15 +419,14 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const int u4 = tid + q * 256;           // 512 units of 16 bytes per operand
-      const int row = u4 / 32, us = u4 % 32;
-      const int u = us ^ ((row & 3) * 4);
+      const int row = u4 / 32, u = u4 % 32;
       wf32x4 za = {0, 0, 0, 0}, zb = {0, 0, 0, 0};
       if (row < tail) {
         if (i0 + u * 4 < ld_out) za = *reinterpret_cast<const wf32x4 *>(Zb + (mt + row) * ld_out + i0 + u * 4);
         if (j0 + u * 4 < ld_in) zb = *reinterpret_cast<const wf32x4 *>(H + (mt + row) * ld_in + j0 + u * 4);
       }
-      *reinterpret_cast<wf32x4 *>(wg_lds + row * 512 + us * 16) = za;
-      *reinterpret_cast<wf32x4 *>(wg_lds + kOperand + row * 512 + us * 16) = zb;
+      *reinterpret_cast<wf32x4 *>(wg_lds + row * 512 + u * 16) = za;
+      *reinterpret_cast<wf32x4 *>(wg_lds + kOperand + row * 512 + u * 16) = zb;
     }
     __syncthreads();
     stage_mfmas(0);
@@ -446,16 +436,16 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
   const long pi = (long)gridDim.x / tj * kWgTile;  // padded rows
   const long pj = (long)tj * kWgTile;
   float *P = partials + (long)ks * pi * pj;
+  // block (a, b), accumulator element v of lane (lr, lg) is output row 4 (4 lg + v) + a, column 4 lr + b of the wave's
+  // 64 x 64 block: the four b of a lane are 16 contiguous bytes
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const long i = i0 + wi * 64 + a * 16 + lg * 4 + v;
-        const long j = j0 + wj * 64 + b * 16 + lr;
-        P[i * pj + j] = acc[a][b][v];
-      }
+    for (int v = 0; v < 4; ++v) {
+      const long i = i0 + wi * 64 + (lg * 4 + v) * 4 + a;
+      const long j = j0 + wj * 64 + lr * 4;
+      *reinterpret_cast<wf32x4 *>(P + i * pj + j) = wf32x4{acc[a][0][v], acc[a][1][v], acc[a][2][v], acc[a][3][v]};
+    }
 }
 
 // gW[i][j] = sum_k partials[k][i][j] in a fixed order: a block takes 64 outputs, its four wavefronts a quarter of
@@ -499,8 +489,8 @@ hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M
   const WgradPlan p = wgrad_plan(M, d_out, d_in);
   if (p.ti * p.tj <= 0 || p.ksplit <= 0 || p.ksplit > 65535) return hipErrorInvalidValue;
   if constexpr (std::is_same<T, float>::value) {
-    // 16-byte loads: both operands must be 16-byte aligned (their row pitches are multiples of 32 elements)
-    if ((reinterpret_cast<size_t>(Zbar) | reinterpret_cast<size_t>(H)) & 15) return hipErrorInvalidValue;
+    // 16-byte loads and stores: the operands and the partial sums must be 16-byte aligned (row pitches are multiples of 32 elements)
+    if ((reinterpret_cast<size_t>(Zbar) | reinterpret_cast<size_t>(H) | reinterpret_cast<size_t>(partials)) & 15) return hipErrorInvalidValue;
     constexpr size_t lds = 4 * (size_t)kWgK * kWgTile * sizeof(float);
     hipLaunchKernelGGL(wgrad_kernel_f32, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
                        p.rows_per, p.tj, partials);
