@@ -199,13 +199,17 @@ constexpr int kWgPitch = kWgTile + 16; // LDS row pitch in elements: the four k 
 constexpr int kWgTargetBlocks = 1024;  // about two rounds of resident workgroups
 
 struct WgradPlan {
-  int ti, tj, ksplit;
+  int ti, tj, ksplit, tile_i, tile_j;
   long rows_per;
 };
-static WgradPlan wgrad_plan(long M, int d_out, int d_in) {
+// tile_i x tile_j outputs per workgroup: 128 x 128, or 256 x 64 (fp32 kernel, inputs of at most 64 features: the first
+// layer of a low-dimensional problem would fill half of a 128-column tile or less)
+static WgradPlan wgrad_plan(long M, int d_out, int d_in, bool narrow) {
   WgradPlan p;
-  p.ti = (d_out + kWgTile - 1) / kWgTile;
-  p.tj = (d_in + kWgTile - 1) / kWgTile;
+  p.tile_i = narrow ? 2 * kWgTile : kWgTile;
+  p.tile_j = narrow ? kWgTile / 2 : kWgTile;
+  p.ti = (d_out + p.tile_i - 1) / p.tile_i;
+  p.tj = (d_in + p.tile_j - 1) / p.tile_j;
   long ks = kWgTargetBlocks / ((long)p.ti * p.tj);
   const long max_ks = (M + 8 * kWgK - 1) / (8 * kWgK);  // at least eight stages per block
   if (ks > max_ks) ks = max_ks;
@@ -215,9 +219,16 @@ static WgradPlan wgrad_plan(long M, int d_out, int d_in) {
   p.ksplit = (int)((M + p.rows_per - 1) / p.rows_per);
   return p;
 }
+static bool wgrad_narrow(int d_in, bool fp32) { return fp32 && d_in <= kWgTile / 2; }
 size_t wgrad_partial_elems(long M, int d_out, int d_in) {
-  const WgradPlan p = wgrad_plan(M, d_out, d_in);
-  return (size_t)p.ksplit * p.ti * kWgTile * p.tj * kWgTile;
+  // the caller's buffer serves either precision: the larger of the two plans
+  size_t need = 0;
+  for (int fp32 = 0; fp32 < 2; ++fp32) {
+    const WgradPlan p = wgrad_plan(M, d_out, d_in, wgrad_narrow(d_in, fp32 != 0));
+    const size_t n = (size_t)p.ksplit * p.ti * p.tile_i * p.tj * p.tile_j;
+    if (n > need) need = n;
+  }
+  return need;
 }
 
 template <typename T>
@@ -324,54 +335,61 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const T *Zb, int ld_out, con
 // (the guards and 64-bit address arithmetic of the generic kernel above cost its MFMA stream a fifth of its issue
 // cycles).  Columns past the operand's width re-read column 0 of the tile: they only reach output entries the reduction
 // never reads.  A ragged last stage (fewer than 16 rows) goes through registers with zero fill.
+// TI = 128: a 128 x 128 output tile, waves 2 x 2.  TI = 256: 256 x 64, waves 4 x 1 (narrow inputs).
+template <int TI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, long M, long rows_per, int tj, float *partials) {
   extern __shared__ __align__(16) unsigned char wg_lds[];
-  constexpr unsigned kOperand = kWgK * kWgTile * sizeof(float);  // 8 KiB
-  constexpr unsigned kBuffer = 2 * kOperand;
+  constexpr int TJ = 128 * 128 / TI;                                // 128 or 64
+  constexpr unsigned kRowA = TI * sizeof(float), kRowB = TJ * sizeof(float);   // LDS row pitches: 512 / 1024 and 512 / 256 B
+  constexpr unsigned kOperandA = kWgK * kRowA, kOperandB = kWgK * kRowB;
+  constexpr unsigned kBuffer = kOperandA + kOperandB;               // 16 or 20 KiB
+  constexpr int kChunksA = kOperandA / 1024, kChunksB = kOperandB / 1024;      // 8 + 8 or 16 + 4 chunks of 1 KiB
+  constexpr int NW = (kChunksA + kChunksB) / 4;                     // chunks per wave and stage: 4 or 5
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int lr = lane & 15, lg = lane >> 4;
-  const int wi = wave >> 1, wj = wave & 1;
+  const int wi = TI == 128 ? wave >> 1 : wave, wj = TI == 128 ? wave & 1 : 0;
   const int tile = blockIdx.x;
   const int ti = tile / tj, tjx = tile % tj;
   const int ks = blockIdx.y;
   const long m0 = ks * rows_per;
   const long m1 = (m0 + rows_per < M) ? m0 + rows_per : M;
-  const int i0 = ti * kWgTile, j0 = tjx * kWgTile;
+  const int i0 = ti * TI, j0 = tjx * TJ;
   const int nfull = (int)((m1 - m0) / kWgK);    // rows_per is a multiple of 16 below 2^35
   const int tail = (int)((m1 - m0) - (long)nfull * kWgK);
 
-  // ---- loads: chunk c of a stage = rows 2c', 2c'+1 of operand c / 8 (c' = c % 8); wave w takes chunks w, w+4, w+8, w+12
-  unsigned c_voff[4];
-  unsigned c_lds[4];
-  {
-    const int r2 = lane >> 5, u = lane & 31;  // row inside the chunk, 16-byte unit of the row
+  // ---- loads: a chunk is 1 KiB of a stage, i.e. 1024 / pitch whole rows; chunks 0 .. kChunksA-1 are Zbar, the others H;
+  // wave w takes chunks w, w+4, ... (kChunksA is a multiple of 4, so position i of every wave is the same operand)
+  unsigned c_voff[NW];
+  unsigned c_lds[NW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = wave_u + 4 * i;
-      const int row = 2 * (c & 7) + r2;
-      const bool isA = i < 2;
-      const int ld = isA ? ld_out : ld_in;
-      const int c0 = isA ? i0 : j0;
-      const int col = (c0 + u * 4 < ld) ? c0 + u * 4 : c0;
-      c_voff[i] = (unsigned)(((long)row * ld + col) * sizeof(float));
-      c_lds[i] = (unsigned)((isA ? 0u : kOperand) + (c & 7) * 1024u);
-    }
+  for (int i = 0; i < NW; ++i) {
+    const int c = wave_u + 4 * i;
+    const bool isA = 4 * i < kChunksA;
+    const int upr = (isA ? kRowA : kRowB) / 16;        // 16-byte units per row
+    const int cidx = isA ? c : c - kChunksA;
+    const int row = cidx * (64 / upr) + lane / upr;
+    const int u = lane % upr;
+    const int ld = isA ? ld_out : ld_in;
+    const int c0 = isA ? i0 : j0;
+    const int col = (c0 + u * 4 < ld) ? c0 + u * 4 : c0;
+    c_voff[i] = (unsigned)(((long)row * ld + col) * sizeof(float));
+    c_lds[i] = (isA ? 0u : kOperandA) + (unsigned)(cidx * 1024);
   }
   const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)wg_lds;
   auto issue = [&](int buf, const float *ga, const float *gb) {   // ga, gb: first row of the stage in either operand (uniform)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NW; ++i) {
       const unsigned off = lds_base + buf * kBuffer + c_lds[i];
-      const float *g = i < 2 ? ga : gb;
+      const float *g = 4 * i < kChunksA ? ga : gb;
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(c_voff[i]), "s"(off), "s"(g) : "memory");
     }
   };
 
   // ---- fragments: lane (lr, lg) reads features 4 lr .. 4 lr + 3 of k row 4 kk + lg of its wave's 64-feature strip
-  const wf32x4 *Af = reinterpret_cast<const wf32x4 *>(wg_lds + lg * 512 + wi * 256 + lr * 16);
-  const wf32x4 *Bf = reinterpret_cast<const wf32x4 *>(wg_lds + kOperand + lg * 512 + wj * 256 + lr * 16);
+  const wf32x4 *Af = reinterpret_cast<const wf32x4 *>(wg_lds + lg * kRowA + wi * 256 + lr * 16);
+  const wf32x4 *Bf = reinterpret_cast<const wf32x4 *>(wg_lds + kOperandA + lg * kRowB + wj * 256 + lr * 16);
 
   wf32x4 acc[4][4];
 #pragma unroll
@@ -382,7 +400,7 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
   auto stage_mfmas = [&](int buf) {
 #pragma unroll
     for (int kk = 0; kk < kWgK / 4; ++kk) {
-      const wf32x4 af = Af[(buf * kBuffer + kk * 4 * 512) / 16], bf = Bf[(buf * kBuffer + kk * 4 * 512) / 16];
+      const wf32x4 af = Af[(buf * kBuffer + kk * 4 * kRowA) / 16], bf = Bf[(buf * kBuffer + kk * 4 * kRowB) / 16];
 #pragma unroll
       for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -416,25 +434,30 @@ void wgrad_kernel_f32(const float *Zb, int ld_out, const float *H, int ld_in, lo
     // fewer than 16 rows left: through registers, rows past the end are zeros.  Every wave passed the barrier that ends
     // the last full stage (and its surplus loads have landed), so buffer 0 is free.
     const long mt = m0 + (long)nfull * kWgK;
+    constexpr int kUprA = kRowA / 16, kUprB = kRowB / 16;   // 16-byte units per row
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int u4 = tid + q * 256;           // 512 units of 16 bytes per operand
-      const int row = u4 / 32, u = u4 % 32;
-      wf32x4 za = {0, 0, 0, 0}, zb = {0, 0, 0, 0};
-      if (row < tail) {
-        if (i0 + u * 4 < ld_out) za = *reinterpret_cast<const wf32x4 *>(Zb + (mt + row) * ld_out + i0 + u * 4);
-        if (j0 + u * 4 < ld_in) zb = *reinterpret_cast<const wf32x4 *>(H + (mt + row) * ld_in + j0 + u * 4);
-      }
-      *reinterpret_cast<wf32x4 *>(wg_lds + row * 512 + u * 16) = za;
-      *reinterpret_cast<wf32x4 *>(wg_lds + kOperand + row * 512 + u * 16) = zb;
+    for (int q = 0; q < kWgK * kUprA / 256; ++q) {
+      const int u4 = tid + q * 256;
+      const int row = u4 / kUprA, u = u4 % kUprA;
+      wf32x4 za = {0, 0, 0, 0};
+      if (row < tail && i0 + u * 4 < ld_out) za = *reinterpret_cast<const wf32x4 *>(Zb + (mt + row) * ld_out + i0 + u * 4);
+      *reinterpret_cast<wf32x4 *>(wg_lds + row * kRowA + u * 16) = za;
+    }
+#pragma unroll
+    for (int q = 0; q < kWgK * kUprB / 256; ++q) {
+      const int u4 = tid + q * 256;
+      const int row = u4 / kUprB, u = u4 % kUprB;
+      wf32x4 zb = {0, 0, 0, 0};
+      if (row < tail && j0 + u * 4 < ld_in) zb = *reinterpret_cast<const wf32x4 *>(H + (mt + row) * ld_in + j0 + u * 4);
+      *reinterpret_cast<wf32x4 *>(wg_lds + kOperandA + row * kRowB + u * 16) = zb;
     }
     __syncthreads();
     stage_mfmas(0);
   }
 
   // partial tile -> partials[ks][i][j] (padded to whole tiles)
-  const long pi = (long)gridDim.x / tj * kWgTile;  // padded rows
-  const long pj = (long)tj * kWgTile;
+  const long pi = (long)gridDim.x / tj * TI;  // padded rows
+  const long pj = (long)tj * TJ;
   float *P = partials + (long)ks * pi * pj;
   // block (a, b), accumulator element v of lane (lr, lg) is output row 4 (4 lg + v) + a, column 4 lr + b of the wave's
   // 64 x 64 block: the four b of a lane are 16 contiguous bytes
@@ -486,14 +509,18 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const T *partials, in
 template <typename T>
 hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M, int d_out, int d_in, T *gW, T *partials,
                         hipStream_t s, int accumulate) {
-  const WgradPlan p = wgrad_plan(M, d_out, d_in);
+  const WgradPlan p = wgrad_plan(M, d_out, d_in, wgrad_narrow(d_in, std::is_same<T, float>::value));
   if (p.ti * p.tj <= 0 || p.ksplit <= 0 || p.ksplit > 65535) return hipErrorInvalidValue;
   if constexpr (std::is_same<T, float>::value) {
     // 16-byte loads and stores: the operands and the partial sums must be 16-byte aligned (row pitches are multiples of 32 elements)
     if ((reinterpret_cast<size_t>(Zbar) | reinterpret_cast<size_t>(H) | reinterpret_cast<size_t>(partials)) & 15) return hipErrorInvalidValue;
-    constexpr size_t lds = 4 * (size_t)kWgK * kWgTile * sizeof(float);
-    hipLaunchKernelGGL(wgrad_kernel_f32, dim3((unsigned)(p.ti * p.tj), (unsigned)p.ksplit), dim3(256), lds, s, Zbar, ld_out, H, ld_in, M,
-                       p.rows_per, p.tj, partials);
+    const dim3 grid((unsigned)(p.ti * p.tj), (unsigned)p.ksplit);
+    const size_t lds = 2 * (size_t)kWgK * (p.tile_i + p.tile_j) * sizeof(float);
+    if (p.tile_i == kWgTile) {
+      hipLaunchKernelGGL(wgrad_kernel_f32<128>, grid, dim3(256), lds, s, Zbar, ld_out, H, ld_in, M, p.rows_per, p.tj, partials);
+    } else {
+      hipLaunchKernelGGL(wgrad_kernel_f32<256>, grid, dim3(256), lds, s, Zbar, ld_out, H, ld_in, M, p.rows_per, p.tj, partials);
+    }
   } else {
     constexpr size_t lds = 4 * (size_t)kWgK * kWgPitch * sizeof(T);
     static LdsLimitOnce lds_limit;
@@ -506,8 +533,8 @@ hipError_t launch_wgrad(const T *Zbar, int ld_out, const T *H, int ld_in, long M
   if (e != hipSuccess) return e;
   const long blocks = ((long)d_out * d_in + 63) / 64;
   if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(wgrad_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, partials, p.ksplit, (long)p.ti * kWgTile,
-                     (long)p.tj * kWgTile, d_out, d_in, gW, accumulate);
+  hipLaunchKernelGGL(wgrad_reduce_kernel<T>, dim3((unsigned)blocks), dim3(256), 0, s, partials, p.ksplit, (long)p.ti * p.tile_i,
+                     (long)p.tj * p.tile_j, d_out, d_in, gW, accumulate);
   return hipGetLastError();
 }
 template hipError_t launch_wgrad<float>(const float *, int, const float *, int, long, int, int, float *, float *, hipStream_t, int);
