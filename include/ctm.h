@@ -124,6 +124,25 @@ int ctm_laplacian(const ctm_mlp *mlp, const void *x, long N, const void *V, int 
                   size_t workspace_bytes, void *stream);
 
 /*
+ * ctm_laplacian for callers that cannot allocate device memory at all: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments and results (bit for bit, the same kernels
+ * run) as ctm_laplacian, but the workspace is a device array built into the library, CTM_STATIC_SCRATCH_BYTES
+ * long; every GPU the library runs on holds its copy until the process ends.  The call allocates nothing and
+ * frees nothing; the caller still owns x, V, u and op.
+ *   - A request with ctm_workspace_bytes(mlp, 2, N, R) > CTM_STATIC_SCRATCH_BYTES returns CTM_ERR_WORKSPACE
+ *     and launches nothing (the benchmark network with basis directions fits 204 points; split larger
+ *     batches or use ctm_laplacian).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *     threads) race.  Calls in stream order on one stream are fine; the array keeps the previous call's
+ *     contents and every element a call reads is written by that call first, so nothing needs clearing.
+ *   - The first call on a device looks up the array's address (hipGetSymbolAddress); make one call before
+ *     starting a graph capture.
+ */
+#define CTM_STATIC_SCRATCH_BYTES (64u << 20)
+int ctm_laplacian_static(const ctm_mlp *mlp, const void *x, long N, const void *V, int R,
+                         long v_point_stride, double scale, void *u, void *op, void *stream);
+
+/*
  * Weighted Laplacian  op[n] = Tr(sigma sigma^T Hessian f(x_n)) = sum_k s_k^T H s_k     (Sec. 3.2, Eq. 8)
  *   sigma   dev [D, K] row-major, shared by all points; the directions are its K columns
  * Same as ctm_laplacian with V = sigma^T, shared, scale = 1.

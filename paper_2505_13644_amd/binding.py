@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libctm.so")
 CTM_F64, CTM_F32, CTM_F32_BF16X3, CTM_F32_BF16 = 0, 1, 2, 3
 CTM_ACT_TANH, CTM_ACT_IDENTITY, CTM_ACT_SIN = 0, 1, 2
 CTM_OK = 0
+CTM_STATIC_SCRATCH_BYTES = 64 << 20   # size of the device array behind ctm_laplacian_static
 STATUS_NAMES = {
     0: "CTM_OK", -1: "CTM_ERR_NULL", -2: "CTM_ERR_SHAPE", -3: "CTM_ERR_DTYPE", -4: "CTM_ERR_UNSUPPORTED",
     -5: "CTM_ERR_WORKSPACE", -6: "CTM_ERR_ALIGN", -7: "CTM_ERR_ALLOC", -8: "CTM_ERR_HIP",
@@ -30,6 +31,8 @@ SIGNATURES = {
     "ctm_workspace_bytes": (c_size_t, [c_void_p, c_int, c_long, c_int]),
     "ctm_laplacian": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p,
                               c_void_p, c_size_t, c_void_p]),
+    "ctm_laplacian_static": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_double, c_void_p, c_void_p,
+                                     c_void_p]),
     "ctm_weighted_laplacian": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_void_p, c_void_p, c_void_p,
                                        c_size_t, c_void_p]),
     "ctm_biharmonic_rand": (c_int, [c_void_p, c_void_p, c_long, c_void_p, c_int, c_long, c_void_p, c_void_p,
@@ -278,6 +281,21 @@ def ctm_laplacian(mlp: Mlp, x, V=None, scale=1.0, u=None, op=None, workspace=Non
                                float(scale), _dev_ptr(u, mlp.dtype, "u"), _dev_ptr(op, mlp.dtype, "op"),
                                c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                _stream_ptr()))
+    return u, op
+
+
+def ctm_laplacian_static(mlp: Mlp, x, V, scale, u, op):
+    """ctm_laplacian on the library's built-in device scratch array: no workspace argument, and nothing is allocated
+    here either -- u and op must be passed in.  V as in ctm_laplacian.  Returns (u, op)."""
+    _check_shapes(mlp, x, V)
+    N = x.shape[0]
+    R, stride = _dirs_of(x, V)
+    for name, t in (("u", u), ("op", op)):
+        if t is None or tuple(t.shape) != _out_shape(mlp, N):
+            raise ValueError(f"{name} must be a preallocated tensor of shape {list(_out_shape(mlp, N))}")
+    _check(lib().ctm_laplacian_static(mlp.handle, _dev_ptr(x, mlp.dtype, "x"), N, _dev_ptr(V, mlp.dtype, "V"), R, stride,
+                                      float(scale), _dev_ptr(u, mlp.dtype, "u"), _dev_ptr(op, mlp.dtype, "op"),
+                                      _stream_ptr()))
     return u, op
 
 

@@ -1,5 +1,6 @@
 // C ABI of libctm.so: argument validation, tiling plan, workspace carving and the
 // per-call launch sequence  seed -> (stacked GEMM + jet rule) per hidden layer -> last layer.
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -12,6 +13,10 @@
 #include "ctm_internal.h"
 
 using namespace ctm;
+
+// Device memory of ctm_laplacian_static: one array per GPU the library runs on, held until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress; kernels and copies get the address it returns.
+static __device__ __align__(256) unsigned char scratch[CTM_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -304,6 +309,23 @@ int check_device(const ctm_mlp *m, const char *who) {
   if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
   if (dev != m->device)
     return fail(CTM_ERR_UNSUPPORTED, "%s: the handle belongs to device %d but device %d is current", who, m->device, dev);
+  return CTM_OK;
+}
+
+// Address of the current device's copy of `scratch`: looked up once per device, with that device current
+// (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+int static_scratch(int device, const char *who, void **out) {
+  if (device < 0 || device >= kMaxDevices) return fail(CTM_ERR_UNSUPPORTED, "%s: device index %d is out of range", who, device);
+  void *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+  if (!p) {
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress of the built-in scratch array");
+    if (!p) return fail(CTM_ERR_HIP, "%s: the built-in scratch array has no device address", who);
+    g_scratch_ptr[device].store(p, std::memory_order_release);
+  }
+  *out = p;
   return CTM_OK;
 }
 
@@ -710,6 +732,31 @@ int ctm_laplacian(const ctm_mlp *m, const void *x, long N, const void *V, int R,
                 (long)R * m->dims[0]);
   const long D = m ? m->dims[0] : 0;
   return run_operator(m, 2, x, N, V, R, v_point_stride, D, 1, scale, u, op, ws, ws_bytes, stream, "ctm_laplacian");
+}
+
+int ctm_laplacian_static(const ctm_mlp *m, const void *x, long N, const void *V, int R, long v_point_stride, double scale,
+                         void *u, void *op, void *stream) {
+  const char *who = "ctm_laplacian_static";
+  if (!m) return fail(CTM_ERR_NULL, "%s: mlp handle is NULL", who);
+  if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
+  if (R < 1) return fail(CTM_ERR_SHAPE, "%s: %d directions, need at least 1", who, R);
+  if (!V && R != m->dims[0])
+    return fail(CTM_ERR_SHAPE, "%s: V = NULL selects the standard basis, so R must be D = %d (got %d)", who, m->dims[0], R);
+  if (v_point_stride != 0 && v_point_stride != (long)R * m->dims[0])
+    return fail(CTM_ERR_SHAPE, "%s: v_point_stride = %ld, must be 0 (shared) or R*D = %ld", who, v_point_stride,
+                (long)R * m->dims[0]);
+  if (N > (1L << 40) / rows_per_point(2, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
+  const size_t need = workspace_layout(m, 2, N, split_dirs(2, R).first).total;
+  if (need > (size_t)CTM_STATIC_SCRATCH_BYTES)
+    return fail(CTM_ERR_WORKSPACE,
+                "%s: N = %ld points with %d directions need %zu bytes of scratch, the built-in array holds %zu; "
+                "use ctm_laplacian with a workspace of your own",
+                who, N, R, need, (size_t)CTM_STATIC_SCRATCH_BYTES);
+  if (int rc = check_device(m, who)) return rc;
+  void *ws = nullptr;
+  if (int rc = static_scratch(m->device, who, &ws)) return rc;
+  return run_operator(m, 2, x, N, V, R, v_point_stride, m->dims[0], 1, scale, u, op, ws, (size_t)CTM_STATIC_SCRATCH_BYTES,
+                      stream, who);
 }
 
 int ctm_weighted_laplacian(const ctm_mlp *m, const void *x, long N, const void *sigma, int K, void *u, void *op,
