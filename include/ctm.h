@@ -130,7 +130,7 @@ int ctm_laplacian(const ctm_mlp *mlp, const void *x, long N, const void *V, int 
  * long; every GPU the library runs on holds its copy until the process ends.  The call allocates nothing and
  * frees nothing; the caller still owns x, V, u and op.
  *   - A request with ctm_workspace_bytes(mlp, 2, N, R) > CTM_STATIC_SCRATCH_BYTES returns CTM_ERR_WORKSPACE
- *     and launches nothing (the benchmark network with basis directions fits 204 points; split larger
+ *     and launches nothing (the benchmark network with basis directions fits 206 points; split larger
  *     batches or use ctm_laplacian).
  *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
  *     threads) race.  Calls in stream order on one stream are fine; the array keeps the previous call's
@@ -195,6 +195,10 @@ int ctm_biharmonic_rand(const ctm_mlp *mlp, const void *x, long N, const void *V
  * stacked-GEMM kernel), the weight gradient Zbar^T H over all N * rho rows, and the bias gradient.
  *
  * ctm_update_mlp re-packs new weights (same shapes) into an existing handle, e.g. after an optimizer step.
+ * The reverse pass reads the weights from the handle, so a *_bwd call must find the weights its *_fwd call ran with:
+ * a handle remembers, per tape address, which update of its weights the recording forward saw, and a *_bwd call
+ * on a tape recorded before the latest ctm_update_mlp returns CTM_ERR_UNSUPPORTED (run forward again).  Calls
+ * that replace the weights must not overlap with operator calls on the same handle.
  */
 size_t ctm_tape_bytes(const ctm_mlp *mlp, long N, int R);
 size_t ctm_backward_workspace_bytes(const ctm_mlp *mlp, long N, int R);

@@ -15,11 +15,24 @@ import torch
 from . import binding as B
 
 
+def _sync_weights(mlp, Ws, bs):
+    """Re-pack the weights into the handle unless it already holds exactly these tensors at these versions.
+
+    The reverse pass reads the weights from the handle, so the handle must still hold a forward's weights when its
+    backward runs: several forwards with unchanged parameters (interior and boundary points of one loss) share one
+    packing, and a parameter update between a forward and its backward makes the library refuse that backward
+    (CTM_ERR_UNSUPPORTED) instead of returning gradients of the wrong network."""
+    key = tuple((t.data_ptr(), t._version, tuple(t.shape)) for t in (*Ws, *bs))
+    if getattr(mlp, "_packed_key", None) != key:
+        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        mlp._packed_key = key
+
+
 class _Laplacian(torch.autograd.Function):
     @staticmethod
     def forward(ctx, mlp, x, V, scale, n_layers, *params):
         Ws, bs = list(params[:n_layers]), list(params[n_layers:])
-        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        _sync_weights(mlp, Ws, bs)
         u, op, tape = B.ctm_laplacian_fwd(mlp, x, V, scale)
         ctx.mlp, ctx.tape, ctx.scale, ctx.n_layers = mlp, tape, scale, n_layers
         ctx.N = x.shape[0]
@@ -38,7 +51,7 @@ class _BiharmonicRand(torch.autograd.Function):
     @staticmethod
     def forward(ctx, mlp, x, V, n_layers, *params):
         Ws, bs = list(params[:n_layers]), list(params[n_layers:])
-        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        _sync_weights(mlp, Ws, bs)
         u, op, tape = B.ctm_biharmonic_rand_fwd(mlp, x, V)
         ctx.mlp, ctx.tape, ctx.N, ctx.S = mlp, tape, x.shape[0], V.shape[-2]
         return u, op
@@ -55,7 +68,7 @@ class _BiharmonicExact(torch.autograd.Function):
     @staticmethod
     def forward(ctx, mlp, x, n_layers, *params):
         Ws, bs = list(params[:n_layers]), list(params[n_layers:])
-        B.ctm_update_mlp(mlp, [W.detach().contiguous() for W in Ws], [b.detach().contiguous() for b in bs])
+        _sync_weights(mlp, Ws, bs)
         u, op, tape = B.ctm_biharmonic_exact_fwd(mlp, x)
         ctx.mlp, ctx.tape, ctx.N = mlp, tape, x.shape[0]
         return u, op

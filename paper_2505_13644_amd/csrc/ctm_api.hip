@@ -4,9 +4,11 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 #include <new>
 #include <string>
 #include <type_traits>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/ctm.h"
@@ -115,7 +117,7 @@ PassPlan plan_pass(int K, int R, bool standard = false, long N = -1, int col_til
   return small;
 }
 
-// ---- interpolation coefficients gamma_{i,j} (App. E, Eq. "ttc_coeff"), exact rational arithmetic
+// ---- interpolation coefficients gamma_{i,j} (App. E, general coefficient formula for gamma_{i,j}), exact rational arithmetic
 struct Frac {
   long long n = 0, d = 1;
 };
@@ -131,8 +133,29 @@ Frac norm(Frac f) {
   f.n /= g; f.d /= g;
   return f;
 }
-Frac mul(Frac a, Frac b) { return norm(Frac{a.n * b.n, a.d * b.d}); }
-Frac add(Frac a, Frac b) { return norm(Frac{a.n * b.d + b.n * a.d, a.d * b.d}); }
+// Products are formed in 128 bits and reduced before they return to 64: the intermediates of the coefficient formula
+// at |i| = 8 pass 1e17, and a product of two of those would not fit.  `overflow` is raised if a reduced value still
+// does not fit 63 bits (none does for |i| <= 8, I <= 4; checked against exact big-integer fractions in the tests).
+thread_local bool g_frac_overflow = false;
+__int128 gcd128(__int128 a, __int128 b) {
+  a = a < 0 ? -a : a;
+  b = b < 0 ? -b : b;
+  while (b) { __int128 t = a % b; a = b; b = t; }
+  return a ? a : 1;
+}
+Frac reduce128(__int128 n, __int128 d) {
+  if (d < 0) { n = -n; d = -d; }
+  const __int128 g = gcd128(n, d);
+  n /= g; d /= g;
+  const __int128 lim = (__int128)0x7fffffffffffffffLL;
+  if (n > lim || n < -lim || d > lim) g_frac_overflow = true;
+  return Frac{(long long)n, (long long)d};
+}
+Frac mul(Frac a, Frac b) { return reduce128((__int128)a.n * b.n, (__int128)a.d * b.d); }
+Frac add(Frac a, Frac b) {
+  const long long g = gcd_ll(a.d, b.d);   // common denominator lcm(a.d, b.d), not a.d * b.d
+  return reduce128((__int128)a.n * (b.d / g) + (__int128)b.n * (a.d / g), (__int128)a.d * (b.d / g));
+}
 // generalised binomial (a over b) = prod_{l<b} (a - l) / (b - l), a rational, b a non-negative integer
 Frac gbinom(Frac a, int b) {
   Frac r{1, 1};
@@ -191,6 +214,24 @@ struct ctm_mlp {
   int slots = 512;               // resident workgroups of the layer kernel: 2 per compute unit
   int min_col_tiles = 1;         // fewest column tiles among the hidden layers
   std::vector<void *> WT;        // l = 1..L-2: W_l transposed, [pad(dims[l])][ld(dims[l+1])], for the reverse pass
+  // The reverse pass reads the weights from the handle, so it must find the weights its forward ran with: every
+  // ctm_update_mlp bumps `version`, a recording forward notes the version under its tape's address, and the matching
+  // reverse pass refuses to run on another version.  (Bounded: the notes are dropped once there are kMaxTapeNotes.)
+  static constexpr size_t kMaxTapeNotes = 1024;
+  mutable std::mutex mu;
+  unsigned long long version = 1;
+  mutable std::unordered_map<const void *, unsigned long long> tape_version;
+  void note_tape(const void *tape) const {
+    std::lock_guard<std::mutex> g(mu);
+    if (tape_version.size() >= kMaxTapeNotes) tape_version.clear();
+    tape_version[tape] = version;
+  }
+  // true unless the tape is known to come from a forward with other weights than the handle holds now
+  bool tape_matches(const void *tape) const {
+    std::lock_guard<std::mutex> g(mu);
+    auto it = tape_version.find(tape);
+    return it == tape_version.end() || it->second == version;
+  }
 };
 
 namespace {
@@ -817,6 +858,11 @@ int ctm_weighted_laplacian_rand(const ctm_mlp *m, const void *x, long N, const v
   if (misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: workspace must be 256-byte aligned", who);
   if (misaligned(sigma, es) || misaligned(V, es))
     return fail(CTM_ERR_ALIGN, "%s: sigma and V must be aligned to the element size", who);
+  // everything run_operator would refuse is refused here, before the direction kernel is queued
+  if (!x) return fail(CTM_ERR_NULL, "%s: x is NULL", who);
+  if (N > (1L << 40) / rows_per_point(2, S)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
+  if (misaligned(x, es) || misaligned(u, es) || misaligned(op, es))
+    return fail(CTM_ERR_ALIGN, "%s: x, u and op must be aligned to the element size", who);
   const bool per_point = sigma_point_stride != 0 || v_point_stride != 0;
   const long Nd = per_point ? N : 1;
   const size_t dbytes = round256((size_t)Nd * S * D * es);
@@ -841,6 +887,10 @@ int ctm_update_mlp(ctm_mlp *m, const void *const *W, const void *const *b, void 
       return fail(CTM_ERR_ALIGN, "ctm_update_mlp: W[%d] / b[%d] not aligned to the element size", l, l);
   }
   if (int rc = check_device(m, "ctm_update_mlp")) return rc;
+  {
+    std::lock_guard<std::mutex> g(m->mu);
+    ++m->version;
+  }
   hipError_t e = pack_everything(m, W, b, reinterpret_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "ctm_update_mlp: weight packing");
   return CTM_OK;
@@ -886,6 +936,7 @@ int recording_forward(const char *who, const ctm_mlp *m, int K, const void *x, l
   if (misaligned(x, es) || misaligned(V, es) || misaligned(u, es) || misaligned(op, es))
     return fail(CTM_ERR_ALIGN, "%s: x, directions, u and op must be aligned to the element size", who);
   if (int rc2 = check_device(m, who)) return rc2;
+  m->note_tape(tape);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
     return run_fwd_tape<double>(m, K, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st);
@@ -907,6 +958,8 @@ int reverse_pass(const char *who, const ctm_mlp *m, int K, long N, int R, double
     if ((gW && misaligned(gW[l], es)) || (gb && misaligned(gb[l], es)))
       return fail(CTM_ERR_ALIGN, "%s: gW[%d] / gb[%d] not aligned to the element size", who, l, l);
   if (int rc2 = check_device(m, who)) return rc2;
+  if (!m->tape_matches(tape))
+    return fail(CTM_ERR_UNSUPPORTED, "%s: the handle's weights were replaced (ctm_update_mlp) after the forward call that recorded this tape", who);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
     return run_bwd<double>(m, K, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st);
@@ -949,7 +1002,9 @@ int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, l
     sj += j[t];
   }
   if (si != sj || si < 1 || si > 8) return fail(CTM_ERR_SHAPE, "ctm_interpolation_gamma: |i| = %d and |j| = %d must agree and lie in 1..8", si, sj);
+  g_frac_overflow = false;
   const Frac g = interp_gamma(I, i, j);
+  if (g_frac_overflow) return fail(CTM_ERR_UNSUPPORTED, "ctm_interpolation_gamma: an intermediate fraction does not fit 64 bits");
   *num = g.n;
   *den = g.d;
   return CTM_OK;
@@ -1038,6 +1093,7 @@ int ctm_biharmonic_exact_fwd(const ctm_mlp *m, const void *x, long N, void *u, v
   if (misaligned(x, es) || misaligned(u, es) || misaligned(op, es))
     return fail(CTM_ERR_ALIGN, "%s: x, u and op must be aligned to the element size", who);
   if ((rc = check_device(m, who)) != CTM_OK) return rc;
+  m->note_tape(tape);
   const int D = m->dims[0];
   const BiharmFamilies f = biharm_families(D);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -1080,6 +1136,8 @@ int ctm_biharmonic_exact_bwd(const ctm_mlp *m, long N, const void *tape, size_t 
     if ((gW && misaligned(gW[l], es)) || (gb && misaligned(gb[l], es)))
       return fail(CTM_ERR_ALIGN, "%s: gW[%d] / gb[%d] not aligned to the element size", who, l, l);
   if ((rc = check_device(m, who)) != CTM_OK) return rc;
+  if (!m->tape_matches(tape))
+    return fail(CTM_ERR_UNSUPPORTED, "%s: the handle's weights were replaced (ctm_update_mlp) after the forward call that recorded this tape", who);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const char *tp = (const char *)tape;
   bool first = true;

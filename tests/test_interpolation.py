@@ -58,3 +58,37 @@ def test_gamma_rejects_bad_arguments():
         ctm.ctm_interpolation_gamma((2, 2), (3, 2))
     with pytest.raises(ctm.CtmError):
         ctm.ctm_interpolation_gamma((9, 0), (9, 0))
+
+
+def gamma_bigint(i, j):
+    """The coefficient formula of App. E in Python's unbounded fractions (no 64-bit limit anywhere):
+    gamma_{i,j} = sum_{0 < m <= i} (-1)^{|i-m|} (i over m) (|i| m / |m| over j) (|m| / |i|)^{|i|}."""
+    def gbinom(a, b):
+        r = Fraction(1)
+        for l in range(b):
+            r *= (a - l) / Fraction(b - l)
+        return r
+    K = sum(i)
+    total = Fraction(0)
+    for m in itertools.product(*[range(t + 1) for t in i]):
+        if sum(m) == 0:
+            continue
+        term = Fraction((-1) ** (K - sum(m)))
+        for t in range(len(i)):
+            term *= gbinom(Fraction(i[t]), m[t]) * gbinom(Fraction(K * m[t], sum(m)), j[t])
+        total += term * Fraction(sum(m), K) ** K
+    return total
+
+
+@pytest.mark.parametrize("i", [(2, 2, 2, 2), (5, 1, 1, 1), (3, 3, 1, 1), (4, 4), (7, 1), (2, 2, 2, 1), (4, 2, 1), (8,), (3, 2, 2, 1)])
+def test_gamma_at_the_largest_orders_matches_unbounded_fractions(i):
+    # the library's 64-bit fractions (128-bit intermediates) at |i| = 7 and 8 with up to four directions, every j
+    K, I = sum(i), len(i)
+    worst = 0
+    for j in itertools.product(range(K + 1), repeat=I):
+        if sum(j) != K:
+            continue
+        want = gamma_bigint(i, j)
+        assert ctm.ctm_interpolation_gamma(i, j) == want, (i, j)
+        worst = max(worst, abs(want.numerator), want.denominator)
+    assert worst < 2 ** 63

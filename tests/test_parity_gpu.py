@@ -35,6 +35,32 @@ def tol_of(dtype):
     return TOL64 if dtype == np.float64 else TOL32
 
 
+# Regression guards: what the arithmetic actually delivers, with a small margin -- far inside the bars above, so that a
+# kernel change that loses a decimal digit or two fails here although it would still pass the bar.  fp32 native: one
+# rounding per product / accumulate, dot products of at most 768 terms, four layers: observed 1e-6.  Split bf16 keeps
+# about 16 bits per operand: observed 1e-5.
+GUARD = {"f32": 2e-5, "bf16x3": 1e-4, "bf16": 2e-2}
+
+
+def check_every_point(got, ref, tol, guard, what):
+    """Per-point mixed tolerance and a relative l2 error beside the scaled max-norm: |d_n| <= tol |ref_n| + guard max|ref|
+    for every point n (an absolute floor is needed because the operator is a sum of signed terms that can cancel to
+    ~0 at a point while the rounding error stays at the scale of the terms), ||d||_2 <= tol ||ref||_2, and the scaled
+    max-norm itself inside the guard."""
+    for name, g, r in (("u", got[0], ref[0]), ("op", got[1], ref[1])):
+        g, r = np.asarray(g, dtype=np.float64), np.asarray(r, dtype=np.float64)
+        d = np.abs(g - r)
+        scale = np.max(np.abs(r))
+        bound = tol * np.abs(r) + guard * scale
+        worst = int(np.argmax(d - bound))
+        l2 = np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-300)
+        print(f"[{what}] {name}: scaled max {np.max(d) / scale:.3e} (guard {guard:g}), rel l2 {l2:.3e}, "
+              f"worst point {worst}: |d| {d[worst]:.3e} vs bound {bound[worst]:.3e}", flush=True)
+        assert np.all(d <= bound), f"{what}: {name}[{worst}] off by {d[worst]:.3e}, allowed {bound[worst]:.3e}"
+        assert l2 <= tol, f"{what}: relative l2 error of {name} {l2:.3e}"
+        assert np.max(d) <= guard * scale, f"{what}: {name} scaled max error {np.max(d) / scale:.3e} above the regression guard {guard:g}"
+
+
 # ---------------------------------------------------------------------------
 # the five named workloads
 # ---------------------------------------------------------------------------
@@ -63,19 +89,19 @@ def test_named_workloads_reduced_batch(name, N):
         check((got[0][idx], got[1][idx]), ref_h, w.tol, "c2 full-Hessian trace")
 
 
-def test_benchmark_shape_in_fp64_sampled():
+def test_benchmark_shape_in_fp64_every_point():
     # the benchmark's network, batch and directions with every array widened to fp64: the fp64 kernels at the tile
-    # shape and launch size the fp32 benchmark uses (three workgroups per CU, two 32-column chunks per tile)
+    # shape and launch size the fp32 benchmark uses (three workgroups per CU, two 32-column chunks per tile).  The
+    # oracle widens its inputs to fp64 anyway, so its result for c2 is the reference here too.
     w = synth.WORKLOADS["c2"]
-    arrs = w.build()
+    arrs32 = w.build()
     wide = lambda v: [a.astype(np.float64) for a in v] if isinstance(v, list) else (v.astype(np.float64) if isinstance(v, np.ndarray) else v)
-    arrs = {k: wide(v) for k, v in arrs.items()}
-    print(f"case c2 in fp64, full N={w.N}", flush=True)
-    gu, go = gpu_run(arrs, w.op)
-    idx = np.sort(np.random.default_rng(5).choice(w.N, 10, replace=False))
-    idx[0], idx[-1] = 0, w.N - 1
-    check((gu[idx], go[idx]), oracle_run(arrs, w.op, idx=idx), TOL64, "c2 in fp64, full-size sample")
-    assert np.all(np.isfinite(go)) and np.all(np.isfinite(gu))
+    arrs = {k: wide(v) for k, v in arrs32.items()}
+    print(f"case c2 in fp64, full N={w.N}, every point", flush=True)
+    got = gpu_run(arrs, w.op)
+    ref = full_size_oracle("c2", arrs32)
+    check(got, ref, TOL64, "c2 in fp64, full size")
+    check_every_point(got, ref, TOL64, TOL64, "c2 in fp64, full size")
 
 
 @pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c3", 48), ("c4", 64), ("c5", 48), ("e1", 12)])
@@ -104,6 +130,48 @@ def test_named_workloads_full_size_sampled(name, n_sample):
     mlp.close()
 
 
+_FULL_ORACLE = {}
+
+
+def full_size_oracle(name, arrs):
+    """The oracle on every point of a named workload (directional mode); computed once per test session."""
+    if name not in _FULL_ORACLE:
+        w = synth.WORKLOADS[name]
+        _FULL_ORACLE[name] = oracle_run(arrs, w.op)
+    return _FULL_ORACLE[name]
+
+
+def split_batch(arrs, lo, hi):
+    sub = dict(arrs)
+    sub["x"] = arrs["x"][lo:hi]
+    if arrs.get("V") is not None and arrs["V"].ndim == 3:
+        sub["V"] = arrs["V"][lo:hi]
+    return sub
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5", "e1"])
+def test_named_workloads_full_size_every_point(name):
+    # the launch configuration the benchmark times, compared with the oracle (directional mode: R second / fourth
+    # directional derivatives per point) on EVERY point, and bitwise batch independence for every point: the batch
+    # cut at a point that is no multiple of any tile height gives the same bits as the full batch
+    w = synth.WORKLOADS[name]
+    arrs = w.build()
+    print(f"case {name} full N={w.N}, every point", flush=True)
+    gu, go, mlp = gpu_run(arrs, w.op, return_mlp=True)
+    ru, ro = full_size_oracle(name, arrs)
+    check((gu, go), (ru, ro), w.tol, f"{name} full size, all {w.N} points")
+    check_every_point((gu, go), (ru, ro), w.tol, GUARD["f32"], f"{name} full size")
+    if name == "c2":   # the other oracle mode (full Hessian, then its trace) on three points
+        idx = [0, 2049, w.N - 1]
+        ref_h = oracle_run(arrs, w.op, idx=idx, mode="hessian")
+        assert err(ref_h[1], ro[idx]) <= 1e-10
+    cut = w.N // 2 + 3
+    parts = [gpu_run(split_batch(arrs, lo, hi), w.op, mlp=mlp) for lo, hi in ((0, cut), (cut, w.N))]
+    assert np.array_equal(np.concatenate([p[0] for p in parts]), gu)
+    assert np.array_equal(np.concatenate([p[1] for p in parts]), go)
+    mlp.close()
+
+
 # ---------------------------------------------------------------------------
 # bf16 matrix-core variants of the fp32 path (bar for these: 2e-2)
 # ---------------------------------------------------------------------------
@@ -124,15 +192,16 @@ def test_bf16_mfma_variants_reduced_batch(mode, name, N):
 
 
 @pytest.mark.parametrize("mode", ["bf16x3", "bf16"])
-@pytest.mark.parametrize("name,n_sample", [("c2", 24), ("c5", 48)])
-def test_bf16_mfma_variants_full_size_sampled(mode, name, n_sample):
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+def test_bf16_mfma_variants_full_size_every_point(mode, name):
     code, tol = mfma_modes()[mode]
     w = synth.WORKLOADS[name]
     arrs = w.build()
-    print(f"case {name} full N={w.N} {mode}", flush=True)
+    print(f"case {name} full N={w.N} {mode}, every point", flush=True)
     gu, go, mlp = gpu_run(arrs, w.op, return_mlp=True, mfma=code)
-    idx = np.sort(np.random.default_rng(7).choice(w.N, n_sample, replace=False))
-    check((gu[idx], go[idx]), oracle_run(arrs, w.op, idx=idx), tol, f"{name} full-size sample {mode}")
+    ref = full_size_oracle(name, arrs)
+    check((gu, go), ref, tol, f"{name} full size {mode}")
+    check_every_point((gu, go), ref, tol, GUARD[mode], f"{name} full size {mode}")
     gu2, go2 = gpu_run(arrs, w.op, mlp=mlp)
     assert np.array_equal(gu, gu2) and np.array_equal(go, go2)
     mlp.close()
