@@ -181,7 +181,9 @@ int ctm_biharmonic_rand(const ctm_mlp *mlp, const void *x, long N, const void *V
  *
  * ctm_laplacian_fwd computes the same (u, op) as ctm_laplacian (collapsed order-2 Taylor mode) and records, in
  * the caller's `tape`, what the reverse pass needs: the input coefficient block and, per hidden layer, the
- * pre-activation rows and the output rows.  One pass only: R <= 254.  CTM_F32 and CTM_F64 handles.
+ * pre-activation rows and the output rows.  Any R >= 1: direction sets too large for one tile are split into passes,
+ * each with a tape of its own (ctm_tape_bytes counts them all), and the reverse pass adds the gradients of the passes
+ * in pass order.  CTM_F32 and CTM_F64 handles.
  *   tape    dev, ctm_tape_bytes(mlp, N, R) bytes (0 on invalid arguments), 256-byte aligned
  *
  * ctm_laplacian_bwd takes dL/du and dL/dop of a scalar L and the tape of the matching forward call (same mlp
@@ -213,7 +215,7 @@ int ctm_update_mlp(ctm_mlp *mlp, const void *const *W, const void *const *b, voi
  * The same pair of calls for the randomized biharmonic (Sec. 3.3, Eq. 9; "differentiable" evaluation, Sec. 4):
  * ctm_biharmonic_rand_fwd computes the (u, op) of ctm_biharmonic_rand by collapsed order-4 Taylor mode and
  * records the tape; ctm_biharmonic_rand_bwd runs the reverse of the order-4 rule (it needs the fifth derivative
- * of the activation) and writes dL/dW_l, dL/db_l.  One pass only: S <= 84.  Arguments as in the Laplacian pair;
+ * of the activation) and writes dL/dW_l, dL/db_l.  Any S >= 1 (several passes beyond S = 84, as above).  Arguments as in the Laplacian pair;
  * the scale 1/(3S) is implied.  V must not be NULL.
  */
 size_t ctm_biharmonic_tape_bytes(const ctm_mlp *mlp, long N, int S);
@@ -227,8 +229,8 @@ int ctm_biharmonic_rand_bwd(const ctm_mlp *mlp, long N, int S, const void *tape,
 /*
  * And for the exact biharmonic (Sec. 3.3, Eq. 12; "differentiable" evaluation, Sec. 4): the forward records one
  * order-4 tape per direction family of the interpolation formula, the reverse pass runs once per family and adds
- * the three contributions in a fixed order (u enters through the first).  Every family must fit one pass:
- * D (D - 1) <= 84, i.e. D <= 9 (CTM_ERR_UNSUPPORTED beyond).  Arguments as in the pairs above.
+ * the three contributions in a fixed order (u enters through the first).  Any D: families of more than 84 directions
+ * (D >= 10) run in several passes.  Arguments as in the pairs above.
  */
 size_t ctm_biharmonic_exact_tape_bytes(const ctm_mlp *mlp, long N);
 size_t ctm_biharmonic_exact_backward_workspace_bytes(const ctm_mlp *mlp, long N);

@@ -82,7 +82,7 @@ class _BiharmonicExact(torch.autograd.Function):
 
 
 def biharmonic_exact(mlp, Ws, bs, x):
-    """(u, op) of ctm_biharmonic_exact, differentiable with respect to the tensors in Ws and bs (D <= 9)."""
+    """(u, op) of ctm_biharmonic_exact, differentiable with respect to the tensors in Ws and bs."""
     return _BiharmonicExact.apply(mlp, x, len(Ws), *Ws, *bs)
 
 

@@ -476,16 +476,13 @@ int check_tape_call(const ctm_mlp *m, int K, long N, int R, const char *who) {
     return fail(CTM_ERR_UNSUPPORTED, "%s: the recording forward and the reverse pass are built for CTM_F32 and CTM_F64", who);
   if (N < 1) return fail(CTM_ERR_SHAPE, "%s: N = %ld, need N >= 1", who, N);
   if (R < 1) return fail(CTM_ERR_SHAPE, "%s: %d directions, need at least 1", who, R);
-  if (R > max_dirs_per_pass(K))
-    return fail(CTM_ERR_UNSUPPORTED, "%s: %d directions; the recording forward keeps one pass and takes at most %d", who, R,
-                max_dirs_per_pass(K));
   if (N > (1L << 40) / rows_per_point(K, R)) return fail(CTM_ERR_SHAPE, "%s: N * rows per point overflows", who);
   return CTM_OK;
 }
 
 template <typename T>
 int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
-                 hipStream_t st, bool accumulate_op = false) {
+                 hipStream_t st, bool accumulate_op = false, int r0 = 0) {
   const TapeLayout tl = tape_layout(m, K, N, R);
   const PassPlan pl = plan_pass(K, R, false, N, m->min_col_tiles, m->slots);
   const int L = m->L;
@@ -493,7 +490,7 @@ int run_fwd_tape(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R,
   SeedArgs<T> sa;
   sa.x = x; sa.V = V; sa.out = (T *)(tp + tl.h0); sa.N = N;
   sa.v_sn = sn; sa.v_sr = m->dims[0]; sa.v_sd = 1;
-  sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = 0; sa.standard = 0; sa.R = R;
+  sa.D = m->dims[0]; sa.ld = m->ld[0]; sa.rho = pl.rho; sa.order = K; sa.r0 = r0; sa.standard = 0; sa.R = R;
   if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
   hipError_t e = launch_seed<T>(sa, st);
   if (e != hipSuccess) return fail_hip(e, "seed kernel launch");
@@ -580,6 +577,53 @@ int run_bwd(const ctm_mlp *m, int K, long N, int R, double scale, const void *ta
       (void)prof_mark(st, 1);
       cur ^= 1;
     }
+  }
+  return CTM_OK;
+}
+
+// ---- direction sets that need several passes (more rows per point than one tile holds) ----------------------------
+// The recording forward keeps one tape per pass, back to back; u is the same in every pass and enters through the
+// first one; the operator values and the gradients of the passes add up, always in pass order (bitwise reproducible).
+struct PassTapes {
+  Split sp;
+  std::vector<size_t> off;   // byte offset of each pass's tape
+  size_t total;
+  int dirs(int pass) const { return pass == sp.n_passes - 1 ? sp.lastR : sp.first; }
+};
+PassTapes pass_tapes(const ctm_mlp *m, int K, long N, int R) {
+  PassTapes t;
+  t.sp = split_dirs(K, R);
+  size_t off = 0;
+  for (int p = 0; p < t.sp.n_passes; ++p) {
+    t.off.push_back(off);
+    off += tape_layout(m, K, N, t.dirs(p)).total;
+  }
+  t.total = off;
+  return t;
+}
+
+template <typename T>
+int fwd_tape_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, double scale, T *u, T *op, void *tape,
+                    hipStream_t st, bool accumulate_first) {
+  const PassTapes pt = pass_tapes(m, K, N, R);
+  for (int p = 0; p < pt.sp.n_passes; ++p) {
+    const bool first = !accumulate_first && p == 0;
+    const int rc = run_fwd_tape<T>(m, K, x, N, V, pt.dirs(p), sn, scale, first ? u : nullptr, op, (char *)tape + pt.off[p], st, !first,
+                                   p * pt.sp.first);
+    if (rc != CTM_OK) return rc;
+  }
+  return CTM_OK;
+}
+
+template <typename T>
+int bwd_passes(const ctm_mlp *m, int K, long N, int R, double scale, const void *tape, const T *gu, const T *gop, void *const *gW,
+               void *const *gb, void *ws, hipStream_t st, bool accumulate_first) {
+  const PassTapes pt = pass_tapes(m, K, N, R);
+  for (int p = 0; p < pt.sp.n_passes; ++p) {
+    const bool first = !accumulate_first && p == 0;
+    const int rc = run_bwd<T>(m, K, N, pt.dirs(p), scale, (const char *)tape + pt.off[p], first ? gu : nullptr, gop, gW, gb, ws, st,
+                              first ? 0 : 1);
+    if (rc != CTM_OK) return rc;
   }
   return CTM_OK;
 }
@@ -898,22 +942,22 @@ int ctm_update_mlp(ctm_mlp *m, const void *const *W, const void *const *b, void 
 
 size_t ctm_tape_bytes(const ctm_mlp *m, long N, int R) {
   if (check_tape_call(m, 2, N, R, "ctm_tape_bytes") != CTM_OK) return 0;
-  return tape_layout(m, 2, N, R).total;
+  return pass_tapes(m, 2, N, R).total;
 }
 
 size_t ctm_backward_workspace_bytes(const ctm_mlp *m, long N, int R) {
   if (check_tape_call(m, 2, N, R, "ctm_backward_workspace_bytes") != CTM_OK) return 0;
-  return bwd_layout(m, 2, N, R).total;
+  return bwd_layout(m, 2, N, split_dirs(2, R).first).total;
 }
 
 size_t ctm_biharmonic_tape_bytes(const ctm_mlp *m, long N, int S) {
   if (check_tape_call(m, 4, N, S, "ctm_biharmonic_tape_bytes") != CTM_OK) return 0;
-  return tape_layout(m, 4, N, S).total;
+  return pass_tapes(m, 4, N, S).total;
 }
 
 size_t ctm_biharmonic_backward_workspace_bytes(const ctm_mlp *m, long N, int S) {
   if (check_tape_call(m, 4, N, S, "ctm_biharmonic_backward_workspace_bytes") != CTM_OK) return 0;
-  return bwd_layout(m, 4, N, S).total;
+  return bwd_layout(m, 4, N, split_dirs(4, S).first).total;
 }
 
 }  // extern "C"
@@ -929,7 +973,7 @@ int recording_forward(const char *who, const ctm_mlp *m, int K, const void *x, l
   if (!V && R != m->dims[0]) return fail(CTM_ERR_SHAPE, "%s: V = NULL selects the standard basis, so R must be D = %d (got %d)", who, m->dims[0], R);
   if (v_point_stride != 0 && v_point_stride != (long)R * m->dims[0])
     return fail(CTM_ERR_SHAPE, "%s: v_point_stride = %ld, must be 0 (shared) or R*D = %ld", who, v_point_stride, (long)R * m->dims[0]);
-  const size_t need = tape_layout(m, K, N, R).total;
+  const size_t need = pass_tapes(m, K, N, R).total;
   if (tape_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: tape has %zu bytes, need %zu", who, tape_bytes, need);
   const size_t es = elem_size(m->dtype);
   if (misaligned(tape, 256)) return fail(CTM_ERR_ALIGN, "%s: tape must be 256-byte aligned", who);
@@ -939,8 +983,8 @@ int recording_forward(const char *who, const ctm_mlp *m, int K, const void *x, l
   m->note_tape(tape);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
-    return run_fwd_tape<double>(m, K, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st);
-  return run_fwd_tape<float>(m, K, (const float *)x, N, (const float *)V, R, v_point_stride, scale, (float *)u, (float *)op, tape, st);
+    return fwd_tape_passes<double>(m, K, (const double *)x, N, (const double *)V, R, v_point_stride, scale, (double *)u, (double *)op, tape, st, false);
+  return fwd_tape_passes<float>(m, K, (const float *)x, N, (const float *)V, R, v_point_stride, scale, (float *)u, (float *)op, tape, st, false);
 }
 
 int reverse_pass(const char *who, const ctm_mlp *m, int K, long N, int R, double scale, const void *tape, size_t tape_bytes,
@@ -948,8 +992,8 @@ int reverse_pass(const char *who, const ctm_mlp *m, int K, long N, int R, double
   int rc = check_tape_call(m, K, N, R, who);
   if (rc != CTM_OK) return rc;
   if (!tape || !ws) return fail(CTM_ERR_NULL, "%s: tape or workspace is NULL", who);
-  if (tape_bytes < tape_layout(m, K, N, R).total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than the tape size query says", who);
-  const size_t need = bwd_layout(m, K, N, R).total;
+  if (tape_bytes < pass_tapes(m, K, N, R).total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than the tape size query says", who);
+  const size_t need = bwd_layout(m, K, N, split_dirs(K, R).first).total;
   if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
   const size_t es = elem_size(m->dtype);
   if (misaligned(tape, 256) || misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: tape and workspace must be 256-byte aligned", who);
@@ -962,8 +1006,8 @@ int reverse_pass(const char *who, const ctm_mlp *m, int K, long N, int R, double
     return fail(CTM_ERR_UNSUPPORTED, "%s: the handle's weights were replaced (ctm_update_mlp) after the forward call that recorded this tape", who);
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (m->dtype == CTM_F64)
-    return run_bwd<double>(m, K, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st);
-  return run_bwd<float>(m, K, N, R, scale, tape, (const float *)gu, (const float *)gop, gW, gb, ws, st);
+    return bwd_passes<double>(m, K, N, R, scale, tape, (const double *)gu, (const double *)gop, gW, gb, ws, st, false);
+  return bwd_passes<float>(m, K, N, R, scale, tape, (const float *)gu, (const float *)gop, gW, gb, ws, st, false);
 }
 
 }  // namespace
@@ -1058,11 +1102,23 @@ int exact_tape_layout(const ctm_mlp *m, long N, const char *who, ExactTape *t) {
     if (f.count[fam] > 0x7fffffffL) return fail(CTM_ERR_SHAPE, "%s: D too large", who);
     const int rc = check_tape_call(m, 4, N, (int)f.count[fam], who);
     if (rc != CTM_OK) return rc;
-    off += tape_layout(m, 4, N, (int)f.count[fam]).total;
+    off += pass_tapes(m, 4, N, (int)f.count[fam]).total;
   }
   t->dirs = off;
   t->total = off + round256((size_t)f.rmax * m->dims[0] * elem_size(m->dtype));
   return CTM_OK;
+}
+
+// Reverse-pass workspace of the exact biharmonic: the largest pass of any family.
+size_t exact_bwd_need(const ctm_mlp *m, long N) {
+  const BiharmFamilies f = biharm_families(m->dims[0]);
+  size_t need = 0;
+  for (int fam = 0; fam < 3; ++fam) {
+    if (f.count[fam] == 0) continue;
+    const size_t b = bwd_layout(m, 4, N, split_dirs(4, (int)f.count[fam]).first).total;
+    need = b > need ? b : need;
+  }
+  return need;
 }
 
 }  // namespace
@@ -1077,7 +1133,7 @@ size_t ctm_biharmonic_exact_tape_bytes(const ctm_mlp *m, long N) {
 size_t ctm_biharmonic_exact_backward_workspace_bytes(const ctm_mlp *m, long N) {
   ExactTape t;
   if (exact_tape_layout(m, N, "ctm_biharmonic_exact_backward_workspace_bytes", &t) != CTM_OK) return 0;
-  return bwd_layout(m, 4, N, (int)biharm_families(m->dims[0]).rmax).total;
+  return exact_bwd_need(m, N);
 }
 
 int ctm_biharmonic_exact_fwd(const ctm_mlp *m, const void *x, long N, void *u, void *op, void *tape, size_t tape_bytes,
@@ -1104,13 +1160,13 @@ int ctm_biharmonic_exact_fwd(const ctm_mlp *m, const void *x, long N, void *u, v
     if (m->dtype == CTM_F64) {
       hipError_t e = launch_biharm_dirs<double>((double *)(tp + t.dirs), D, fam, st);
       if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
-      rc = run_fwd_tape<double>(m, 4, (const double *)x, N, (const double *)(tp + t.dirs), (int)f.count[fam], 0, f.weight[fam],
-                                first ? (double *)u : nullptr, (double *)op, tp + t.off[fam], st, !first);
+      rc = fwd_tape_passes<double>(m, 4, (const double *)x, N, (const double *)(tp + t.dirs), (int)f.count[fam], 0, f.weight[fam],
+                                   (double *)u, (double *)op, tp + t.off[fam], st, !first);
     } else {
       hipError_t e = launch_biharm_dirs<float>((float *)(tp + t.dirs), D, fam, st);
       if (e != hipSuccess) return fail_hip(e, "direction kernel launch");
-      rc = run_fwd_tape<float>(m, 4, (const float *)x, N, (const float *)(tp + t.dirs), (int)f.count[fam], 0, f.weight[fam],
-                               first ? (float *)u : nullptr, (float *)op, tp + t.off[fam], st, !first);
+      rc = fwd_tape_passes<float>(m, 4, (const float *)x, N, (const float *)(tp + t.dirs), (int)f.count[fam], 0, f.weight[fam],
+                                  (float *)u, (float *)op, tp + t.off[fam], st, !first);
     }
     if (rc != CTM_OK) return rc;
     first = false;
@@ -1127,7 +1183,7 @@ int ctm_biharmonic_exact_bwd(const ctm_mlp *m, long N, const void *tape, size_t 
   if (!tape || !ws) return fail(CTM_ERR_NULL, "%s: tape or workspace is NULL", who);
   if (tape_bytes < t.total) return fail(CTM_ERR_WORKSPACE, "%s: tape is smaller than ctm_biharmonic_exact_tape_bytes() says", who);
   const BiharmFamilies f = biharm_families(m->dims[0]);
-  const size_t need = bwd_layout(m, 4, N, (int)f.rmax).total;
+  const size_t need = exact_bwd_need(m, N);
   if (ws_bytes < need) return fail(CTM_ERR_WORKSPACE, "%s: workspace has %zu bytes, need %zu", who, ws_bytes, need);
   const size_t es = elem_size(m->dtype);
   if (misaligned(tape, 256) || misaligned(ws, 256)) return fail(CTM_ERR_ALIGN, "%s: tape and workspace must be 256-byte aligned", who);
@@ -1144,11 +1200,11 @@ int ctm_biharmonic_exact_bwd(const ctm_mlp *m, long N, const void *tape, size_t 
   for (int fam = 0; fam < 3; ++fam) {  // the families' contributions add up in this order; u enters through the first only
     if (f.count[fam] == 0) continue;
     if (m->dtype == CTM_F64)
-      rc = run_bwd<double>(m, 4, N, (int)f.count[fam], f.weight[fam], tp + t.off[fam], first ? (const double *)gu : nullptr,
-                           (const double *)gop, gW, gb, ws, st, first ? 0 : 1);
+      rc = bwd_passes<double>(m, 4, N, (int)f.count[fam], f.weight[fam], tp + t.off[fam], (const double *)gu, (const double *)gop, gW,
+                              gb, ws, st, !first);
     else
-      rc = run_bwd<float>(m, 4, N, (int)f.count[fam], f.weight[fam], tp + t.off[fam], first ? (const float *)gu : nullptr,
-                          (const float *)gop, gW, gb, ws, st, first ? 0 : 1);
+      rc = bwd_passes<float>(m, 4, N, (int)f.count[fam], f.weight[fam], tp + t.off[fam], (const float *)gu, (const float *)gop, gW, gb,
+                             ws, st, !first);
     if (rc != CTM_OK) return rc;
     first = false;
   }
