@@ -233,7 +233,7 @@ def main():
     # the elementwise first layer (shared directions) is bound by writing the [N*rho, d_1] block once
     es = 8 if w.dtype == np.float64 else 4
     shared_first = w.directions in ("basis", "sigma") and w.dims[0] <= 64 and w.op != "biharmonic_exact"
-    if shared_first:
+    if shared_first and ms["seed"] > 0:   # (the one-launch path of tiny calls has no separate first-layer kernel)
         first_bytes = (w.N * rho * w.dims[1] + w.N * w.dims[0]) * es
         first_ms = ms["seed"] / args.steps
         roofline["first_layer"] = {"bound": "hbm", "achieved": first_bytes / (first_ms * 1e-3) / 1e9, "peak": 8000.0,

@@ -255,10 +255,42 @@ Layout workspace_layout(const ctm_mlp *m, int K, long N, int Rpass, bool standar
   return lo;
 }
 
+// Calls small enough for the one-launch path: all coefficient rows in one workgroup, blocks and one weight matrix in
+// LDS, a bounded amount of arithmetic, storage-type arithmetic (not the bf16 variants), collapsed mode.
+bool small_call_fits(const ctm_mlp *m, int K, long N, int R) {
+  if (is_bf16(m->dtype) || m->L > kSmallMaxLayers) return false;
+  const long rho = rows_per_point(K, R);
+  if (N > kSmallMaxRows || N * rho > kSmallMaxRows) return false;
+  if (small_call_lds_bytes(m->dims.data(), m->L, N * rho, elem_size(m->dtype)) > kSmallMaxLds) return false;
+  long macs = 0;
+  for (int l = 0; l + 1 < m->L; ++l) macs += N * rho * (long)m->dims[l] * m->dims[l + 1];
+  return macs <= kSmallMaxMacs;
+}
+
+template <typename T>
+int run_small(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, long sr, long sd, double scale, T *u, T *op,
+              hipStream_t st, bool accumulate) {
+  SmallArgs<T> a = {};
+  a.x = x; a.V = V; a.v_sn = sn; a.v_sr = sr; a.v_sd = sd;
+  a.L = m->L; a.N = (int)N; a.R = R; a.rho = (int)rows_per_point(K, R); a.order = K; a.act = (int)m->act; a.C = m->dims[m->L];
+  a.accumulate = accumulate ? 1 : 0; a.scale = scale; a.u = u; a.op = op;
+  for (int l = 0; l < m->L; ++l) {
+    a.W[l] = (const T *)m->Wp[l]; a.b[l] = (const T *)m->bp[l]; a.ld[l] = m->ld[l];
+  }
+  a.pitch = small_call_pitch(m->dims.data(), m->L);
+  for (int l = 0; l <= m->L; ++l) a.dims[l] = m->dims[l];
+  if (prof_mark(st, -1) != hipSuccess) return fail(CTM_ERR_HIP, "profiling event failed");
+  hipError_t e = launch_small_call<T>(a, small_call_lds_bytes(m->dims.data(), m->L, N * a.rho, sizeof(T)), st);
+  if (e != hipSuccess) return fail_hip(e, "one-launch kernel");
+  (void)prof_mark(st, 1);
+  return CTM_OK;
+}
+
 template <typename T>
 int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, long sn, long sr, long sd,
                double scale, T *u, T *op, void *ws, hipStream_t st, bool accumulate_first = false,
                bool standard = false) {
+  if (!standard && small_call_fits(m, K, N, R)) return run_small<T>(m, K, x, N, V, R, sn, sr, sd, scale, u, op, st, accumulate_first);
   const Split sp = split_dirs(K, R, standard);
   const Layout lo = workspace_layout(m, K, N, sp.first, standard);
   T *buf[2] = {reinterpret_cast<T *>(ws), reinterpret_cast<T *>((char *)ws + lo.block_bytes)};

@@ -165,6 +165,29 @@ template <typename T>
 hipError_t launch_sigma_dirs(const T *sigma, long sig_stride, const T *V, long v_stride, T *out, long Nd, int S, int D, int K,
                              hipStream_t s);
 
+// One-workgroup path for tiny calls (ctm_small.hip): the whole call in one launch, coefficients resident in LDS.
+constexpr int kSmallMaxLayers = 8;            // linear layers
+constexpr int kSmallMaxRows = 256;            // N * rho
+constexpr size_t kSmallMaxLds = 64 * 1024;    // two coefficient blocks + all weights
+constexpr long kSmallMaxMacs = 1L << 20;      // multiply-adds of all hidden layers together
+template <typename T> struct SmallArgs {
+  const T *x;                      // [N][D]
+  const T *V;                      // directions (element (n, r, k) at V[n*v_sn + r*v_sr + k*v_sd]) or nullptr (basis)
+  long v_sn, v_sr, v_sd;
+  const T *W[kSmallMaxLayers];     // packed weights of the handle: hidden layers zero-padded [>= ld[l+1]][ld[l]], last [C][ld[L-1]]
+  const T *b[kSmallMaxLayers];     // padded biases; last: [C]
+  int dims[kSmallMaxLayers + 1];
+  int ld[kSmallMaxLayers];         // padded width of dims[l]
+  int L, N, R, rho, order, act, C;
+  int pitch;                       // LDS row pitch of the coefficient blocks (small_call_pitch)
+  int accumulate;                  // 1: op += (u untouched), as in FinalArgs
+  double scale;
+  T *u, *op;                       // [N][C], may be nullptr
+};
+int small_call_pitch(const int *dims, int L);
+size_t small_call_lds_bytes(const int *dims, int L, long rows, size_t elem_size);
+template <typename T> hipError_t launch_small_call(const SmallArgs<T> &a, size_t lds_bytes, hipStream_t s);
+
 template <typename T> struct FinalArgs {
   const T *pair;  // [N][1 + nk][ld] : h_0 and the nk highest-order rows of the last hidden layer
   int nk;         // 1 (collapsed) or R (un-collapsed: summed here)

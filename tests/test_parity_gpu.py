@@ -451,14 +451,15 @@ def test_errors_from_the_library_with_a_live_handle():
     assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 3, 15, p(u), p(op), p(tape), tape.numel() - 1, st) == -5
     assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, None, 3, 15, p(u), p(op), p(tape), tape.numel(), st) == -1
     assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 3, 14, p(u), p(op), p(tape), tape.numel(), st) == -2
-    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 85, 85 * 5, p(u), p(op), p(tape), tape.numel(), st) == -4
+    # 85 directions take two passes and two tapes: the tape of a 3-direction call is too small for them
+    assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 85, 85 * 5, p(u), p(op), p(tape), tape.numel(), st) == -5
     assert L.ctm_biharmonic_rand_fwd(mlp.handle, p(x), 8, p(V), 3, 15, p(u), p(op), p(tape), tape.numel(), st) == 0
     bws = torch.empty(ctm.ctm_biharmonic_backward_workspace_bytes(mlp, 8, 3), dtype=torch.uint8, device=dev)
     assert L.ctm_biharmonic_rand_bwd(mlp.handle, 8, 3, p(tape), tape.numel(), p(u), p(op), None, None, p(bws), bws.numel() - 1, st) == -5
     assert L.ctm_biharmonic_rand_bwd(mlp.handle, 8, 3, p(tape), tape.numel() - 1, p(u), p(op), None, None, p(bws), bws.numel(), st) == -5
     assert L.ctm_biharmonic_rand_bwd(mlp.handle, 8, 3, p(tape), tape.numel(), p(u), p(op), None, None, p(bws), bws.numel(), st) == 0  # no gradient wanted
     assert L.ctm_laplacian_fwd(mlp.handle, p(x), 8, None, 5, 0, 1.0, p(u), p(op), p(tape), 16, st) == -5
-    assert L.ctm_laplacian_fwd(mlp.handle, p(x), 8, None, 300, 0, 1.0, p(u), p(op), p(tape), tape.numel(), st) == -4
+    assert L.ctm_laplacian_fwd(mlp.handle, p(x), 8, None, 300, 0, 1.0, p(u), p(op), p(tape), tape.numel(), st) == -2   # basis needs R = D
     torch.cuda.synchronize()
     # the bf16 variants have no recording forward
     m16 = ctm.ctm_create_mlp([torch.from_numpy(W).to(dev) for W in arrs["Ws"]], None, mfma=ctm.CTM_F32_BF16X3)
@@ -642,6 +643,45 @@ def test_results_do_not_depend_on_the_tile_shape(op_name):
     assert orc.scaled_max_err(u.cpu().numpy()[idx], ru) <= 2e-4
     assert orc.scaled_max_err(op.cpu().numpy()[idx], rop) <= 2e-4
     mlp.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("dims,N,R,per_point,K", [
+    ((5, 16, 16, 1), 8, None, False, 2),       # c1: 56 rows
+    ((5, 16, 16, 1), 36, None, False, 2),      # 252 rows: the largest batch of that network on the one-launch path
+    ((7, 33, 20, 3), 12, 6, True, 2),          # odd widths, three outputs, per-point directions
+    ((4, 24, 24, 24, 1), 9, 5, False, 4),      # order 4, shared directions, 17 rows per point
+    ((3, 40, 1), 30, 2, True, 4),              # one hidden layer, order 4
+])
+def test_one_launch_path_agrees_with_the_tiled_path(dtype, dims, N, R, per_point, K):
+    # calls of at most 256 coefficient rows run in one workgroup with the coefficients resident in LDS; the same points
+    # inside a batch too large for that take the tiled kernels: both must match the oracle, and each other to rounding
+    # (they sum the dot products in different orders)
+    import torch
+    import paper_2505_13644_amd as ctm
+    tol = tol_of(dtype)
+    big = 300
+    arrs = small_case(dims, big, dtype, seed=N + K, R=R, per_point=per_point)
+    op_name = "laplacian" if K == 2 else "biharmonic_rand"
+    rho = ctm.ctm_rows_per_point(K, dims[0] if R is None else R)
+    assert N * rho <= 256 < big * rho
+    sub = split_batch(arrs, 0, N)
+    print(f"case one-launch dims={dims} N={N} R={R} K={K} {np.dtype(dtype).name}", flush=True)
+    if dims[-1] == 1:
+        ref = oracle_run(sub, op_name)
+    else:
+        from oracle import operators as orc
+        fn = orc.laplacian if K == 2 else orc.biharmonic_rand
+        args = (sub["x"], sub["V"], sub["scale"]) if K == 2 else (sub["x"], sub["V"])
+        ref = orc.per_output(fn, sub["Ws"], sub["bs"], *args)
+    small = gpu_run(sub, op_name)
+    tiled = gpu_run(arrs, op_name)
+    check(small, ref, tol, "one launch")
+    check((tiled[0][:N], tiled[1][:N]), ref, tol, "tiled")
+    close = 1e-12 if dtype == np.float64 else 2e-5
+    assert err(small[0], tiled[0][:N]) <= close and err(small[1], tiled[1][:N]) <= close
+    again = gpu_run(sub, op_name)
+    assert np.array_equal(small[0], again[0]) and np.array_equal(small[1], again[1])
 
 
 @pytest.mark.parametrize("gain", [4.0, 8.0])
