@@ -56,14 +56,17 @@ typedef enum {
   CTM_F32 = 1,        /* fp32 storage, fp32 MFMA (the benchmarked path)                     */
   CTM_F32_BF16X3 = 2, /* fp32 storage; GEMMs on the bf16 matrix cores with every operand split
                          into hi + lo bf16 parts (3 MFMAs per product, fp32 accumulate)      */
-  CTM_F32_BF16 = 3    /* fp32 tensors at the boundary; GEMM inputs rounded to bf16 (1 MFMA, fp32 accumulate;
+  CTM_F32_BF16 = 3,   /* fp32 tensors at the boundary; GEMM inputs rounded to bf16 (1 MFMA, fp32 accumulate;
                          the workspace blocks between layers are kept in bf16)                */
+  CTM_DTYPE_RANGE_ = 0x7fffffff /* not a dtype: widens the enum to int, so that an unknown value passed in by a
+                                   caller is an ordinary value the library can refuse (CTM_ERR_DTYPE)           */
 } ctm_dtype;
 
 typedef enum {
   CTM_ACT_TANH = 0,
   CTM_ACT_IDENTITY = 1, /* linear network: every operator is exactly 0 (a test hook)          */
-  CTM_ACT_SIN = 2       /* sin, the elementwise example of the paper's graph-rewrite appendix  */
+  CTM_ACT_SIN = 2,      /* sin, the elementwise example of the paper's graph-rewrite appendix  */
+  CTM_ACT_RANGE_ = 0x7fffffff /* not an activation: widens the enum to int (see CTM_DTYPE_RANGE_)      */
 } ctm_act;
 
 typedef enum {

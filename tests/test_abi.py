@@ -123,3 +123,24 @@ def test_product_package_does_not_touch_the_oracle():
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle\b|oracle[/.](operators|nested_dual)", text, flags=re.M), \
                     f"{f} reaches into the oracle package"
+
+
+def test_plain_c_driver_of_the_abi_compiles_and_passes(tmp_path):
+    # include/ctm.h is a C header: a C11 program that calls every entry point with arguments the host must refuse (the
+    # same program runs under ASan / UBSan through tests/sanitize_host.py)
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "abi_host_driver")
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    subprocess.run([cc, "-std=c11", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "abi_host_driver.c"), "-o", exe, "-L", lib_dir, "-lctm",
+                    f"-Wl,-rpath,{lib_dir}", "-L/opt/rocm/lib", "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    import torch
+    env = dict(os.environ)
+    if not torch.cuda.is_available():
+        env["CTM_DRIVER_NO_GPU"] = "1"
+    r = subprocess.run([exe], env=env, capture_output=True, text=True)
+    assert r.returncode == 0 and "abi host driver: ok" in r.stdout, r.stdout + r.stderr
