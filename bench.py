@@ -35,10 +35,11 @@ def gemm_flops(dims, N, rho, R, per_point_dirs):
     return f
 
 
-def recorded_traffic(name):
+def recorded_traffic(tag):
     """HBM bytes per stacked-GEMM launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
-    workload (counters cannot be read from inside this process); None if there is no such summary."""
-    path = os.path.join(ROOT, "profiles", f"layer_kernel_{name}_hbm_traffic.txt")
+    workload and variant (counters cannot be read from inside this process); None if there is no such summary.
+    tag: the workload name, plus _bf16 / _bf16x3 / _f64 / _backward for the variants."""
+    path = os.path.join(ROOT, "profiles", f"layer_kernel_{tag}_hbm_traffic.txt")
     try:
         with open(path) as fh:
             for line in fh:
@@ -99,6 +100,7 @@ def main():
                     help="standard = the un-collapsed comparison path (1 + K*R rows per point); c1..c5 only")
     ap.add_argument("--backward", action="store_true",
                     help="time forward-with-tape plus the reverse pass to all weights (laplacian and biharmonic_rand workloads, collapsed, native MFMA)")
+    ap.add_argument("--fp64", action="store_true", help="run an fp32 workload with every array widened to fp64 (fp64 MFMA kernels)")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -113,6 +115,11 @@ def main():
 
     w = synth.WORKLOADS[args.workload]
     arrs = w.build()
+    if args.fp64:
+        if args.mfma != "native":
+            sys.exit("bench.py: --fp64 and --mfma exclude each other")
+        wide = lambda v: [a.astype(np.float64) for a in v] if isinstance(v, list) else (v.astype(np.float64) if isinstance(v, np.ndarray) else v)
+        arrs = {k: wide(v) for k, v in arrs.items()}
     dev = torch.device("cuda:0")
     t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
     mfma = {"native": None, "bf16x3": ctm.CTM_F32_BF16X3, "bf16": ctm.CTM_F32_BF16}[args.mfma]
@@ -216,7 +223,7 @@ def main():
     else:
         flops = gemm_flops(w.dims, w.N, rho, R, w.directions in ("rademacher", "gaussian"))
     layer_ms_per_step = (ms["layer"] + (ms["final"] if bwd else 0.0)) / args.steps   # reverse pass: class "final" holds the weight-gradient GEMMs
-    dt = "f64" if w.dtype == np.float64 else "f32"
+    dt = "f64" if (w.dtype == np.float64 or args.fp64) else "f32"
     if args.mfma != "native":
         dt = args.mfma
         # executed matrix-core flops: 3 bf16 MFMAs per product for the split variant
@@ -224,14 +231,16 @@ def main():
     achieved = flops / (layer_ms_per_step * 1e-3) / 1e12
     roofline = {
         "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
-        "frac": achieved / PEAK_TFLOPS[dt], "traffic": recorded_traffic(w.name),
+        "frac": achieved / PEAK_TFLOPS[dt],
+        "traffic": recorded_traffic(w.name + ("" if args.mfma == "native" else "_" + args.mfma) + ("_f64" if args.fp64 else "")
+                                    + ("_backward" if bwd else "") + ("_standard" if std else "")),
         "kernel": "layer_kernel (stacked GEMM + fused jet rule)",
         "flops_per_step": flops, "launches_per_step": launches["layer"] / args.steps,
         "avg_launch_ms": ms["layer"] / max(1, launches["layer"]),
         "stage_ms_per_step": {{"seed": "first_layer_or_seed"}.get(k, k): v / args.steps for k, v in ms.items()},
     }
     # the elementwise first layer (shared directions) is bound by writing the [N*rho, d_1] block once
-    es = 8 if w.dtype == np.float64 else 4
+    es = 8 if dt == "f64" else 4
     shared_first = w.directions in ("basis", "sigma") and w.dims[0] <= 64 and w.op != "biharmonic_exact"
     if shared_first and ms["seed"] > 0:   # (the one-launch path of tiny calls has no separate first-layer kernel)
         first_bytes = (w.N * rho * w.dims[1] + w.N * w.dims[0]) * es
@@ -249,6 +258,8 @@ def main():
                                + (", forward with tape + reverse pass to all weights" if bwd else "")},
         "roofline": roofline,
     }
+    if args.fp64:
+        out["config"]["workload"] += ", arrays widened to fp64"
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(w, arrs, args.cpu_seconds)
     mlp.close()
