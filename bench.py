@@ -6,7 +6,7 @@ the timed region.  Prints one JSON line:
   value / unit        operator evaluations per second (N / time per step), whole job
   roofline            the stacked-GEMM launches of a step: algorithmic flops / their HIP-event-timed duration
                       against the dense MFMA peak of the arithmetic type; `traffic` = HBM bytes per launch from
-                      the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of the workload (null if none)
+                      the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of the workload and variant (profiles/layer_kernel_<tag>.txt; null if none)
   cpu_baseline        the fp64 numpy oracle timed on the host cores for a bounded sample of the same workload
 """
 import argparse
@@ -39,7 +39,7 @@ def recorded_traffic(tag):
     """HBM bytes per stacked-GEMM launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this
     workload and variant (counters cannot be read from inside this process); None if there is no such summary.
     tag: the workload name, plus _bf16 / _bf16x3 / _f64 / _backward for the variants."""
-    path = os.path.join(ROOT, "profiles", f"layer_kernel_{tag}_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"layer_kernel_{tag}.txt")
     try:
         with open(path) as fh:
             for line in fh:
@@ -241,7 +241,9 @@ def main():
     }
     # the elementwise first layer (shared directions) is bound by writing the [N*rho, d_1] block once
     es = 8 if dt == "f64" else 4
-    shared_first = w.directions in ("basis", "sigma") and w.dims[0] <= 64 and w.op != "biharmonic_exact"
+    shared_first = w.directions in ("basis", "sigma") and w.dims[0] <= 64 and w.op != "biharmonic_exact" and not bwd
+    if args.mfma == "bf16":
+        es = 2   # plain-bf16 handles keep the block between the layers as one bf16 plane
     if shared_first and ms["seed"] > 0:   # (the one-launch path of tiny calls has no separate first-layer kernel)
         first_bytes = (w.N * rho * w.dims[1] + w.N * w.dims[0]) * es
         first_ms = ms["seed"] / args.steps
