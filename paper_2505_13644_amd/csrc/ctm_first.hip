@@ -28,7 +28,15 @@ template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
     z = w[a.r0 + r];
   } else {
     const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
-    for (int k = 0; k < a.D; ++k) z += w[k] * v[(long)k * a.v_sd];
+    int k = 0;
+    for (; k + 7 < a.D; k += 8) {   // eight terms' operands in flight at once (the loads are strided and uncached at first); k ascending
+      T wv[8], vv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { wv[i] = w[k + i]; vv[i] = v[(long)(k + i) * a.v_sd]; }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) z += wv[i] * vv[i];
+    }
+    for (; k < a.D; ++k) z += w[k] * v[(long)k * a.v_sd];
   }
   a.Z1[(long)r * a.ld1 + j] = z;
 }
@@ -145,7 +153,8 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
 // (row, feature) than as a stacked GEMM over a seeded block whose higher-order rows are all zero: the layer is then
 // bound by writing its output block, like the shared-direction kernel above.  A workgroup takes kPPPoints points;
 // their x and directions are staged in LDS (zero-padded to 16 inputs) and read back 4 inputs at a time.
-constexpr int kPPPoints = 2;  // measured on the order-4 benchmark workload: 1 -> 26 us, 2 -> 28 us, 4 -> 44 us (too few workgroups)
+constexpr int kPPPoints = 2;  // measured on the order-4 benchmark workload: 1 -> 26 us, 2 -> 28 us, 4 -> 44 us (too few workgroups);
+                              // sharing a point's directions out over four workgroups (each recomputing the moment): 42 us
 constexpr int kPPDmax = 16;
 
 template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer_pp_kernel(const FirstArgs<T> a) {
