@@ -76,9 +76,10 @@ int max_dirs_per_pass(int K, bool standard = false) {
 }
 
 // Pick the row-block count that wastes the fewest MFMA rows (ties: the taller tile).  When that tile
-// shape leaves the GPU under-filled (fewer tiles than resident workgroup slots: small batches), fall
-// back to the shortest tile whose row efficiency is within 7 % of the best and that fills the slots,
-// or to the shortest such tile if none does.  tiles_per_point_block = column tiles of the narrowest layer.
+// shape leaves the GPU under-filled (fewer than `slots` tiles, i.e. fewer than two per compute unit: small
+// batches), fall back to the shortest tile whose row efficiency is within 7 % of the best and that reaches
+// `slots` tiles, or to the shortest such tile if none does.  col_tiles = column tiles of the narrowest layer
+// (one tile shape per pass).
 PassPlan plan_pass(int K, int R, bool standard = false, long N = -1, int col_tiles = 1, int slots = 512) {
   PassPlan best{R, (int)rows_per_point(K, R, standard), 0, 0};
   double best_eff = -1.0;
@@ -211,7 +212,9 @@ struct ctm_mlp {
   void *arena = nullptr;
   std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: [dims[L]][ld] and [dims[L]]
   std::vector<void *> Whi, Wlo;  // bf16 variants: split weights of the hidden layers
-  int slots = 512;               // resident workgroups of the layer kernel: 2 per compute unit
+  int slots = 512;               // under-fill threshold of the tile plan: two tiles per compute unit.  Deliberately below the 3-4
+                                 // workgroups a CU can hold: with 2-3 tiles per CU the most row-efficient tile still measured
+                                 // faster than a shorter one (weighted Laplacian, N = 2048: 5-25 % slower with shorter tiles)
   int min_col_tiles = 1;         // fewest column tiles among the hidden layers
   std::vector<void *> WT;        // l = 1..L-2: W_l transposed, [pad(dims[l])][ld(dims[l+1])], for the reverse pass
   // The reverse pass reads the weights from the handle, so it must find the weights its forward ran with: every
