@@ -287,18 +287,6 @@ int ctm_interpolation_gamma(int I, const int *i, const int *j, long long *num, l
 int ctm_tile_plan(ctm_dtype dtype, int K, int R, int *points_per_tile, int *row_blocks,
                   int *dirs_per_pass, int *n_passes);
 
-/*
- * Benchmark diagnostics.  Between ctm_profile_begin() and ctm_profile_end() every operator
- * call made by the calling thread brackets each kernel it launches with HIP events on the
- * call's stream (this creates events, so it is not for production loops).
- * ctm_profile_end() waits for the last event and returns, per kernel class, the summed
- * event-to-event time in milliseconds and the number of launches:
- *   index 0 seed kernel, 1 stacked GEMM + jet rule (one launch per hidden layer), 2 last layer.
- * Either output pointer may be NULL.
- */
-int ctm_profile_begin(void);
-int ctm_profile_end(double ms[3], long launches[3]);
-
 /* Message for the calling thread's most recent failing call ("" if none). */
 const char *ctm_last_error(void);
 

@@ -1,7 +1,7 @@
 """ctypes binding of libctm.so.  Argument marshalling only: every step of the path
 runs in the library's HIP kernels.  PyTorch supplies device memory and the stream.
 
-The functions carry the names of the C entry points declared in include/ctm.h.
+The functions carry the names of the C entry points declared in include/ctm.h (and include/ctm_bench.h).
 There is no fallback: if the library is missing or a call fails, an exception is raised.
 """
 from __future__ import annotations
@@ -22,7 +22,7 @@ STATUS_NAMES = {
     -5: "CTM_ERR_WORKSPACE", -6: "CTM_ERR_ALIGN", -7: "CTM_ERR_ALLOC", -8: "CTM_ERR_HIP",
 }
 
-# name -> (restype, argtypes); mirrors include/ctm.h
+# name -> (restype, argtypes); mirrors include/ctm.h and include/ctm_bench.h
 SIGNATURES = {
     "ctm_create_mlp": (c_int, [c_int, POINTER(c_int), POINTER(c_void_p), POINTER(c_void_p), c_int, c_int, c_void_p,
                                POINTER(c_void_p)]),

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/ctm.h"
+#include "../../include/ctm_bench.h"
 #include "ctm_internal.h"
 
 using namespace ctm;

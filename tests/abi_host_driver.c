@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include "ctm.h"
+#include "ctm_bench.h"
 
 static int failures = 0;
 #define EXPECT(cond) do { if (!(cond)) { printf("FAILED line %d: %s  [last error: %s]\n", __LINE__, #cond, ctm_last_error()); ++failures; } } while (0)
