@@ -501,6 +501,35 @@ def test_operator_call_can_be_captured_in_a_hip_graph_and_replayed():
     mlp.close()
 
 
+def test_concurrent_calls_on_two_streams_with_their_own_workspaces():
+    # a handle is read-only in operator calls: calls that overlap on two streams with distinct workspaces and outputs
+    # must give the results of the same calls made one after the other
+    import torch
+    import paper_2505_13644_amd as ctm
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    w = synth.WORKLOADS["c3"]
+    arrs = w.build(1500)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    halves = [split_batch(arrs, 0, 700), split_batch(arrs, 700, 1500)]
+    xs = [t(h["x"]) for h in halves]
+    Vs = [t(h["V"]) for h in halves]
+    ref = [ctm.ctm_laplacian(mlp, x, V, arrs["scale"]) for x, V in zip(xs, Vs)]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [(torch.empty_like(r[0]), torch.empty_like(r[1])) for r in ref]
+    wss = [torch.empty(ctm.ctm_workspace_bytes(mlp, 2, x.shape[0], w.R), dtype=torch.uint8, device=dev) for x in xs]
+    print("case two streams, N=700 and N=800", flush=True)
+    for rep in range(3):
+        for i in (0, 1):
+            with torch.cuda.stream(streams[i]):
+                ctm.ctm_laplacian(mlp, xs[i], Vs[i], arrs["scale"], outs[i][0], outs[i][1], wss[i])
+    torch.cuda.synchronize()
+    for i in (0, 1):
+        assert torch.equal(outs[i][0], ref[i][0]) and torch.equal(outs[i][1], ref[i][1])
+    mlp.close()
+
+
 @pytest.mark.parametrize("op_name,N", [("laplacian", 37), ("biharmonic_rand", 23), ("biharmonic_exact", 9)])
 def test_calls_stay_inside_their_buffers(op_name, N):
     # guard words before and after u, op and the workspace must survive a call untouched

@@ -52,3 +52,37 @@ def test_static_scratch_entry_point_matches_the_workspace_entry_point():
     torch.cuda.synchronize()
     assert torch.all(u == 3.0) and torch.all(op == 3.0)
     mlp.close()
+
+
+def test_static_scratch_entry_point_replays_from_a_captured_graph():
+    # the callers it is for: a captured graph holds kernel launches only (no allocation, no memset node); replays with
+    # new inputs between eager work must reproduce the eager results bit for bit
+    import torch
+    import paper_2505_13644_amd as ctm
+
+    dev = torch.device("cuda:0")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    w = synth.WORKLOADS["c3"]
+    N = 64
+    arrs = w.build(N)
+    mlp = ctm.ctm_create_mlp([t(W) for W in arrs["Ws"]], [t(b) for b in arrs["bs"]])
+    x, V = t(arrs["x"]), t(arrs["V"])
+    u, op = torch.empty(N, device=dev), torch.empty(N, device=dev)
+    print("case static entry point under graph capture, N=64", flush=True)
+    ctm.ctm_laplacian_static(mlp, x, V, arrs["scale"], u, op)      # first call on the device: looks up the array's address
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        ctm.ctm_laplacian_static(mlp, x, V, arrs["scale"], u, op)
+    for rep in range(3):
+        x.copy_(t(synth.make_points(N, 50, seed=200 + rep)))
+        u.zero_(); op.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        gu, go = u.cpu().numpy().copy(), op.cpu().numpy().copy()
+        eu, eo = ctm.ctm_laplacian(mlp, x, V, arrs["scale"])        # eager, own workspace
+        torch.cuda.synchronize()
+        assert np.array_equal(gu, eu.cpu().numpy()) and np.array_equal(go, eo.cpu().numpy()), f"replay {rep}"
+        assert np.any(go != 0)
+    del g
+    mlp.close()
