@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libctm.so")
-SOURCES = ["ctm_layer.hip", "ctm_layer_bf16.hip", "ctm_first.hip", "ctm_bwd.hip", "ctm_misc.hip", "ctm_small.hip", "ctm_api.hip"]
+SOURCES = ["ctm_layer.hip", "ctm_layer_bf16.hip", "ctm_layer_bf16_t256.hip", "ctm_first.hip", "ctm_bwd.hip", "ctm_misc.hip", "ctm_small.hip", "ctm_api.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -213,6 +213,7 @@ struct ctm_mlp {
   void *arena = nullptr;
   std::vector<void *> Wp, bp;  // l < L-1: padded matrices; l = L-1: [dims[L]][ld] and [dims[L]]
   std::vector<void *> Whi, Wlo;  // bf16 variants: split weights of the hidden layers
+  int cus = 256;                 // compute units of the handle's device
   int slots = 512;               // under-fill threshold of the tile plan: two tiles per compute unit.  Deliberately below the 3-4
                                  // workgroups a CU can hold: with 2-3 tiles per CU the most row-efficient tile still measured
                                  // faster than a shorter one (weighted Laplacian, N = 2048: 5-25 % slower with shorter tiles)
@@ -355,7 +356,17 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
         if (is_bf16(m->dtype)) {
           la.Whi = m->Whi[l]; la.Wlo = m->Wlo[l];
           la.out_bf16 = last ? 0 : bf16_blocks;
-          e = launch_layer_bf16(la, pl.MB, m->dtype == CTM_F32_BF16X3 ? 3 : 1, st);
+          // plain bf16: 256-column tiles where the layer is wide enough to fill them (at most a fifth of the columns of its
+          // tiles padding) and the batch gives every compute unit at least two of them
+          const long wide_ct = (m->ld[l + 1] + kWideCols - 1) / kWideCols;
+          const bool wide = m->dtype == CTM_F32_BF16 && !standard && bf16_t256_supported(pl.MB, la.wpp) &&
+                            5 * (long)m->ld[l + 1] >= 4 * wide_ct * kWideCols && la.n_row_tiles * wide_ct >= 2L * m->cus;
+          if (wide) {
+            la.n_col_tiles = (int)wide_ct;
+            e = launch_layer_bf16_t256(la, pl.MB, st);
+          } else {
+            e = launch_layer_bf16(la, pl.MB, m->dtype == CTM_F32_BF16X3 ? 3 : 1, st);
+          }
           done = true;
         }
       }
@@ -447,7 +458,8 @@ hipError_t pack_everything(ctm_mlp *m, const void *const *W, const void *const *
   hipError_t e = (m->dtype == CTM_F64) ? pack_all<double>(m, W, b, st) : pack_all<float>(m, W, b, st);
   const int bn = tile_cols_of(m->dtype);
   for (int l = 0; e == hipSuccess && is_bf16(m->dtype) && l + 1 < m->L; ++l)
-    e = launch_pack_bf16((const float *)W[l], m->dims[l + 1], m->dims[l], m->Whi[l], m->Wlo[l], m->col_tiles[l] * bn, m->ld[l], st);
+    e = launch_pack_bf16((const float *)W[l], m->dims[l + 1], m->dims[l], m->Whi[l], m->Wlo[l],
+                         (m->col_tiles[l] * bn + kWideCols - 1) / kWideCols * kWideCols, m->ld[l], st);
   for (int l = 1; e == hipSuccess && l + 1 < m->L; ++l) {
     const int rows_pad = m->col_tiles[l - 1] * bn;
     if (m->dtype == CTM_F64)
@@ -761,11 +773,12 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
     total += round256(rows_pad * m->ld[l] * es);
     boff[l] = total;
     total += round256(rows_pad * es);
-    if (is_bf16(dtype) && !lastl) {
+    if (is_bf16(dtype) && !lastl) {   // the 256-column plain-bf16 kernel reads whole 256-row column tiles
+      const size_t rows_bf = (rows_pad + kWideCols - 1) / kWideCols * kWideCols;
       hoff[l] = total;
-      total += round256(rows_pad * m->ld[l] * 2);
+      total += round256(rows_bf * m->ld[l] * 2);
       loff[l] = total;
-      total += round256(rows_pad * m->ld[l] * 2);
+      total += round256(rows_bf * m->ld[l] * 2);
     }
     if (l >= 1 && !lastl) {  // transposed copy: rows = padded dims[l], k extent = ld of dims[l+1]
       toff[l] = total;
@@ -775,7 +788,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
   hipError_t e = hipGetDevice(&m->device);
   if (e != hipSuccess) { delete m; return fail_hip(e, "ctm_create_mlp: hipGetDevice"); }
   int cus = 0;
-  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device) == hipSuccess && cus > 0) m->slots = 2 * cus;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device) == hipSuccess && cus > 0) { m->slots = 2 * cus; m->cus = cus; }
   m->min_col_tiles = m->col_tiles[0];
   for (int ct : m->col_tiles) m->min_col_tiles = ct < m->min_col_tiles ? ct : m->min_col_tiles;
   e = hipMalloc(&m->arena, total);

@@ -80,6 +80,11 @@ bool row_blocks_supported(int MB);
 // fp32 storage, bf16 matrix cores: nsplit = 3 (hi*hi + hi*lo + lo*hi) or 1 (hi*hi only)
 hipError_t launch_layer_bf16(const LayerArgs<float> &a, int MB, int nsplit, hipStream_t s);
 hipError_t launch_pack_bf16(const float *W, int d_out, int d_in, void *hi, void *lo, int rows_pad, int ld, hipStream_t s);
+// Plain bf16 with 256-column tiles (same tile heights and points per tile as launch_layer_bf16): a.n_col_tiles counts
+// 256-column tiles and Whi must be padded to that many rows.  Collapsed forward only.
+constexpr int kWideCols = 256;
+bool bf16_t256_supported(int MB, int wpp);
+hipError_t launch_layer_bf16_t256(const LayerArgs<float> &a, int MB, hipStream_t s);
 
 template <typename T> struct SeedArgs {
   const T *x;   // [N][D]

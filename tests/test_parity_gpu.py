@@ -207,6 +207,30 @@ def test_bf16_mfma_variants_full_size_every_point(mode, name):
     mlp.close()
 
 
+@pytest.mark.parametrize("dims,N,R,K", [
+    ((6, 256, 448, 1), 4100, 10, 2),     # 12 row blocks (16 points of 12 rows), two column tiles, the second 192 columns wide, ragged batch
+    ((5, 64, 256, 1), 1027, 32, 4),      # order 4: two points of 98 rows per tile, two wavefronts per point, last tile one point
+    ((9, 256, 480, 224, 1), 2050, 16, 2),  # 9 row blocks; 256 -> 480 takes the 256-column tiles, 480 -> 224 the 128-column ones
+])
+def test_plain_bf16_256_column_tiles(dims, N, R, K):
+    # batches that give every compute unit at least two 256-column tiles take the wide plain-bf16 kernel (every tile height
+    # it is built for, both ways of sharing a tile's points among the wavefronts); compared with the oracle on every point
+    import paper_2505_13644_amd as ctm
+    arrs = small_case(dims, N, np.float32, seed=N, R=R, per_point=True)
+    op_name = "laplacian" if K == 2 else "biharmonic_rand"
+    print(f"case bf16 256-column tiles dims={dims} N={N} R={R} K={K}", flush=True)
+    got = gpu_run(arrs, op_name, mfma=ctm.CTM_F32_BF16)
+    ref = oracle_run(arrs, op_name)
+    check(got, ref, 2e-2, f"bf16 wide {dims}")
+    again = gpu_run(arrs, op_name, mfma=ctm.CTM_F32_BF16)
+    assert np.array_equal(got[0], again[0]) and np.array_equal(got[1], again[1])
+    # the same points in a batch too small for the wide tiles take the 128-column kernel: same result up to the order of the k sum
+    sub = split_batch(arrs, 0, 40)
+    small = gpu_run(sub, op_name, mfma=ctm.CTM_F32_BF16)
+    scale = max(np.max(np.abs(ref[1])), 1e-30)
+    assert np.max(np.abs(small[1] - got[1][:40])) <= 2e-2 * scale
+
+
 @pytest.mark.parametrize("mode", ["bf16x3", "bf16"])
 @pytest.mark.parametrize("dims,N,R,per_point", [((7, 33, 65, 1), 19, None, False), ((3, 100, 1), 130, None, False),
                                                 ((4, 48, 48, 48, 1), 33, 21, True), ((6, 24, 16, 1), 21, 300, False)])
