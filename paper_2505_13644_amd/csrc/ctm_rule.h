@@ -161,6 +161,25 @@ __device__ __forceinline__ void jet_rule(const T *c, int CROW, T bias, const Out
         char *rb = out.row_base(1);
         const long bump = 4 * out.step_bytes();
         const T *cr = c + CROW;
+        // eight directions per trip while they last (their LDS reads are in flight together: the rule is bound by LDS
+        // latency where few wavefronts share a SIMD), then four; a group still adds its directions in ascending order
+        for (; i0 + 7 < R; i0 += 8, rb += 2 * bump, cr += 8 * CROW) {
+          T z1[NG], y1[NG];
+#pragma unroll
+          for (int k = 0; k < NG; ++k) z1[k] = cr[(sub + k * WPP) * CROW];
+#pragma unroll
+          for (int k = 0; k < NG; ++k) y1[k] = cr[(4 + sub + k * WPP) * CROW];
+#pragma unroll
+          for (int k = 0; k < NG; ++k) {
+            sg[k] += z1[k] * z1[k];
+            out.store(rb, voff[k], d1 * z1[k]);
+          }
+#pragma unroll
+          for (int k = 0; k < NG; ++k) {
+            sg[k] += y1[k] * y1[k];
+            out.store(rb + bump, voff[k], d1 * y1[k]);
+          }
+        }
         for (; i0 + 3 < R; i0 += 4, rb += bump, cr += 4 * CROW) {
           T z1[NG];
 #pragma unroll
