@@ -204,7 +204,29 @@ template <typename T, int BF> __global__ __launch_bounds__(256) void first_layer
     const T dK = K == 2 ? d2 : act_d4<T>(a.act, t, d1);
     put(0, t);
     T mom = T(0);  // sum_r z1_r^K, the only term of the collapsed row at the first layer
-    for (int r = 0; r < R; ++r) {
+    int r = 0;
+    if (!a.standard && !a.last) {
+      // four directions per trip: their dot products are independent chains of multiply-adds, and their stores go out
+      // together; the moment still adds the directions in ascending order
+      for (; r + 3 < R; r += 4) {
+        T z[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z[i] = dot16(vs + ((long)p * R + r + i) * kPPDmax);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const T z1 = z[i], z1s = z1 * z1;
+          mom += K == 2 ? z1s : z1s * z1s;
+          if (K == 2) {
+            put(1 + r + i, d1 * z1);
+          } else {
+            put(1 + 3 * (r + i), d1 * z1);
+            put(2 + 3 * (r + i), d2 * z1s);
+            put(3 + 3 * (r + i), d3 * z1s * z1);
+          }
+        }
+      }
+    }
+    for (; r < R; ++r) {
       const T z1 = dot16(vs + ((long)p * R + r) * kPPDmax);
       const T z1s = z1 * z1;
       const T zK = K == 2 ? z1s : z1s * z1s;
