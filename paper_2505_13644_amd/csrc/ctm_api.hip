@@ -219,6 +219,7 @@ struct ctm_mlp {
                                  // faster than a shorter one (weighted Laplacian, N = 2048: 5-25 % slower with shorter tiles)
   int min_col_tiles = 1;         // fewest column tiles among the hidden layers
   std::vector<void *> WT;        // l = 1..L-2: W_l transposed, [pad(dims[l])][ld(dims[l+1])], for the reverse pass
+  void *W1T = nullptr;           // W_1 transposed, [ld(dims[0])][ld(dims[1])], for the shared-direction first-layer kernels
   // The reverse pass reads the weights from the handle, so it must find the weights its forward ran with: every
   // ctm_update_mlp bumps `version`, a recording forward notes the version under its tape's address, and the matching
   // reverse pass refuses to run on another version.  (Bounded: the notes are dropped once there are kMaxTapeNotes.)
@@ -317,7 +318,7 @@ int run_passes(const ctm_mlp *m, int K, const T *x, long N, const T *V, int R, l
       // shared directions: the first layer is written directly, without a seed block or a GEMM
       const bool last = (L == 2);
       FirstArgs<T> fa;
-      fa.x = x; fa.V = V; fa.W = (const T *)m->Wp[0]; fa.bias = (const T *)m->bp[0];
+      fa.x = x; fa.V = V; fa.W = (const T *)m->Wp[0]; fa.WT = (const T *)m->W1T; fa.bias = (const T *)m->bp[0]; fa.cus = m->cus;
       fa.Z1 = dirs;
       fa.out = last ? pair : buf[0];
       fa.N = N; fa.v_sn = sn; fa.v_sr = sr; fa.v_sd = sd;
@@ -460,6 +461,12 @@ hipError_t pack_everything(ctm_mlp *m, const void *const *W, const void *const *
   for (int l = 0; e == hipSuccess && is_bf16(m->dtype) && l + 1 < m->L; ++l)
     e = launch_pack_bf16((const float *)W[l], m->dims[l + 1], m->dims[l], m->Whi[l], m->Wlo[l],
                          (m->col_tiles[l] * bn + kWideCols - 1) / kWideCols * kWideCols, m->ld[l], st);
+  if (e == hipSuccess && m->L >= 2) {
+    if (m->dtype == CTM_F64)
+      e = launch_pack<double>((const double *)W[0], nullptr, m->dims[0], m->dims[1], (double *)m->W1T, nullptr, m->ld[0], m->ld[1], st, 1);
+    else
+      e = launch_pack<float>((const float *)W[0], nullptr, m->dims[0], m->dims[1], (float *)m->W1T, nullptr, m->ld[0], m->ld[1], st, 1);
+  }
   for (int l = 1; e == hipSuccess && l + 1 < m->L; ++l) {
     const int rows_pad = m->col_tiles[l - 1] * bn;
     if (m->dtype == CTM_F64)
@@ -785,6 +792,8 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
       total += round256((size_t)((dims[l] + bn - 1) / bn) * bn * pad_ld(dims[l + 1]) * es);
     }
   }
+  const size_t w1t_off = total;  // W_1 transposed, zero-padded to [ld(dims[0])][ld(dims[1])]
+  total += round256((size_t)m->ld[0] * m->ld[1] * es);
   hipError_t e = hipGetDevice(&m->device);
   if (e != hipSuccess) { delete m; return fail_hip(e, "ctm_create_mlp: hipGetDevice"); }
   int cus = 0;
@@ -804,6 +813,7 @@ int ctm_create_mlp(int n_layers, const int *dims, const void *const *W, const vo
     m->Wlo.push_back((char *)m->arena + loff[l]);
     m->WT.push_back((char *)m->arena + toff[l]);
   }
+  m->W1T = (char *)m->arena + w1t_off;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   e = pack_everything(m, W, b, st);
   if (e != hipSuccess) {

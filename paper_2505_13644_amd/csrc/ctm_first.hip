@@ -22,38 +22,42 @@ template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int r = blockIdx.y;
   if (j >= a.ld1) return;
-  const T *w = a.W + (long)j * a.ld0;
+  const T *w = a.WT + j;   // W_1 transposed: consecutive threads read consecutive words
+  const long ws = a.ld1;
   T z = T(0);
   if (a.V == nullptr) {
-    z = w[a.r0 + r];
+    z = w[(a.r0 + r) * ws];
   } else {
     const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
     int k = 0;
-    for (; k + 7 < a.D; k += 8) {   // eight terms' operands in flight at once (the loads are strided and uncached at first); k ascending
+    for (; k + 7 < a.D; k += 8) {   // eight terms' operands in flight at once; k ascending
       T wv[8], vv[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { wv[i] = w[k + i]; vv[i] = v[(long)(k + i) * a.v_sd]; }
+      for (int i = 0; i < 8; ++i) { wv[i] = w[(k + i) * ws]; vv[i] = v[(long)(k + i) * a.v_sd]; }
 #pragma unroll
       for (int i = 0; i < 8; ++i) z += wv[i] * vv[i];
     }
-    for (; k < a.D; ++k) z += w[k] * v[(long)k * a.v_sd];
+    for (; k < a.D; ++k) z += w[k * ws] * v[(long)k * a.v_sd];
   }
   a.Z1[(long)r * a.ld1 + j] = z;
 }
 
-constexpr int kFirstPoints = 16;  // points per workgroup
-constexpr int kFirstDmax = 64;    // input widths up to this are held in registers
+constexpr int kFirstPoints = 16;      // points per workgroup ...
+constexpr int kFirstPointsSmall = 4;  // ... and in batches too small to give every compute unit two such workgroups
+constexpr int kFirstDmax = 64;        // input widths up to this are held in registers
 
 // BF = 0: out holds rows of T; BF = 1: out is written as bf16 (input of the plain-bf16 GEMM kernel).
 // DM: the input width rounded up to 8, 16, 32 or 64 -- the length of the register-resident weight row and of the dot
-// products (a 5-dimensional problem should not pay for 64 inputs).
-template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
-  __shared__ T xs[kFirstPoints][DM];
+// products (a 5-dimensional problem should not pay for 64 inputs).  NP: points per workgroup.
+// A thread's weight row comes from the transposed copy of W_1, so that the threads of a wavefront read consecutive
+// words (from the row-major copy every lane would open a cache line of its own for each of its D words).
+template <typename T, int BF, int DM, int NP> __global__ __launch_bounds__(256) void first_layer_kernel(const FirstArgs<T> a) {
+  __shared__ T xs[NP][DM];
   const int tid = threadIdx.x;
   const int j = blockIdx.x * 256 + tid;
-  const long n0 = (long)blockIdx.y * kFirstPoints;
-  const int np = (int)((a.N - n0) < kFirstPoints ? (a.N - n0) : kFirstPoints);
-  for (int i = tid; i < kFirstPoints * DM; i += 256) {  // unused entries must be zero, not stale
+  const long n0 = (long)blockIdx.y * NP;
+  const int np = (int)((a.N - n0) < NP ? (a.N - n0) : NP);
+  for (int i = tid; i < NP * DM; i += 256) {  // unused entries must be zero, not stale
     const int p = i / DM, k = i % DM;
     xs[p][k] = (p < np && k < a.D) ? a.x[(n0 + p) * a.D + k] : T(0);
   }
@@ -62,12 +66,12 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
 
   T w[DM];
 #pragma unroll
-  for (int k = 0; k < DM; ++k) w[k] = k < a.D ? a.W[(long)j * a.ld0 + k] : T(0);
+  for (int k = 0; k < DM; ++k) w[k] = k < a.D ? a.WT[(long)k * a.ld1 + j] : T(0);
   const T bias = a.bias[j];
 
-  T t[kFirstPoints], d1[kFirstPoints];
+  T t[NP], d1[NP];
 #pragma unroll
-  for (int p = 0; p < kFirstPoints; ++p) {
+  for (int p = 0; p < NP; ++p) {
     t[p] = d1[p] = T(0);
     if (p < np) {   // uniform: a short last chunk (or a tiny batch) skips the activations of absent points
       T z0 = bias;
@@ -89,7 +93,7 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
     }
   };
 #pragma unroll
-  for (int p = 0; p < kFirstPoints; ++p)
+  for (int p = 0; p < NP; ++p)
     if (p < np) put(p * pstep, t[p]);
   T mom = T(0);  // sum_r z1_r^order, the only term of the collapsed row at the first layer
   for (int r = 0; r < a.R; ++r) {
@@ -103,7 +107,7 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
       const long row1 = (K == 2) ? 1 + r : 1 + 4 * r;            // first-order row of direction r
       const long rowK = a.last ? 1 + r : ((K == 2) ? 1 + a.R + r : 4 + 4 * r);
 #pragma unroll
-      for (int p = 0; p < kFirstPoints; ++p)
+      for (int p = 0; p < NP; ++p)
         if (p < np) {
           const T d2 = act_d2<T>(a.act, t[p], d1[p]);
           const T dK = (K == 2) ? d2 : act_d4<T>(a.act, t[p], d1[p]);
@@ -123,13 +127,13 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
     if (a.order == 2) {
       const long orow = (long)(1 + r) * ld;
 #pragma unroll
-      for (int p = 0; p < kFirstPoints; ++p)
+      for (int p = 0; p < NP; ++p)
         if (p < np) put(orow + p * pstep, d1[p] * z1);
     } else {
       const long orow = (long)(1 + 3 * r) * ld;
       const T z1c = z1s * z1;
 #pragma unroll
-      for (int p = 0; p < kFirstPoints; ++p)
+      for (int p = 0; p < NP; ++p)
         if (p < np) {
           const T d2 = act_d2<T>(a.act, t[p], d1[p]), d3 = act_d3<T>(a.act, t[p], d1[p]);
           put(orow + p * pstep, d1[p] * z1);
@@ -141,7 +145,7 @@ template <typename T, int BF, int DM> __global__ __launch_bounds__(256) void fir
   if (a.standard) return;  // no collapsed row
   const long olast = (long)(a.last ? 1 : rho - 1) * ld;
 #pragma unroll
-  for (int p = 0; p < kFirstPoints; ++p)
+  for (int p = 0; p < NP; ++p)
     if (p < np) {
       const T dk = (a.order == 2) ? act_d2<T>(a.act, t[p], d1[p]) : act_d4<T>(a.act, t[p], d1[p]);
       put(olast + p * pstep, dk * mom);
@@ -286,22 +290,23 @@ template <typename T> static hipError_t launch_first_pp(const FirstArgs<T> &a, h
   return hipGetLastError();
 }
 
-template <typename T, int DM> static hipError_t launch_first_dm(const FirstArgs<T> &b, dim3 grid, hipStream_t s) {
+template <typename T, int DM, int NP> static hipError_t launch_first_dm(const FirstArgs<T> &b, dim3 grid, hipStream_t s) {
   if constexpr (std::is_same<T, float>::value) {
     if (b.out_bf16) {
-      hipLaunchKernelGGL((first_layer_kernel<T, 1, DM>), grid, dim3(256), 0, s, b);
+      hipLaunchKernelGGL((first_layer_kernel<T, 1, DM, NP>), grid, dim3(256), 0, s, b);
       return hipGetLastError();
     }
   }
   if (b.out_bf16) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((first_layer_kernel<T, 0, DM>), grid, dim3(256), 0, s, b);
+  hipLaunchKernelGGL((first_layer_kernel<T, 0, DM, NP>), grid, dim3(256), 0, s, b);
   return hipGetLastError();
 }
-template <typename T> static hipError_t launch_first_width(const FirstArgs<T> &b, dim3 grid, hipStream_t s) {
-  if (b.D <= 8) return launch_first_dm<T, 8>(b, grid, s);
-  if (b.D <= 16) return launch_first_dm<T, 16>(b, grid, s);
-  if (b.D <= 32) return launch_first_dm<T, 32>(b, grid, s);
-  return launch_first_dm<T, 64>(b, grid, s);
+template <typename T, int NP> static hipError_t launch_first_width(const FirstArgs<T> &b, dim3 grid, hipStream_t s) {
+  if (b.D > kFirstDmax) return hipErrorInvalidValue;
+  if (b.D <= 8) return launch_first_dm<T, 8, NP>(b, grid, s);
+  if (b.D <= 16) return launch_first_dm<T, 16, NP>(b, grid, s);
+  if (b.D <= 32) return launch_first_dm<T, 32, NP>(b, grid, s);
+  return launch_first_dm<T, 64, NP>(b, grid, s);
 }
 
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s) {
@@ -309,18 +314,24 @@ template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t
   hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256, a.R), dim3(256), 0, s, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const long chunks = (a.N + kFirstPoints - 1) / kFirstPoints;
+  // 16 points per workgroup amortise the weight row best; a batch that gives fewer than two such workgroups per compute
+  // unit is latency-bound instead and takes 4 (sigma-weighted Laplacian, N = 2048: 41 -> 29 us with the transposed reads).
+  // The arithmetic of a (point, feature) pair is the same either way.
+  const long col_blocks = (a.ld1 + 255) / 256;
+  const bool small = ((a.N + kFirstPoints - 1) / kFirstPoints) * col_blocks < 2L * a.cus;
+  const int np = small ? kFirstPointsSmall : kFirstPoints;
+  const long chunks = (a.N + np - 1) / np;
   if (chunks > 65535L * 65535L) return hipErrorInvalidValue;
   // grid.y is limited to 65535: fold larger batches into several launches
   for (long c0 = 0; c0 < chunks; c0 += 65535) {
     const long nc = (chunks - c0) < 65535 ? (chunks - c0) : 65535;
     FirstArgs<T> b = a;
-    b.x = a.x + c0 * kFirstPoints * a.D;
-    b.out_point0 = c0 * kFirstPoints;
-    b.N = a.N - c0 * kFirstPoints;
-    if (b.N > nc * kFirstPoints) b.N = nc * kFirstPoints;
-    const dim3 grid((a.ld1 + 255) / 256, (unsigned)nc);
-    e = launch_first_width<T>(b, grid, s);
+    b.x = a.x + c0 * np * a.D;
+    b.out_point0 = c0 * np;
+    b.N = a.N - c0 * np;
+    if (b.N > nc * np) b.N = nc * np;
+    const dim3 grid((unsigned)col_blocks, (unsigned)nc);
+    e = small ? launch_first_width<T, kFirstPointsSmall>(b, grid, s) : launch_first_width<T, kFirstPoints>(b, grid, s);
     if (e != hipSuccess) return e;
   }
   return hipSuccess;

@@ -107,6 +107,7 @@ template <typename T> struct FirstArgs {
   const T *x;     // [N][D]
   const T *V;     // directions (element (n, r, k) at V[n*v_sn + r*v_sr + k*v_sd]) or nullptr (basis)
   const T *W;     // zero-padded first-layer weights [rows_pad][ld0]
+  const T *WT;    // the same transposed, [ld0][ld1] (shared-direction kernels: consecutive features are consecutive words)
   const T *bias;  // [rows_pad]
   T *Z1;          // scratch [R][ld1]: W_1 v_r
   T *out;         // last == 0: [N * rho][ld1]; last == 1: [N][2][ld1]
@@ -118,6 +119,7 @@ template <typename T> struct FirstArgs {
   int out_rows;   // rows per point in out
   int out_bf16 = 0;      // 0: rows of T; 1: out is written as bf16 (same indexing)
   long out_point0 = 0;   // index of this launch's first point in out (x and N are already offset)
+  int cus = 256;         // compute units of the device (launch shape of small batches)
 };
 constexpr int kMaxOutputs = 1024;  // widest last layer (outputs are produced by a per-point dot-product kernel)
 // 0: none (seed block + stacked GEMM); 1: directions shared by all points; 2: per-point directions with D <= 16
