@@ -145,9 +145,10 @@ void layer_kernel(const LayerArgs<T> a) {
   // ---- global -> LDS by LDS-direct loads (global_load_lds_dwordx4): every lane names its own 16 global bytes and
   // the wave's 1 KiB lands at LDS address M0 + 16 * lane, without passing through registers.  A stage row is 64 bytes
   // (BK elements, unpadded), so one instruction moves a chunk of 16 rows: lane l brings row l/4 of the chunk, and the
-  // row's four 16-byte units are stored XOR-swizzled with bits 2..3 of the row, so that the 16 rows x one unit that 16
-  // lanes of a fragment read touch fall into 16 different 16-byte bank groups (measured neutral: LDS conflicts are
-  // not on this kernel's critical path).  Chunks 0..MB-1 are the A tile, MB..MB+BN/16-1 the
+  // row's four 16-byte units are stored XOR-swizzled with bits 1..2 of the row.  Measured on the fragment reads below
+  // (16-byte reads, lane l: row l % 16, unit l / 16): with this swizzle the bank-conflict counter reads zero and a wave
+  // instruction occupies the LDS for 4 cycles; swizzled with bits 2..3 of the row, or not at all, it took 8 (the hardware
+  // serves 8 rows x 2 units per cycle, not 16 rows x 1).  Neutral for this kernel's time: its LDS is idle 85 % of the cycles.  Chunks 0..MB-1 are the A tile, MB..MB+BN/16-1 the
   // B tile; wave w takes chunks w, w+4, ...  Rows past the tile's last valid row re-read that row: they only feed
   // accumulator rows the epilogue never looks at (MFMA rows do not mix).  The loads are unconditional per wave, so
   // the k loop stays branch-free apart from the uniform chunk-count test.
@@ -165,7 +166,7 @@ void layer_kernel(const LayerArgs<T> a) {
   for (int i = 0; i < NCH; ++i) {
     const int c = wave_u + 4 * i;
     const int rr = lane >> 2;                       // row inside the chunk
-    const int uu = (lane & 3) ^ ((rr >> 2) & 3);    // the unit this lane's LDS slot holds
+    const int uu = (lane & 3) ^ ((rr >> 1) & 3);    // the unit this lane's LDS slot holds
     if (c < MB) {
       const int row = c * 16 + rr;
       const int grow = row < rows_valid ? row : rows_valid - 1;
@@ -208,7 +209,7 @@ void layer_kernel(const LayerArgs<T> a) {
   //     while the last MFMAs of this stage execute.
   static_assert(BK == 4 * KV, "one k-group per stage");
   const int npairs = a.ldin / (2 * BK);  // ldin is a multiple of 32, so the stage count is even
-  const int lgs = lg ^ ((lr >> 2) & 3);  // 16-byte units of a row are stored XOR-swizzled: conflict-free fragment reads
+  const int lgs = lg ^ ((lr >> 1) & 3);  // 16-byte units of a row are stored XOR-swizzled: conflict-free fragment reads
   const T *Ar = As + lr * LROW + lgs * KV;
   const T *Br = Bs + (wave * 16 + lr) * LROW + lgs * KV;  // + nb * 64 rows
   vld bf[2][NB], af[2];

@@ -34,9 +34,11 @@ template <int MB, int NSPLIT> struct TileB {
   static constexpr int AROWS = 2 * MBH * 16;      // LDS rows of the A planes; rows >= 16*MB are never written
   static constexpr int BM = 16 * MB;
   static constexpr int BN = 128, BK = 32;
-  // bf16 elements per LDS row.  Split: 64 B of k + 16 B pad (rows are written from registers).  Plain: 64 B,
-  // unpadded and XOR-swizzled, because the rows arrive by LDS-direct loads (16 rows = 1 KiB per wave instruction).
-  static constexpr int PITCH = NSPLIT == 3 ? BK + 8 : BK;
+  // bf16 elements per LDS row: 64 B, unpadded; the four 16-byte units of a row are XOR-swizzled with bits 1..2 of the row
+  // (conflict-free fragment reads, see layer_kernel).  The plain variant's rows arrive by LDS-direct loads (16 rows = 1 KiB
+  // per wave instruction), the split variant writes them from registers; with its former 80-byte rows every fragment read
+  // took twice the LDS cycles (benchmark layers: 1.77 -> 1.73 ms).
+  static constexpr int PITCH = BK;
   static constexpr int PLANES = NSPLIT == 3 ? 2 : 1;
   static constexpr int A_PLANE = AROWS * PITCH;
   static constexpr int B_PLANE = BN * PITCH;
@@ -115,7 +117,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     int u = tid + i * kThreadsB;
     u = u < TL::BM * UPR ? u : TL::BM * UPR - 1;
     const int row = u / UPR, q = u % UPR;
-    a_off[i] = row * PITCH + q * 8;
+    a_off[i] = row * PITCH + (q ^ ((row >> 1) & 3)) * 8;
     const int grow = row < rows_valid ? row : rows_valid - 1;
     a_src[i] = (long)grow * a.ldin + q * 8;
   }
@@ -125,7 +127,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   for (int i = 0; i < TL::B_LD; ++i) {
     const int u = tid + i * kThreadsB;
     const int row = u / UPR, q = u % UPR;
-    b_off[i] = row * PITCH + q * 8;
+    b_off[i] = row * PITCH + (q ^ ((row >> 1) & 3)) * 8;
     b_src[i] = (long)row * a.ldin + q * 8;
   }
 
@@ -172,7 +174,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   };
 
   // Plain variant: both operands are bf16 in HBM, so a k-block goes straight to LDS by LDS-direct loads
-  // (global_load_lds_dwordx4: lane l of a wave brings row l/4, 16-byte unit (l%4) ^ ((l/4 >> 2) & 3) of a 16-row chunk to
+  // (global_load_lds_dwordx4: lane l of a wave brings row l/4, 16-byte unit (l%4) ^ ((l/4 >> 1) & 3) of a 16-row chunk to
   // LDS address M0 + 16*l).  Chunks 0..MB-1 are the A tile, MB..MB+7 the B tile; wave w takes chunks w, w+4, ...
   constexpr int kChunks = MB + BN / 16;
   constexpr int NCH = (kChunks + 3) / 4;
@@ -183,7 +185,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   for (int i = 0; i < NCH; ++i) {
     const int c = wave_u + 4 * i;
     const int rr = lane >> 2;
-    const int uu = (lane & 3) ^ ((rr >> 2) & 3);
+    const int uu = (lane & 3) ^ ((rr >> 1) & 3);
     if (c < MB) {
       const int row = c * 16 + rr;
       const int grow = row < rows_valid ? row : rows_valid - 1;
@@ -223,7 +225,7 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
   __syncthreads();
-  const int lgs = SPLIT ? lg : (lg ^ ((lr >> 2) & 3));  // plain: swizzled unit (rows lr and 16*m + lr share bits 2..3)
+  const int lgs = lg ^ ((lr >> 1) & 3);  // swizzled unit (rows lr and 16*m + lr share bits 1..2)
 
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = TL::NSTAGE == 2 ? (kt & 1) : 0;

@@ -75,7 +75,7 @@ void layer_kernel_bf16_t256(const LayerArgs<float> a) {
   for (int i = 0; i < NCH; ++i) {
     const int c = wave_u + 4 * i;
     const int rr = lane >> 2;
-    const int uu = (lane & 3) ^ ((rr >> 2) & 3);
+    const int uu = (lane & 3) ^ ((rr >> 1) & 3);
     if (c < MB) {
       const int row = c * 16 + rr;
       const int grow = row < rows_valid ? row : rows_valid - 1;
@@ -112,7 +112,7 @@ void layer_kernel_bf16_t256(const LayerArgs<float> a) {
   issue(0, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  const int lgs = lg ^ ((lr >> 2) & 3);   // swizzled unit (rows lr and 16 m + lr share bits 2..3)
+  const int lgs = lg ^ ((lr >> 1) & 3);   // swizzled unit (rows lr and 16 m + lr share bits 1..2)
 
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = kt & 1;
