@@ -16,7 +16,7 @@ constexpr int kXcdsB = 8;
 // matrix pipe a third of them).  This variant halves the weight bytes and cuts the LDS fragment bytes per MFMA:
 //   * 4 wavefronts side by side own 16 * MB rows x 256 columns; each computes ALL MB row blocks x 4 column blocks
 //     (16 * MB accumulator registers: MB <= 13), so an A fragment feeds four MFMAs and no row block is padded;
-//   * two workgroups per compute unit (59 KiB of stages / 65 KiB of staged C each): one's epilogue runs under the
+//   * two workgroups per compute unit (59 KiB of stages / 55 KiB of staged C each): one's epilogue runs under the
 //     other's main loop, which is bound by loads and leaves the vector ALU and most LDS cycles free;
 //   * the MFMA operands are swapped (D^T = B A^T), so a lane holds four consecutive FEATURES of one coefficient row and
 //     stages them with one 16-byte LDS store (only one wavefront owns the 64 columns of a chunk, and it stages alone).
@@ -24,7 +24,7 @@ constexpr int kXcdsB = 8;
 template <int MB> struct TileT {
   static constexpr int BM = 16 * MB, BN = 256, BK = 32, PITCH = BK;
   static constexpr int A_PLANE = BM * PITCH, B_PLANE = BN * PITCH, STAGE = A_PLANE + B_PLANE;   // bf16 elements
-  static constexpr int CROW = 64 + 16;   // floats; 16-byte stores of the four lane groups of a row land in different banks
+  static constexpr int CROW = 64 + 4;    // floats; measured: the 16-byte staging stores are free of bank conflicts with this pitch (not with 72 or 80)
   static constexpr size_t kStageBytes = 2 * (size_t)STAGE * 2;
   static constexpr size_t kCBytes = (size_t)BM * CROW * 4;
   static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
