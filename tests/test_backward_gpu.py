@@ -115,6 +115,14 @@ def test_only_some_gradients_and_missing_cotangents():
     _, rW2, rb2 = og.laplacian_loss_grads(Ws2, bs2, arrs["x"], arrs["V"], 0.25, np.zeros(21), gop)
     for l in range(3):
         assert rel(gWn[l].cpu().numpy(), rW2[l]) <= 1e-9 and rel(gbn[l].cpu().numpy(), rb2[l]) <= 1e-9
+    # ... and so does every copy of the weights the handle keeps: the plain forward with shared directions reads a
+    # transposed copy of the first layer's
+    from oracle import operators as orc
+    xx = np.random.default_rng(5).random((64, 6))           # 512 coefficient rows: the tiled path, not the one-launch one
+    gu, gl = ctm.ctm_laplacian(mlp, t(xx))                  # standard basis
+    ru, rl = orc.laplacian(Ws2, bs2, xx)
+    torch.cuda.synchronize()
+    assert orc.scaled_max_err(gu.cpu().numpy(), ru) <= 1e-10 and orc.scaled_max_err(gl.cpu().numpy(), rl) <= 1e-10
     mlp.close()
 
 
