@@ -169,6 +169,11 @@ def test_named_workloads_full_size_every_point(name):
     parts = [gpu_run(split_batch(arrs, lo, hi), w.op, mlp=mlp) for lo, hi in ((0, cut), (cut, w.N))]
     assert np.array_equal(np.concatenate([p[0] for p in parts]), gu)
     assert np.array_equal(np.concatenate([p[1] for p in parts]), go)
+    # a cut that keeps the launch shapes of the full batch (16-point workgroups in the first-layer kernel) and ends in a
+    # ragged chunk and a ragged tile
+    big = (3 * w.N) // 4 - 71
+    pu, po = gpu_run(split_batch(arrs, 0, big), w.op, mlp=mlp)
+    assert np.array_equal(pu, gu[:big]) and np.array_equal(po, go[:big])
     mlp.close()
 
 
