@@ -17,28 +17,25 @@
 
 namespace ctm {
 
-// z1[r][j] = sum_k W[j][k] v_r[k].  One thread per (direction, feature).
+// z1[r][j] = sum_k W[j][k] v_r[k] for an explicit direction set V.  One thread per (direction, feature).
+// (For the standard basis z1[r] is row r of the transposed weights and the first-layer kernel reads it there.)
 template <typename T> __global__ void first_dirs_kernel(const FirstArgs<T> a) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int r = blockIdx.y;
   if (j >= a.ld1) return;
   const T *w = a.WT + j;   // W_1 transposed: consecutive threads read consecutive words
   const long ws = a.ld1;
+  const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
   T z = T(0);
-  if (a.V == nullptr) {
-    z = w[(a.r0 + r) * ws];
-  } else {
-    const T *v = a.V + (long)(a.r0 + r) * a.v_sr;
-    int k = 0;
-    for (; k + 7 < a.D; k += 8) {   // eight terms' operands in flight at once; k ascending
-      T wv[8], vv[8];
+  int k = 0;
+  for (; k + 7 < a.D; k += 8) {   // eight terms' operands in flight at once; k ascending
+    T wv[8], vv[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { wv[i] = w[(k + i) * ws]; vv[i] = v[(long)(k + i) * a.v_sd]; }
+    for (int i = 0; i < 8; ++i) { wv[i] = w[(k + i) * ws]; vv[i] = v[(long)(k + i) * a.v_sd]; }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) z += wv[i] * vv[i];
-    }
-    for (; k < a.D; ++k) z += w[k * ws] * v[(long)k * a.v_sd];
+    for (int i = 0; i < 8; ++i) z += wv[i] * vv[i];
   }
+  for (; k < a.D; ++k) z += w[k * ws] * v[(long)k * a.v_sd];
   a.Z1[(long)r * a.ld1 + j] = z;
 }
 
@@ -311,9 +308,16 @@ template <typename T, int NP> static hipError_t launch_first_width(const FirstAr
 
 template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t s) {
   if (a.v_sn != 0) return launch_first_pp<T>(a, s);
-  hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256, a.R), dim3(256), 0, s, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  FirstArgs<T> dirs = a;
+  if (a.V == nullptr) {
+    // standard basis: W_1 e_r is row r of the transposed weights, nothing to compute (the kernel only reads Z1)
+    dirs.Z1 = const_cast<T *>(a.WT) + (long)a.r0 * a.ld1;
+  } else {
+    hipLaunchKernelGGL(first_dirs_kernel<T>, dim3((a.ld1 + 255) / 256, a.R), dim3(256), 0, s, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   // 16 points per workgroup amortise the weight row best; a batch that gives fewer than two such workgroups per compute
   // unit is latency-bound instead and takes 4 (sigma-weighted Laplacian, N = 2048: 41 -> 29 us with the transposed reads).
   // The arithmetic of a (point, feature) pair is the same either way.
@@ -325,7 +329,7 @@ template <typename T> hipError_t launch_first(const FirstArgs<T> &a, hipStream_t
   // grid.y is limited to 65535: fold larger batches into several launches
   for (long c0 = 0; c0 < chunks; c0 += 65535) {
     const long nc = (chunks - c0) < 65535 ? (chunks - c0) : 65535;
-    FirstArgs<T> b = a;
+    FirstArgs<T> b = dirs;
     b.x = a.x + c0 * np * a.D;
     b.out_point0 = c0 * np;
     b.N = a.N - c0 * np;
