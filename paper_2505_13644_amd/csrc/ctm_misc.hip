@@ -156,24 +156,44 @@ template <typename T> __global__ __launch_bounds__(256) void final_kernel(const 
   const T *h0 = a.pair + n * (1 + a.nk) * a.ld;
   for (int c0 = 0; c0 < a.C; c0 += 4) {
     T s0[4] = {T(0), T(0), T(0), T(0)}, sk[4] = {T(0), T(0), T(0), T(0)};
-    for (int k = lane; k < a.ld; k += 64) {
-      const T v0 = h0[k];
-      T hk = T(0);
-      for (int r = 1; r <= a.nk; ++r) hk += h0[(long)r * a.ld + k];  // nk > 1: the sum un-collapsed mode defers to the end
+    const int nc = (a.C - c0) < 4 ? (a.C - c0) : 4;   // outputs of this group (uniform); unused slots stay zero
+    // kU strides of the feature loop at a time: all their loads are issued before the first multiply-add, which are
+    // then taken in ascending k as before (one stride at a time the loop paid a memory round trip per 64 features)
+    constexpr int kU = 4;
+    for (int kb = lane; kb < a.ld; kb += 64 * kU) {
+      T v0[kU], hk[kU], wv[kU][4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int c = (c0 + i < a.C) ? c0 + i : a.C - 1;  // clamped: surplus slots repeat the last output and are dropped
-        const T w = a.w[(long)c * a.ld + k];
-        s0[i] += w * v0;
-        sk[i] += w * hk;
+      for (int q = 0; q < kU; ++q) {
+        const int k = kb + 64 * q;
+        const bool in = k < a.ld;
+        v0[q] = in ? h0[k] : T(0);
+        hk[q] = T(0);
+        if (in)
+          for (int r = 1; r <= a.nk; ++r) hk[q] += h0[(long)r * a.ld + k];  // nk > 1: the sum un-collapsed mode defers to the end
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wv[q][i] = (in && i < nc) ? a.w[(long)(c0 + i) * a.ld + k] : T(0);
+      }
+#pragma unroll
+      for (int q = 0; q < kU; ++q) {
+        if (kb + 64 * q < a.ld) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (i < nc) {
+              s0[i] += wv[q][i] * v0[q];
+              sk[i] += wv[q][i] * hk[q];
+            }
+          }
+        }
       }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      if (i < nc) {
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        s0[i] += __shfl_xor(s0[i], off, 64);
-        sk[i] += __shfl_xor(sk[i], off, 64);
+        for (int off = 32; off >= 1; off >>= 1) {
+          s0[i] += __shfl_xor(s0[i], off, 64);
+          sk[i] += __shfl_xor(sk[i], off, 64);
+        }
       }
     }
     if (lane == 0) {
