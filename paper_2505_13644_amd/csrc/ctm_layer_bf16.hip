@@ -50,11 +50,13 @@ template <int MB, int NSPLIT> struct TileB {
   // three up to MB = 13; its staged C chunk then drops the bank-conflict pad at MB = 13, which is what lets the third fit
   static constexpr int kWgPerCu = (NSPLIT == 1 && MB <= 13) ? 3 : 2;
   static constexpr int CROW = 64 + ((kWgPerCu == 3 && 3 * (size_t)BM * 68 * 4 > 160 * 1024) ? 0 : 4);
-  // The split variant keeps ONE stage in LDS (two barriers per k step) so that two workgroups fit a
-  // CU and cover each other's barriers, conversions and load latency; the plain variant's stage is
-  // half as large and is double-buffered.
+  // The split variant keeps ONE stage of its A planes in LDS (they are split from fp32 registers; two barriers per k
+  // step) so that two workgroups fit a CU and cover each other's barriers, conversions and load latency; its weight
+  // planes are bf16 in memory already and come by LDS-direct loads into a double buffer of their own, one k step ahead.
+  // The plain variant's stage is half as large and is double-buffered as a whole.
   static constexpr int NSTAGE = NSPLIT == 3 ? 1 : 2;
-  static constexpr size_t kStageBytes = NSTAGE * (size_t)STAGE * 2;
+  static constexpr int B_BUF = PLANES * B_PLANE;   // split: one buffer of the weight planes [hi][lo]
+  static constexpr size_t kStageBytes = NSPLIT == 3 ? ((size_t)PLANES * A_PLANE + 2 * (size_t)B_BUF) * 2 : NSTAGE * (size_t)STAGE * 2;
   static constexpr size_t kCBytes = (size_t)BM * CROW * 4;
   // behind them: the group sums that wavefronts sharing a point exchange (2 point slots x 4 groups x 64 columns)
   static constexpr size_t kRedOffset = ((kStageBytes > kCBytes ? kStageBytes : kCBytes) + 15) / 16 * 16;
@@ -121,19 +123,8 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     const int grow = row < rows_valid ? row : rows_valid - 1;
     a_src[i] = (long)grow * a.ldin + q * 8;
   }
-  int b_off[TL::B_LD];
-  long b_src[TL::B_LD];
-#pragma unroll
-  for (int i = 0; i < TL::B_LD; ++i) {
-    const int u = tid + i * kThreadsB;
-    const int row = u / UPR, q = u % UPR;
-    b_off[i] = row * PITCH + (q ^ ((row >> 1) & 3)) * 8;
-    b_src[i] = (long)row * a.ldin + q * 8;
-  }
-
   f32x4 ga[SPLIT ? TL::A_LD : 1][2];
   bf16x8 gah[SPLIT ? 1 : TL::A_LD];
-  bf16x8 gbh[TL::B_LD], gbl[TL::B_LD];
   auto load_global = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < TL::A_LD; ++i) {
@@ -144,17 +135,10 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
         gah[i] = *reinterpret_cast<const bf16x8 *>(Ah_g + a_src[i] + k0);
       }
     }
-#pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) {
-      gbh[i] = *reinterpret_cast<const bf16x8 *>(Bhi + b_src[i] + k0);
-      if (SPLIT) gbl[i] = *reinterpret_cast<const bf16x8 *>(Blo + b_src[i] + k0);
-    }
   };
-  // stage layout: [A hi][A lo][B hi][B lo] (lo planes only when SPLIT)
-  auto store_lds = [&](int stage) {
-    __bf16 *S = lds + stage * TL::STAGE;
-    __bf16 *Ah = S, *Al = S + TL::A_PLANE;
-    __bf16 *Bh = S + TL::PLANES * TL::A_PLANE, *Bl = Bh + TL::B_PLANE;
+  // split layout: [A hi][A lo] then two weight buffers [B hi][B lo]; the A planes are written here, from registers
+  auto store_lds = [&]() {
+    __bf16 *Ah = lds, *Al = lds + TL::A_PLANE;
 #pragma unroll
     for (int i = 0; i < TL::A_LD; ++i) {
       if constexpr (SPLIT) {
@@ -165,11 +149,6 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
       } else {
         *reinterpret_cast<bf16x8 *>(Ah + a_off[i]) = gah[i];
       }
-    }
-#pragma unroll
-    for (int i = 0; i < TL::B_LD; ++i) {
-      *reinterpret_cast<bf16x8 *>(Bh + b_off[i]) = gbh[i];
-      if (SPLIT) *reinterpret_cast<bf16x8 *>(Bl + b_off[i]) = gbl[i];
     }
   };
 
@@ -210,6 +189,22 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     }
   };
 
+  // Split variant: the weight planes the same way into their own double buffer.  16 chunks of 16 rows (8 of the hi plane,
+  // then 8 of the lo plane); wave w takes chunks w, w + 4, w + 8, w + 12.  Address = uniform plane base + per-lane offset.
+  constexpr int kBChunks = 2 * BN / 16;
+  auto issue_b = [&](int buf, int k0) {
+    const int rr = lane >> 2;
+    const unsigned voff = (unsigned)(((long)rr * a.ldin + ((lane & 3) ^ ((rr >> 1) & 3)) * 8) * 2);   // < 2^32: 16 rows of ldin
+#pragma unroll
+    for (int i = 0; i < kBChunks / 4; ++i) {
+      const int c = wave_u + 4 * i;                 // uniform
+      const int plane = c / (BN / 16), cb = c % (BN / 16);
+      const __bf16 *g = (plane ? Blo : Bhi) + (long)cb * 16 * a.ldin + k0;
+      const unsigned off = lds_base + (unsigned)((TL::PLANES * TL::A_PLANE + buf * TL::B_BUF + plane * TL::B_PLANE + cb * 16 * PITCH) * 2);
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2" : : "v"(voff), "s"(off), "s"(g) : "memory");
+    }
+  };
+
   f32x4 acc[MBH][4];
 #pragma unroll
   for (int m = 0; m < MBH; ++m)
@@ -218,8 +213,10 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
 
   const int nk = a.ldin / BK;
   if constexpr (SPLIT) {
+    issue_b(0, 0);
     load_global(0);
-    store_lds(0);
+    store_lds();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   } else {
     issue(0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -230,13 +227,19 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
   for (int kt = 0; kt < nk; ++kt) {
     const int stage = TL::NSTAGE == 2 ? (kt & 1) : 0;
     const int k_next = (kt + 1 < nk) ? (kt + 1) * BK : kt * BK;   // last stage re-fetches itself (unused)
-    if constexpr (SPLIT) load_global(k_next);
-    else issue(stage ^ 1, k_next);   // every wave finished reading that stage before the previous barrier
+    if constexpr (SPLIT) {
+      // weights of the next k step into the other weight buffer (every wave finished reading it before the previous
+      // barrier), issued ahead of the fp32 loads so that the compiler's waits for those also cover these
+      issue_b((kt & 1) ^ 1, k_next);
+      load_global(k_next);
+    } else {
+      issue(stage ^ 1, k_next);   // every wave finished reading that stage before the previous barrier
+    }
 
-    const __bf16 *S = lds + stage * TL::STAGE;
+    const __bf16 *S = lds + stage * TL::STAGE;   // split: stage == 0, the single A stage
     const __bf16 *Ah = S + (wr * MBH * 16 + lr) * PITCH + lgs * 8;
     const __bf16 *Al = Ah + TL::A_PLANE;
-    const __bf16 *Bh = S + TL::PLANES * TL::A_PLANE + (wc * 64 + lr) * PITCH + lgs * 8;
+    const __bf16 *Bh = (SPLIT ? lds + TL::PLANES * TL::A_PLANE + (kt & 1) * TL::B_BUF : S + TL::PLANES * TL::A_PLANE) + (wc * 64 + lr) * PITCH + lgs * 8;
     const __bf16 *Bl = Bh + TL::B_PLANE;
     bf16x8 bh[4], bl[4];
 #pragma unroll
@@ -266,11 +269,10 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
     }
 
     if constexpr (SPLIT) {
-      __syncthreads();        // every wave finished reading the only stage
-      store_lds(0);
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of the next stage has landed
+      __syncthreads();        // every wave finished reading the A stage
+      store_lds();
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of the next stage (split: of the next weights) has landed
     __syncthreads();
   }
 
