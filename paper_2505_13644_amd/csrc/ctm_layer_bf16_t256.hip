@@ -159,7 +159,7 @@ void layer_kernel_bf16_t256(const LayerArgs<float> a) {
       if (a.out_bf16)
         jet_rule<float, Bf16Rows, WPP, false>(c, CROW, bias, Bf16Rows{reinterpret_cast<__bf16 *>(a.Hout) + o_off, a.ldout, (unsigned)(j * 2)}, a, active, sub, red);
       else
-        jet_rule<float, PlainRows<float>, WPP, false>(c, CROW, bias, PlainRows<float>{a.Hout + o_off, a.ldout, (unsigned)(j * 4)}, a, active, sub, red);
+        jet_rule<float, StreamRows<float>, WPP, false>(c, CROW, bias, StreamRows<float>{{a.Hout + o_off, a.ldout, (unsigned)(j * 4)}}, a, active, sub, red);
     };
     if constexpr (WPP == 1) {  // a wavefront per point
       if (col_ok)
