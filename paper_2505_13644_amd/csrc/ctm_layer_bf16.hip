@@ -306,9 +306,35 @@ void layer_kernel_bf16(const LayerArgs<float> a) {
         jet_rule<float, StreamRows<float>, WPP>(c, CROW, bias, StreamRows<float>{{a.Hout + o_off, a.ldout, (unsigned)(j * 4)}}, a, active, sub, red);
     };
     if constexpr (WPP == 1) {  // a wavefront per point
-      if (col_ok)
+      if (!a.last) {
+        // every row of every point goes out: the rule overwrites the chunk in place, and the finished chunk leaves with
+        // 16-byte stores (a quarter / an eighth of the store instructions of one element per lane and row)
+        if (col_ok)
+          for (int p = wave_u; p < p_valid; p += kThreadsB / 64)
+            jet_rule<float, LdsRows<float>, 1>(Cs + p * rho * CROW + j, CROW, bias, LdsRows<float>{Cs + p * rho * CROW, CROW, (unsigned)(j * 4)}, a);
+        __syncthreads();
+        const long jg0 = (long)col_tile * BN + chunk * 64;
+        const long orow0 = p0 * rho;   // rows per point in the output block = rho (not the last hidden layer)
+        if (a.out_bf16) {
+          const int q = tid & 7;       // 8 lanes x 8 features per row
+          if (jg0 + q * 8 < a.ldout)
+            for (int r = tid >> 3; r < rows_valid; r += kThreadsB / 8) {
+              const f32x4 x0 = *reinterpret_cast<const f32x4 *>(Cs + r * CROW + q * 8), x1 = *reinterpret_cast<const f32x4 *>(Cs + r * CROW + q * 8 + 4);
+              bf16x8 v;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) { v[i] = (__bf16)x0[i]; v[4 + i] = (__bf16)x1[i]; }
+              __builtin_nontemporal_store(v, reinterpret_cast<bf16x8 *>(reinterpret_cast<__bf16 *>(a.Hout) + (orow0 + r) * a.ldout + jg0 + q * 8));
+            }
+        } else {
+          const int q = tid & 15;      // 16 lanes x 4 features per row
+          if (jg0 + q * 4 < a.ldout)
+            for (int r = tid >> 4; r < rows_valid; r += kThreadsB / 16)
+              __builtin_nontemporal_store(*reinterpret_cast<const f32x4 *>(Cs + r * CROW + q * 4), reinterpret_cast<f32x4 *>(a.Hout + (orow0 + r) * a.ldout + jg0 + q * 4));
+        }
+      } else if (col_ok) {
         for (int p = wave_u; p < p_valid; p += kThreadsB / 64)
           rule(Cs + p * rho * CROW + j, p0 + p, true, 0, nullptr);
+      }
     } else {  // one or two points per tile: 4 or 2 wavefronts share a point's directions (see jet_rule)
       const int p = WPP == 2 ? (wave_u >> 1) : 0;
       const int sub = WPP == 2 ? (wave_u & 1) : wave_u;

@@ -77,6 +77,18 @@ template <typename T> struct StreamRows : PlainRows<T> {
     __builtin_nontemporal_store(v, reinterpret_cast<T *>(base + voff));
   }
 };
+// Rows written back into the staged chunk in LDS, in place of the pre-activations they were computed from (the rule reads
+// a row before it writes it; one thread owns a (point, feature) column, so this is only for a wavefront per point).  The
+// caller then copies the finished chunk to global memory with 16-byte stores.
+template <typename T> struct LdsRows {
+  T *o;         // the point's first row in the chunk
+  long step;    // row pitch of the chunk, elements
+  mutable unsigned lane_bytes = 0;
+  __device__ __forceinline__ void put(long row, T v) const { store(row_base(row), lane_bytes, v); }
+  __device__ __forceinline__ char *row_base(long row) const { return reinterpret_cast<char *>(o + row * step); }
+  __device__ __forceinline__ long step_bytes() const { return step * (long)sizeof(T); }
+  __device__ __forceinline__ void store(char *base, unsigned &voff, T v) const { *reinterpret_cast<T *>(base + voff) = v; }
+};
 struct Bf16Rows {  // rows of bf16 (the block between the layers of a plain-bf16 handle)
   __bf16 *o;
   long step;
